@@ -1,0 +1,199 @@
+"""ctypes binding of libmustdrop.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+F32, BF16 = 0, 1
+FILTER_BUDGET, FILTER_THRESHOLD = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmustdrop.so")
+_lib = None
+
+EXPORTS = [
+    "mustdrop_last_error", "mustdrop_version",
+    "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge",
+    "mustdrop_prefill_filter_workspace_bytes", "mustdrop_prefill_filter",
+    "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append",
+]
+
+
+class MustDropError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"mustdrop error {code}: {message}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def library() -> C.CDLL:
+    """Loads the HIP library built in-tree (python -m paper_2411_10803_amd.build).  No fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2411_10803_amd.build` "
+                              "(there is no CPU fallback)")
+        lib = C.CDLL(_LIB_PATH)
+        lib.mustdrop_last_error.restype = C.c_char_p
+        lib.mustdrop_version.restype = C.c_int
+        for n in ("mustdrop_encode_merge_workspace_bytes", "mustdrop_prefill_filter_workspace_bytes",
+                  "mustdrop_decode_evict_workspace_bytes"):
+            getattr(lib, n).restype = C.c_size_t
+        for n in ("mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append"):
+            getattr(lib, n).restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise MustDropError(rc, library().mustdrop_last_error().decode())
+
+
+def _ptr(t) -> C.c_void_p:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return C.c_void_p(0)
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    assert t.is_contiguous(), "tensors handed to the C ABI must be contiguous"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None) -> C.c_void_p:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _workspace(nbytes: int, device):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def encode_workspace(B, T, Hg, Wg, Hc, kt, kh, kw, device="cuda"):
+    n = library().mustdrop_encode_merge_workspace_bytes(B, T, Hg, Wg, Hc, kt, kh, kw)
+    return _workspace(n, device)
+
+
+def prefill_workspace(B, Mv, N, H, Rcap, device="cuda"):
+    n = library().mustdrop_prefill_filter_workspace_bytes(B, Mv, N, H, Rcap)
+    return _workspace(n, device)
+
+
+def decode_workspace(B, Lcap, H, device="cuda"):
+    n = library().mustdrop_decode_evict_workspace_bytes(B, Lcap, H)
+    return _workspace(n, device)
+
+
+def mustdrop_encode_merge(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget,
+                          out: Optional[Dict] = None, workspace=None, stream=None, want_scores=True) -> Dict:
+    """Sec. 3.3.  x [B, M, D] (f32 / bf16); q_cls [B, Hc, dc]; k_cls [B, 1+M, Hc, dc]; returns the output tensors."""
+    import torch
+    B, M, D = x.shape
+    dev = x.device
+    if key_budget > 0:
+        Hc, dc = q_cls.shape[1], q_cls.shape[2]
+        qk_dtype = _dtype_code(q_cls)
+    else:
+        Hc, dc, qk_dtype = 1, D, _dtype_code(x)
+    W = M // (kt * kh * kw)
+    if out is None:
+        out = {
+            "out_x": torch.zeros_like(x),
+            "out_index": torch.full((B, M), -1, dtype=torch.int32, device=dev),
+            "out_mass": torch.zeros((B, M), dtype=torch.float32, device=dev),
+            "out_is_key": torch.zeros((B, M), dtype=torch.uint8, device=dev),
+            "out_valid": torch.zeros((B, M), dtype=torch.uint8, device=dev),
+            "out_count": torch.zeros((B,), dtype=torch.int32, device=dev),
+            "key_index": torch.full((B, max(key_budget, 1)), -1, dtype=torch.int32, device=dev),
+            "a_cls": torch.zeros((B, M), dtype=torch.float32, device=dev) if want_scores else None,
+            "window_sim": torch.zeros((B, max(W, 1)), dtype=torch.float32, device=dev) if want_scores else None,
+        }
+    if workspace is None:
+        workspace = encode_workspace(B, T, Hg, Wg, Hc, kt, kh, kw, dev)
+    out["workspace"] = workspace
+    _check(library().mustdrop_encode_merge(
+        _ptr(x), C.c_int(_dtype_code(x)), _ptr(q_cls), _ptr(k_cls), C.c_int(qk_dtype), _ptr(mass_in), _ptr(valid),
+        C.c_int(B), C.c_int(T), C.c_int(Hg), C.c_int(Wg), C.c_int(D), C.c_int(Hc), C.c_int(dc),
+        C.c_int(kt), C.c_int(kh), C.c_int(kw), C.c_float(tau), C.c_int(key_budget),
+        _ptr(out["out_x"]), _ptr(out["out_index"]), _ptr(out["out_mass"]), _ptr(out["out_is_key"]),
+        _ptr(out["out_valid"]), _ptr(out["out_count"]), _ptr(out["key_index"]),
+        _ptr(out.get("a_cls")), _ptr(out.get("window_sim")),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return out
+
+
+def mustdrop_prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_scale, mode, budget,
+                            gamma, alpha, Rcap=None, out: Optional[Dict] = None, workspace=None, stream=None,
+                            want_scores=True) -> Dict:
+    """Sec. 3.4.  q_txt [B,N,H,d]; k, v [B,L,H,d]; hidden [B,L,C] (bf16)."""
+    import torch
+    B, N, H, d = q_txt.shape
+    Cdim = hidden.shape[2]
+    dev = q_txt.device
+    if Rcap is None:
+        Rcap = budget if mode == FILTER_BUDGET else Mv
+    if out is None:
+        out = {
+            "hidden_out": torch.zeros((B, Rcap + N, Cdim), dtype=hidden.dtype, device=dev),
+            "k_out": torch.zeros((B, Rcap + N, H, d), dtype=k.dtype, device=dev),
+            "v_out": torch.zeros((B, Rcap + N, H, d), dtype=v.dtype, device=dev),
+            "kept_index": torch.full((B, Rcap), -1, dtype=torch.int32, device=dev),
+            "kept_count": torch.zeros((B,), dtype=torch.int32, device=dev),
+            "out_len": torch.zeros((B,), dtype=torch.int32, device=dev),
+            "out_protect": torch.zeros((B, Rcap + N), dtype=torch.uint8, device=dev),
+            "score_global": torch.zeros((B, Mv), dtype=torch.float32, device=dev) if want_scores else None,
+            "score_indiv": torch.zeros((B, Mv), dtype=torch.float32, device=dev) if want_scores else None,
+        }
+    if workspace is None:
+        workspace = prefill_workspace(B, Mv, N, H, Rcap, dev)
+    out["workspace"] = workspace
+    _check(library().mustdrop_prefill_filter(
+        _ptr(q_txt), _ptr(k), _ptr(v), _ptr(hidden), _ptr(vis_valid), _ptr(txt_len), _ptr(is_key),
+        C.c_int(B), C.c_int(Mv), C.c_int(N), C.c_int(H), C.c_int(d), C.c_int(Cdim),
+        C.c_float(softmax_scale), C.c_int(mode), C.c_int(budget), C.c_float(gamma), C.c_float(alpha),
+        C.c_int(Rcap),
+        _ptr(out["hidden_out"]), _ptr(out["k_out"]), _ptr(out["v_out"]),
+        _ptr(out["kept_index"]), _ptr(out["kept_count"]), _ptr(out.get("out_len")), _ptr(out.get("out_protect")),
+        _ptr(out.get("score_global")), _ptr(out.get("score_indiv")),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return out
+
+
+def mustdrop_decode_evict(q, k_cache, v_cache, acc, ids, protect, length, softmax_scale, decay, budget,
+                          evicted_ids=None, evicted_count=None, workspace=None, stream=None):
+    """Sec. 3.5, one decode step; the cache state is updated in place.  Returns the workspace used."""
+    B, Lcap, H, d = k_cache.shape
+    if workspace is None:
+        workspace = decode_workspace(B, Lcap, H, k_cache.device)
+    _check(library().mustdrop_decode_evict(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
+        C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d),
+        C.c_float(softmax_scale), C.c_float(decay), C.c_int(budget),
+        _ptr(evicted_ids), _ptr(evicted_count),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return workspace
+
+
+def mustdrop_decode_append(k_new, v_new, k_cache, v_cache, acc, ids, protect, length, new_id, protect_new=1,
+                           stream=None):
+    """Eq. 3: appends one entry per sample at slot len[b] (device-side, asynchronous)."""
+    B, Lcap, H, d = k_cache.shape
+    _check(library().mustdrop_decode_append(
+        _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
+        C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d), C.c_int(int(new_id)), C.c_int(int(protect_new)),
+        _stream(stream)))

@@ -1,0 +1,338 @@
+// Stage 3 -- decode (Sec. 3.5): score the KV cache against the query of the token being generated
+// (attention of Eq. 4), keep a running score per entry, evict down to a budget and compact the
+// cache by hole filling.
+//
+//   decode_logits_kernel  one wave per cache entry at a time: an entry's K row (H heads x d, all
+//                         contiguous) is read once with 16-byte loads, 16 lanes per head slice;
+//                         segmented butterflies give the H logits.  Pure streaming: a GEMV at about
+//                         1 flop per byte, so plain ALUs, not MFMA.
+//   decode_select_kernel  one block per sample: softmax statistics per head, head mean, running
+//                         score update, radix top-k among unprotected entries, hole/mover lists,
+//                         moves of the small per-entry arrays
+//   decode_move_kernel    copies the K and V rows of the movers into the holes
+#include "md_device.hpp"
+#include "md_host.hpp"
+
+namespace md {
+namespace {
+
+constexpr float kLog2eD = 1.4426950408889634f;
+
+struct DecodeDims { int B, Lcap, H, d; };
+
+// logits[b][j][h] = scale * q[b][h] . k[b][j][h]      (token-major so an entry's H logits are contiguous)
+// LPH = lanes per head slice = d / 8.
+template <int LPH>
+__global__ __launch_bounds__(256) void decode_logits_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
+    DecodeDims p, float scale, int tokens_per_block, float* __restrict__ logits)
+{
+    const int lane = lane_id(), wv = wave_id();
+    const int b = blockIdx.y;
+    const int n = min(len[b], p.Lcap);
+    const int t0 = blockIdx.x * tokens_per_block;
+    if (t0 >= n) return;
+    const int t1 = min(t0 + tokens_per_block, n);
+    const int row = p.H * p.d;                      // elements per entry
+    const int nvec = row / 8;                       // 16-byte vectors per entry
+    const int iters = (nvec + kWave - 1) / kWave;
+    const uint16_t* qb = q + (long)b * row;
+    const uint16_t* kb = k_cache + (long)b * p.Lcap * row;
+    float* lb = logits + (long)b * p.Lcap * p.H;
+
+    for (int it = 0; it < iters; ++it) {
+        const int idx = it * kWave + lane;
+        float qv[8];
+        if (idx < nvec) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(qb + idx * 8);
+            qv[0] = bf16_lo(w.x); qv[1] = bf16_hi(w.x); qv[2] = bf16_lo(w.y); qv[3] = bf16_hi(w.y);
+            qv[4] = bf16_lo(w.z); qv[5] = bf16_hi(w.z); qv[6] = bf16_lo(w.w); qv[7] = bf16_hi(w.w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[e] = 0.f;
+        }
+        const int head = idx / LPH;
+        for (int j = t0 + wv; j < t1; j += 4) {
+            float part = 0.f;
+            if (idx < nvec) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(kb + (long)j * row + idx * 8);
+                part = qv[0] * bf16_lo(w.x);
+                part = fmaf(qv[1], bf16_hi(w.x), part);
+                part = fmaf(qv[2], bf16_lo(w.y), part);
+                part = fmaf(qv[3], bf16_hi(w.y), part);
+                part = fmaf(qv[4], bf16_lo(w.z), part);
+                part = fmaf(qv[5], bf16_hi(w.z), part);
+                part = fmaf(qv[6], bf16_lo(w.w), part);
+                part = fmaf(qv[7], bf16_hi(w.w), part);
+            }
+#pragma unroll
+            for (int m = 1; m < LPH; m <<= 1) part += __shfl_xor(part, m, kWave);
+            if (idx < nvec && (lane & (LPH - 1)) == 0) lb[(long)j * p.H + head] = part * scale;
+        }
+    }
+}
+
+__global__ __launch_bounds__(1024) void decode_select_kernel(
+    DecodeDims p, const float* __restrict__ logits, float decay, int budget,
+    float* __restrict__ acc, int32_t* __restrict__ ids, uint8_t* __restrict__ protect, int32_t* __restrict__ len,
+    uint8_t* __restrict__ keep, int32_t* __restrict__ holes, int32_t* __restrict__ movers, int32_t* __restrict__ n_move,
+    int32_t* __restrict__ evicted_ids, int32_t* __restrict__ evicted_count)
+{
+    extern __shared__ float s_dyn[];                 // [2*H] max / inv, then [32][H] scratch
+    __shared__ int s_red[16];
+    __shared__ int s_hist[256];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int H = p.H;
+    const int n = min(max(len[b], 0), p.Lcap);
+    float* s_max = s_dyn;
+    float* s_inv = s_dyn + H;
+    float* s_part = s_dyn + 2 * H;                   // [parts][H]
+    const float* lb = logits + (long)b * p.Lcap * H;
+    float* ab = acc + (long)b * p.Lcap;
+    int32_t* ib = ids + (long)b * p.Lcap;
+    uint8_t* pb = protect + (long)b * p.Lcap;
+    uint8_t* kb = keep + (long)b * p.Lcap;
+    int32_t* hb = holes + (long)b * p.Lcap;
+    int32_t* mvb = movers + (long)b * p.Lcap;
+
+    if (n == 0) {
+        if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
+        return;
+    }
+    // per-head softmax statistics over the live entries: thread = (part, head)
+    const int parts = blockDim.x / H;                // host guarantees H <= blockDim.x and H | blockDim.x
+    const int h = tid % H, part = tid / H;
+    {
+        float mx = -INFINITY;
+        if (part < parts)
+            for (int j = part; j < n; j += parts) mx = fmaxf(mx, lb[(long)j * H + h]);
+        if (part < parts) s_part[part * H + h] = mx;
+        __syncthreads();
+        if (tid < H) {
+            float m2 = -INFINITY;
+            for (int q = 0; q < parts; ++q) m2 = fmaxf(m2, s_part[q * H + tid]);
+            s_max[tid] = m2;
+        }
+        __syncthreads();
+        const float mh = s_max[h];
+        float z = 0.f;
+        if (part < parts)
+            for (int j = part; j < n; j += parts) z += exp2f((lb[(long)j * H + h] - mh) * kLog2eD);
+        if (part < parts) s_part[part * H + h] = z;
+        __syncthreads();
+        if (tid < H) {
+            float z2 = 0.f;
+            for (int q = 0; q < parts; ++q) z2 += s_part[q * H + tid];
+            s_inv[tid] = 1.0f / (z2 * (float)H);
+        }
+        __syncthreads();
+    }
+    // a_t[j] = mean_h softmax ; acc <- decay*acc + a_t
+    for (int j = tid; j < n; j += blockDim.x) {
+        float a = 0.f;
+        for (int hh = 0; hh < H; ++hh) a += exp2f((lb[(long)j * H + hh] - s_max[hh]) * kLog2eD) * s_inv[hh];
+        ab[j] = fmaf(decay, ab[j], a);
+    }
+    __syncthreads();
+
+    if (n <= budget) {                               // nothing to evict
+        if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
+        return;
+    }
+    int np = 0;
+    for (int j = tid; j < n; j += blockDim.x) np += pb[j] != 0;
+    np = block_sum_i(np, s_red);
+    const int nu = n - np;
+    const int extra = min(max(budget - np, 0), nu);
+    const int new_len = np + extra;
+    SelectBound sb{0ull, 63};
+    if (extra > 0) {
+        auto keyfn = [&](int i, bool& ok) -> uint64_t {
+            ok = pb[i] == 0;
+            return ok ? rank_key(ab[i], ib[i]) : 0ull;
+        };
+        sb = block_radix_select(keyfn, n, extra, s_hist);
+    }
+    // keep flags, hole / mover / evicted lists (ascending slot order by construction of the scan)
+    int run_h = 0, run_m = 0, run_e = 0;
+    for (int base = 0; base < n; base += blockDim.x) {
+        const int j = base + tid;
+        bool kp = false;
+        if (j < n) {
+            kp = pb[j] != 0 || (extra > 0 && (rank_key(ab[j], ib[j]) >> sb.shift) >= sb.bound);
+            kb[j] = kp;
+        }
+        const bool is_hole = j < new_len && !kp;
+        const bool is_mover = j >= new_len && j < n && kp;
+        const bool is_ev = j < n && !kp;
+        int th, tm, te;
+        const int rh = block_rank(is_hole, s_red, th);
+        const int rm = block_rank(is_mover, s_red, tm);
+        const int re = block_rank(is_ev, s_red, te);
+        if (is_hole) hb[run_h + rh] = j;
+        if (is_mover) mvb[run_m + rm] = j;
+        if (is_ev && evicted_ids) evicted_ids[(long)b * p.Lcap + run_e + re] = ib[j];
+        run_h += th; run_m += tm; run_e += te;
+    }
+    __syncthreads();
+    // move the small per-entry arrays (sources >= new_len, destinations < new_len: no overlap)
+    for (int t = tid; t < run_m; t += blockDim.x) {
+        const int src = mvb[t], dst = hb[t];
+        ab[dst] = ab[src];
+        ib[dst] = ib[src];
+        pb[dst] = pb[src];
+    }
+    if (tid == 0) {
+        n_move[b] = run_m;
+        len[b] = new_len;
+        if (evicted_count) evicted_count[b] = run_e;
+    }
+}
+
+// Row moves: block (g, b) copies movers[t] -> holes[t] for t = g, g + gridDim.x, ...
+__global__ __launch_bounds__(256) void decode_move_kernel(
+    DecodeDims p, const int32_t* __restrict__ holes, const int32_t* __restrict__ movers,
+    const int32_t* __restrict__ n_move, u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache)
+{
+    const int b = blockIdx.y;
+    const int nm = n_move[b];
+    const int rv = p.H * p.d / 8;
+    for (int t = blockIdx.x; t < nm; t += gridDim.x) {
+        const long src = ((long)b * p.Lcap + movers[(long)b * p.Lcap + t]) * rv;
+        const long dst = ((long)b * p.Lcap + holes[(long)b * p.Lcap + t]) * rv;
+        for (int c = threadIdx.x; c < rv; c += blockDim.x) {
+            k_cache[dst + c] = k_cache[src + c];
+            v_cache[dst + c] = v_cache[src + c];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void decode_append_kernel(
+    DecodeDims p, const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new,
+    u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache,
+    float* __restrict__ acc, int32_t* __restrict__ ids, uint8_t* __restrict__ protect, int32_t* __restrict__ len,
+    int32_t new_id, int protect_new)
+{
+    const int b = blockIdx.x;
+    const int slot = len[b];
+    if (slot < 0 || slot >= p.Lcap) return;
+    const int rv = p.H * p.d / 8;
+    const long dst = ((long)b * p.Lcap + slot) * rv;
+    for (int c = threadIdx.x; c < rv; c += blockDim.x) {
+        k_cache[dst + c] = k_new[(long)b * rv + c];
+        v_cache[dst + c] = v_new[(long)b * rv + c];
+    }
+    __syncthreads();                                   // every thread has read len[b] before it changes
+    if (threadIdx.x == 0) {
+        acc[(long)b * p.Lcap + slot] = 0.f;
+        ids[(long)b * p.Lcap + slot] = new_id;
+        protect[(long)b * p.Lcap + slot] = protect_new ? 1 : 0;
+        len[b] = slot + 1;
+    }
+}
+
+struct DecodeWorkspace {
+    float* logits; uint8_t* keep; int32_t* holes; int32_t* movers; int32_t* n_move;
+    size_t bytes;
+};
+
+DecodeWorkspace carve_decode(void* base, int B, int Lcap, int H) {
+    Carver c(base);
+    DecodeWorkspace w;
+    w.logits = c.take<float>((size_t)B * Lcap * H);
+    w.keep = c.take<uint8_t>((size_t)B * Lcap);
+    w.holes = c.take<int32_t>((size_t)B * Lcap);
+    w.movers = c.take<int32_t>((size_t)B * Lcap);
+    w.n_move = c.take<int32_t>((size_t)B);
+    w.bytes = c.off;
+    return w;
+}
+
+int check_decode_dims(const char* who, int B, int Lcap, int H, int d) {
+    if (B <= 0 || Lcap <= 0 || H <= 0 || d <= 0) return fail(MD_EINVAL, "%s: B, Lcap, H, d must be positive", who);
+    if (d != 8 && d != 16 && d != 32 && d != 64 && d != 128 && d != 256 && d != 512)
+        return fail(MD_ESHAPE, "%s: head dim %d must be a power of two in [8, 512]", who, d);
+    if (H > 1024 || (1024 % H) != 0) return fail(MD_ESHAPE, "%s: H=%d must divide 1024", who, H);
+    if ((long)B * Lcap > (1l << 28)) return fail(MD_ESHAPE, "%s: cache too large", who);
+    return MD_OK;
+}
+
+}  // namespace
+}  // namespace md
+
+using namespace md;
+
+extern "C" size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H) {
+    if (B <= 0 || Lcap <= 0 || H <= 0) return 0;
+    return carve_decode(nullptr, B, Lcap, H).bytes;
+}
+
+extern "C" int mustdrop_decode_evict(
+    const void* q, void* k_cache, void* v_cache,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d,
+    float softmax_scale, float decay, int budget,
+    int32_t* evicted_ids, int32_t* evicted_count,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    int rc = check_decode_dims("decode_evict", B, Lcap, H, d);
+    if (rc != MD_OK) return rc;
+    if (!q || !k_cache || !v_cache || !acc || !ids || !protect || !len)
+        return fail(MD_EINVAL, "decode_evict: q, the caches and the state arrays are required");
+    if (budget < 0) return fail(MD_EINVAL, "decode_evict: negative budget");
+    if (std::isnan(softmax_scale) || std::isnan(decay)) return fail(MD_EINVAL, "decode_evict: NaN parameter");
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache))
+        return fail(MD_EALIGN, "decode_evict: q and the caches must be 16-byte aligned");
+    const size_t cache_bytes = (size_t)B * Lcap * H * d * 2;
+    if (overlaps(k_cache, cache_bytes, v_cache, cache_bytes)) return fail(MD_EALIAS, "decode_evict: k_cache overlaps v_cache");
+    if (overlaps(q, (size_t)B * H * d * 2, k_cache, cache_bytes) || overlaps(q, (size_t)B * H * d * 2, v_cache, cache_bytes))
+        return fail(MD_EALIAS, "decode_evict: q overlaps a cache");
+    const DecodeWorkspace w = carve_decode(workspace, B, Lcap, H);
+    if (!workspace || workspace_bytes < w.bytes)
+        return fail(MD_EWORKSPACE, "decode_evict: workspace of %zu bytes needed, %zu given", w.bytes, workspace ? workspace_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(MD_EALIGN, "decode_evict: workspace must be 256-byte aligned");
+
+    DecodeDims p{B, Lcap, H, d};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int tpb = 32;
+    dim3 g1((Lcap + tpb - 1) / tpb, B);
+    const uint16_t* qp = static_cast<const uint16_t*>(q);
+    const uint16_t* kp = static_cast<const uint16_t*>(k_cache);
+    switch (d / 8) {
+        case 1: decode_logits_kernel<1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        case 2: decode_logits_kernel<2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        case 4: decode_logits_kernel<4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        case 8: decode_logits_kernel<8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        case 16: decode_logits_kernel<16><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        case 32: decode_logits_kernel<32><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        default: decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+    }
+    const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);
+    decode_select_kernel<<<B, 1024, lds, st>>>(p, w.logits, decay, budget, acc, ids, protect, len,
+                                              w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
+    dim3 g3(32, B);
+    decode_move_kernel<<<g3, 256, 0, st>>>(p, w.holes, w.movers, w.n_move,
+                                          static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache));
+    return check_launch("decode_evict");
+}
+
+extern "C" int mustdrop_decode_append(
+    const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d, int32_t new_id, int protect_new, void* stream)
+{
+    clear_error();
+    int rc = check_decode_dims("decode_append", B, Lcap, H, d);
+    if (rc != MD_OK) return rc;
+    if (!k_new || !v_new || !k_cache || !v_cache || !acc || !ids || !protect || !len)
+        return fail(MD_EINVAL, "decode_append: all pointers are required");
+    if (new_id < 0) return fail(MD_EINVAL, "decode_append: ids must be non-negative");
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+        return fail(MD_EALIGN, "decode_append: tensors must be 16-byte aligned");
+    DecodeDims p{B, Lcap, H, d};
+    decode_append_kernel<<<B, 256, 0, static_cast<hipStream_t>(stream)>>>(
+        p, static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
+        static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new);
+    return check_launch("decode_append");
+}

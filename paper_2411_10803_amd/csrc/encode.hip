@@ -1,0 +1,496 @@
+// Stage 1 -- vision encoding (Sec. 3.3): Key Retaining (Eq. 6-7, budget form) and Local Spatial
+// Merging (Eq. 5), followed by stable compaction of the survivors.
+//
+// Launch plan (all on the caller's stream, no host synchronisation):
+//   cls_logits_kernel   one wave per key row: q_cls . k_j per head            (HBM: reads k_cls once)
+//   window_sim_kernel   one wave per window: Gram matrix in registers -> S    (HBM: reads x once)
+//   encode_decide_kernel one block per sample: softmax + head mean, radix top-k -> O, merge
+//                        decisions, prefix sum of survivors, small outputs    (tiny)
+//   encode_emit_kernel  one wave per window: row copies / mass-weighted means (re-reads x, writes out_x)
+#include "md_device.hpp"
+#include "md_host.hpp"
+
+namespace md {
+namespace {
+
+constexpr int kMaxWindow = 16;
+constexpr int kMaxClsHeads = 256;
+
+struct EncodeDims {
+    int B, T, Hg, Wg, D, Hc, dc;
+    int kt, kh, kw;
+    int M, W, ws, nwx, nwy, nwt;
+};
+
+__device__ __forceinline__ int member_token(const EncodeDims& p, int w, int m) {
+    const int wx = w % p.nwx, wy = (w / p.nwx) % p.nwy, wt = w / (p.nwx * p.nwy);
+    const int dx = m % p.kw, dy = (m / p.kw) % p.kh, dt = m / (p.kw * p.kh);
+    return ((wt * p.kt + dt) * p.Hg + (wy * p.kh + dy)) * p.Wg + (wx * p.kw + dx);
+}
+
+__device__ __forceinline__ int window_of_token(const EncodeDims& p, int tok) {
+    const int x = tok % p.Wg, y = (tok / p.Wg) % p.Hg, t = tok / (p.Wg * p.Hg);
+    return ((t / p.kt) * p.nwy + (y / p.kh)) * p.nwx + (x / p.kw);
+}
+
+// One 16-byte vector of a row, widened to fp32.  VEC = 4 (fp32) or 8 (bf16).
+template <bool BF> struct Vec;
+template <> struct Vec<false> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void load(const void* row, int c, float (&o)[4]) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c);
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+    __device__ static __forceinline__ void store(void* row, int c, const float (&o)[4]) {
+        f32x4 v; v.x = o[0]; v.y = o[1]; v.z = o[2]; v.w = o[3];
+        *reinterpret_cast<f32x4*>(static_cast<float*>(row) + c) = v;
+    }
+};
+template <> struct Vec<true> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void load(const void* row, int c, float (&o)[8]) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c);
+        o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
+        o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+    }
+    __device__ static __forceinline__ void store(void* row, int c, const float (&o)[8]) {
+        u32x4 v;
+        v.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
+        v.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
+        v.z = f32_to_bf16(o[4]) | (f32_to_bf16(o[5]) << 16);
+        v.w = f32_to_bf16(o[6]) | (f32_to_bf16(o[7]) << 16);
+        *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(row) + c) = v;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 6 numerator: logit[b][h][j] = q_cls[b][h] . k_cls[b][j][h] / sqrt(dc), j = 0..M.
+// One wave per key row.  A head covers vph = dc/VEC consecutive 16-byte vectors (a power of two),
+// so the per-head sums are segmented butterflies over vph lanes (or whole-wave sums if vph >= 64).
+template <bool BF>
+__global__ __launch_bounds__(256) void cls_logits_kernel(
+    const void* __restrict__ q_cls, const void* __restrict__ k_cls, const uint8_t* __restrict__ valid,
+    EncodeDims p, float* __restrict__ logits)
+{
+    constexpr int VEC = Vec<BF>::N;
+    const int lane = lane_id();
+    const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
+    const long rows = (long)p.B * (p.M + 1);
+    if (item >= rows) return;
+    const int b = (int)(item / (p.M + 1)), j = (int)(item % (p.M + 1));
+    if (j > 0 && valid && !valid[(size_t)b * p.M + (j - 1)]) return;     // padding: never read
+
+    const size_t esz = BF ? 2 : 4;
+    const char* qrow = static_cast<const char*>(q_cls) + (size_t)b * p.D * esz;
+    const char* krow = static_cast<const char*>(k_cls) + ((size_t)b * (p.M + 1) + j) * p.D * esz;
+    const int nvec = p.D / VEC, vph = p.dc / VEC;
+    const float scale = 1.0f / sqrtf((float)p.dc);
+    float* out = logits + (size_t)b * p.Hc * (p.M + 1) + j;
+
+    float acc = 0.f;
+    const int iters = (nvec + kWave - 1) / kWave;
+    for (int it = 0; it < iters; ++it) {
+        const int idx = it * kWave + lane;
+        float part = 0.f;
+        if (idx < nvec) {
+            float qv[VEC], kv[VEC];
+            Vec<BF>::load(qrow, idx * VEC, qv);
+            Vec<BF>::load(krow, idx * VEC, kv);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) part = fmaf(qv[e], kv[e], part);
+        }
+        if (vph < kWave) {
+            for (int m = 1; m < vph; m <<= 1) part += __shfl_xor(part, m, kWave);
+            if (idx < nvec && (lane & (vph - 1)) == 0) out[(size_t)(idx / vph) * (p.M + 1)] = part * scale;
+        } else {
+            acc += part;
+            const int per_head = vph / kWave;                 // iterations per head
+            if ((it + 1) % per_head == 0) {
+                const float tot = wave_sum(acc);
+                if (lane == 0) out[(size_t)(it / per_head) * (p.M + 1)] = tot * scale;
+                acc = 0.f;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 5: S_w = mean over unordered pairs of valid members of cos(x_m, x_n).  One wave per window;
+// each lane owns a strided slice of the feature dimension and keeps the upper triangle of the
+// Gram matrix (norms on the diagonal) in registers; one butterfly per entry at the end.
+template <int WSM, bool BF>
+__global__ __launch_bounds__(256) void window_sim_kernel(
+    const void* __restrict__ x, const uint8_t* __restrict__ valid, EncodeDims p, float* __restrict__ sim)
+{
+    constexpr int VEC = Vec<BF>::N;
+    const int lane = lane_id();
+    const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
+    if (item >= (long)p.B * p.W) return;
+    const int b = (int)(item / p.W), w = (int)(item % p.W);
+    const size_t esz = BF ? 2 : 4;
+
+    const char* rows[WSM];
+    bool ok[WSM];
+#pragma unroll
+    for (int m = 0; m < WSM; ++m) {
+        ok[m] = false;
+        rows[m] = nullptr;
+        if (m < p.ws) {
+            const int tok = member_token(p, w, m);
+            ok[m] = !valid || valid[(size_t)b * p.M + tok];
+            rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + tok) * p.D * esz;
+        }
+    }
+    float G[WSM * (WSM + 1) / 2];
+#pragma unroll
+    for (int i = 0; i < WSM * (WSM + 1) / 2; ++i) G[i] = 0.f;
+
+    for (int c = lane * VEC; c < p.D; c += kWave * VEC) {
+        float v[WSM][VEC];
+#pragma unroll
+        for (int m = 0; m < WSM; ++m) {
+            if (ok[m]) Vec<BF>::load(rows[m], c, v[m]);
+            else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[m][e] = 0.f;
+            }
+        }
+        int idx = 0;
+#pragma unroll
+        for (int m = 0; m < WSM; ++m)
+#pragma unroll
+            for (int n = m; n < WSM; ++n) {
+                float s = G[idx];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s = fmaf(v[m][e], v[n][e], s);
+                G[idx++] = s;
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < WSM * (WSM + 1) / 2; ++i) G[i] = wave_sum(G[i]);
+
+    if (lane == 0) {
+        float S = 0.f;
+        int npairs = 0;
+        float diag[WSM];
+        {
+            int idx = 0;
+#pragma unroll
+            for (int m = 0; m < WSM; ++m) { diag[m] = G[idx]; idx += WSM - m; }
+        }
+        int idx = 0;
+#pragma unroll
+        for (int m = 0; m < WSM; ++m)
+#pragma unroll
+            for (int n = m; n < WSM; ++n) {
+                if (n > m && ok[m] && ok[n]) {
+                    const float den = sqrtf(diag[m]) * sqrtf(diag[n]);
+                    S += (diag[m] > 0.f && diag[n] > 0.f) ? G[idx] / den : 0.f;
+                    ++npairs;
+                }
+                ++idx;
+            }
+        sim[(size_t)b * p.W + w] = npairs > 0 ? S / (float)npairs : 0.f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-sample decisions.  One block per sample.
+__global__ __launch_bounds__(1024) void encode_decide_kernel(
+    EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
+    const float* __restrict__ logits, const float* __restrict__ sim, float tau, int key_budget,
+    float* __restrict__ acls, uint8_t* __restrict__ iskey, uint8_t* __restrict__ wmerged,
+    int32_t* __restrict__ dstpos,
+    int32_t* __restrict__ out_index, float* __restrict__ out_mass, uint8_t* __restrict__ out_is_key,
+    uint8_t* __restrict__ out_valid, int32_t* __restrict__ out_count, int32_t* __restrict__ key_index,
+    float* __restrict__ a_cls_out, float* __restrict__ window_sim_out)
+{
+    __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
+    __shared__ int s_hist[256];
+    __shared__ int s_red[16];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
+    const int M = p.M, W = p.W;
+    const uint8_t* vb = valid ? valid + (size_t)b * M : nullptr;
+    const float* mb = mass_in ? mass_in + (size_t)b * M : nullptr;
+    float* acls_b = acls + (size_t)b * M;
+    uint8_t* iskey_b = iskey + (size_t)b * M;
+    uint8_t* wm_b = wmerged + (size_t)b * W;
+    int32_t* dst_b = dstpos + (size_t)b * M;
+
+    // ---- Key Retaining
+    if (key_budget > 0) {
+        const float* lg = logits + (size_t)b * p.Hc * (M + 1);
+        for (int h = wv; h < p.Hc; h += nw) {
+            const float* l = lg + (size_t)h * (M + 1);
+            float mx = -INFINITY;
+            for (int j = lane; j <= M; j += kWave)
+                if (j == 0 || !vb || vb[j - 1]) mx = fmaxf(mx, l[j]);
+            mx = wave_max(mx);
+            float z = 0.f;
+            for (int j = lane; j <= M; j += kWave)
+                if (j == 0 || !vb || vb[j - 1]) z += __expf(l[j] - mx);
+            z = wave_sum(z);
+            if (lane == 0) { s_max[h] = mx; s_inv[h] = 1.0f / (z * (float)p.Hc); }
+        }
+        __syncthreads();
+        for (int j = tid; j < M; j += blockDim.x) {
+            float a = -INFINITY;
+            if (!vb || vb[j]) {
+                a = 0.f;
+                for (int h = 0; h < p.Hc; ++h) a += __expf(lg[(size_t)h * (M + 1) + j + 1] - s_max[h]) * s_inv[h];
+            }
+            acls_b[j] = a;
+            if (a_cls_out) a_cls_out[(size_t)b * M + j] = a;
+        }
+        __syncthreads();
+        auto keyfn = [&](int i, bool& ok) -> uint64_t {
+            ok = !vb || vb[i];
+            return ok ? rank_key(acls_b[i], i) : 0ull;
+        };
+        const SelectBound sb = block_radix_select(keyfn, M, key_budget, s_hist);
+        int running = 0;
+        for (int base = 0; base < M; base += blockDim.x) {
+            const int j = base + tid;
+            bool sel = false;
+            if (j < M && (!vb || vb[j])) sel = (rank_key(acls_b[j], j) >> sb.shift) >= sb.bound;
+            if (j < M) iskey_b[j] = sel;
+            int total;
+            const int r = block_rank(sel, s_red, total);
+            if (sel) key_index[(size_t)b * key_budget + running + r] = j;
+            running += total;
+        }
+        for (int r = running + tid; r < key_budget; r += blockDim.x) key_index[(size_t)b * key_budget + r] = -1;
+    } else {
+        for (int j = tid; j < M; j += blockDim.x) {
+            iskey_b[j] = 0;
+            if (a_cls_out) a_cls_out[(size_t)b * M + j] = 0.f;
+        }
+    }
+    __syncthreads();
+
+    // ---- merge decision per window: S > tau, >= 2 valid members, no key member
+    for (int w = tid; w < W; w += blockDim.x) {
+        int n = 0;
+        bool has_key = false;
+        for (int m = 0; m < p.ws; ++m) {
+            const int tok = member_token(p, w, m);
+            if (vb && !vb[tok]) continue;
+            ++n;
+            has_key |= iskey_b[tok] != 0;
+        }
+        const float S = sim[(size_t)b * W + w];
+        wm_b[w] = (n >= 2 && !has_key && S > tau) ? 1 : 0;
+        if (window_sim_out) window_sim_out[(size_t)b * W + w] = S;
+    }
+    __syncthreads();
+
+    // ---- survivors in ascending token index: exclusive prefix sum of the survivor flags
+    int running = 0;
+    for (int base = 0; base < M; base += blockDim.x) {
+        const int j = base + tid;
+        bool surv = false, merged = false;
+        float mass = 0.f;
+        if (j < M && (!vb || vb[j])) {
+            const int w = window_of_token(p, j);
+            merged = wm_b[w] != 0;
+            if (!merged) {
+                surv = true;
+                mass = mb ? mb[j] : 1.0f;
+            } else {
+                int first = -1;
+                for (int m = 0; m < p.ws; ++m) {
+                    const int tok = member_token(p, w, m);
+                    if (vb && !vb[tok]) continue;
+                    if (first < 0) first = tok;
+                    mass += mb ? mb[tok] : 1.0f;
+                }
+                surv = (first == j);
+            }
+        }
+        int total;
+        const int r = block_rank(surv, s_red, total);
+        if (j < M) dst_b[j] = surv ? running + r : -1;
+        if (surv) {
+            const size_t o = (size_t)b * M + running + r;
+            out_index[o] = j;
+            out_mass[o] = mass;
+            out_is_key[o] = merged ? 0 : iskey_b[j];
+        }
+        running += total;
+    }
+    if (tid == 0) out_count[b] = running;
+    if (out_valid)
+        for (int s = tid; s < M; s += blockDim.x) out_valid[(size_t)b * M + s] = s < running;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Writes the surviving rows.  One wave per window.
+template <bool BF>
+__global__ __launch_bounds__(256) void encode_emit_kernel(
+    const void* __restrict__ x, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
+    EncodeDims p, const uint8_t* __restrict__ wmerged, const int32_t* __restrict__ dstpos,
+    void* __restrict__ out_x)
+{
+    constexpr int VEC = Vec<BF>::N;
+    const int lane = lane_id();
+    const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
+    if (item >= (long)p.B * p.W) return;
+    const int b = (int)(item / p.W), w = (int)(item % p.W);
+    const size_t esz = BF ? 2 : 4;
+    const size_t rowb = (size_t)p.D * esz;
+    const char* xb = static_cast<const char*>(x) + (size_t)b * p.M * rowb;
+    char* ob = static_cast<char*>(out_x) + (size_t)b * p.M * rowb;
+    const uint8_t* vb = valid ? valid + (size_t)b * p.M : nullptr;
+    const float* mb = mass_in ? mass_in + (size_t)b * p.M : nullptr;
+    const int32_t* dst_b = dstpos + (size_t)b * p.M;
+
+    if (!wmerged[(size_t)b * p.W + w]) {
+        for (int m = 0; m < p.ws; ++m) {
+            const int tok = member_token(p, w, m);
+            if (vb && !vb[tok]) continue;
+            const int pos = dst_b[tok];
+            const u32x4* src = reinterpret_cast<const u32x4*>(xb + (size_t)tok * rowb);
+            u32x4* dst = reinterpret_cast<u32x4*>(ob + (size_t)pos * rowb);
+            for (int c = lane; c < (int)(rowb / 16); c += kWave) dst[c] = src[c];
+        }
+        return;
+    }
+    int first = -1;
+    float msum = 0.f;
+    for (int m = 0; m < p.ws; ++m) {
+        const int tok = member_token(p, w, m);
+        if (vb && !vb[tok]) continue;
+        if (first < 0) first = tok;
+        msum += mb ? mb[tok] : 1.0f;
+    }
+    char* orow = ob + (size_t)dst_b[first] * rowb;
+    for (int c = lane * VEC; c < p.D; c += kWave * VEC) {
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        for (int m = 0; m < p.ws; ++m) {
+            const int tok = member_token(p, w, m);
+            if (vb && !vb[tok]) continue;
+            const float mm = mb ? mb[tok] : 1.0f;
+            float v[VEC];
+            Vec<BF>::load(xb + (size_t)tok * rowb, c, v);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = fmaf(mm, v[e], acc[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = acc[e] / msum;
+        Vec<BF>::store(orow, c, acc);
+    }
+}
+
+struct EncodeWorkspace {
+    float* logits; float* acls; float* sim; uint8_t* iskey; uint8_t* wmerged; int32_t* dstpos;
+    size_t bytes;
+};
+
+EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
+    Carver c(base);
+    EncodeWorkspace ws;
+    ws.logits = c.take<float>((size_t)B * (Hc > 0 ? Hc : 1) * (M + 1));
+    ws.acls = c.take<float>((size_t)B * M);
+    ws.sim = c.take<float>((size_t)B * W);
+    ws.iskey = c.take<uint8_t>((size_t)B * M);
+    ws.wmerged = c.take<uint8_t>((size_t)B * W);
+    ws.dstpos = c.take<int32_t>((size_t)B * M);
+    ws.bytes = c.off;
+    return ws;
+}
+
+template <bool BF>
+void launch_window_sim(int ws, dim3 grid, hipStream_t st, const void* x, const uint8_t* valid,
+                       const EncodeDims& p, float* sim) {
+    if (ws <= 2) window_sim_kernel<2, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
+    else if (ws <= 4) window_sim_kernel<4, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
+    else if (ws <= 8) window_sim_kernel<8, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
+    else window_sim_kernel<16, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
+}
+
+}  // namespace
+}  // namespace md
+
+using namespace md;
+
+extern "C" size_t mustdrop_encode_merge_workspace_bytes(int B, int T, int Hg, int Wg, int Hc, int kt, int kh, int kw) {
+    if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || kt <= 0 || kh <= 0 || kw <= 0) return 0;
+    const long M = (long)T * Hg * Wg;
+    const long W = M / ((long)kt * kh * kw);
+    return carve_encode(nullptr, B, (int)M, (int)(W > 0 ? W : 1), Hc).bytes;
+}
+
+extern "C" int mustdrop_encode_merge(
+    const void* x, md_dtype x_dtype,
+    const void* q_cls, const void* k_cls, md_dtype qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, int key_budget,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
+    int32_t* out_count, int32_t* key_index,
+    float* a_cls_out, float* window_sim_out,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    if (x_dtype != MD_F32 && x_dtype != MD_BF16) return fail(MD_EDTYPE, "encode_merge: unknown x_dtype %d", (int)x_dtype);
+    if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || D <= 0)
+        return fail(MD_EINVAL, "encode_merge: B, T, Hg, Wg, D must be positive (got %d %d %d %d %d)", B, T, Hg, Wg, D);
+    if (kt <= 0 || kh <= 0 || kw <= 0) return fail(MD_EINVAL, "encode_merge: window sizes must be positive");
+    if (T % kt || Hg % kh || Wg % kw)
+        return fail(MD_ESHAPE, "encode_merge: grid %dx%dx%d is not divisible by window %dx%dx%d", T, Hg, Wg, kt, kh, kw);
+    const long ws_l = (long)kt * kh * kw;
+    if (ws_l > kMaxWindow) return fail(MD_ESHAPE, "encode_merge: window of %ld tokens exceeds the limit of %d", ws_l, kMaxWindow);
+    const long M_l = (long)T * Hg * Wg;
+    if (M_l > (1l << 24) || (long)B * M_l > (1l << 30)) return fail(MD_ESHAPE, "encode_merge: too many tokens");
+    const int M = (int)M_l, ws = (int)ws_l, W = M / ws;
+    if (key_budget < 0 || key_budget > M) return fail(MD_EINVAL, "encode_merge: key_budget %d outside [0, %d]", key_budget, M);
+    if (!x || !out_x || !out_index || !out_mass || !out_is_key || !out_count)
+        return fail(MD_EINVAL, "encode_merge: x and the out_* arrays are required");
+    if (std::isnan(tau)) return fail(MD_EINVAL, "encode_merge: tau is NaN");
+    const size_t xe = elt_size(x_dtype);
+    if ((D * xe) % 16) return fail(MD_EALIGN, "encode_merge: a row of D=%d elements is not a multiple of 16 bytes", D);
+    if (!aligned16(x) || !aligned16(out_x)) return fail(MD_EALIGN, "encode_merge: x / out_x must be 16-byte aligned");
+    if (key_budget > 0) {
+        if (qk_dtype != MD_F32 && qk_dtype != MD_BF16) return fail(MD_EDTYPE, "encode_merge: unknown qk_dtype %d", (int)qk_dtype);
+        if (!q_cls || !k_cls || !key_index) return fail(MD_EINVAL, "encode_merge: q_cls, k_cls, key_index are required when key_budget > 0");
+        if (Hc <= 0 || dc <= 0) return fail(MD_EINVAL, "encode_merge: Hc and dc must be positive");
+        if (Hc > kMaxClsHeads) return fail(MD_ESHAPE, "encode_merge: Hc=%d exceeds the limit of %d", Hc, kMaxClsHeads);
+        if ((long)Hc * dc != D) return fail(MD_ESHAPE, "encode_merge: Hc*dc = %ld differs from D = %d", (long)Hc * dc, D);
+        const int vec = qk_dtype == MD_BF16 ? 8 : 4;
+        if ((dc & (dc - 1)) || dc < vec) return fail(MD_ESHAPE, "encode_merge: dc=%d must be a power of two >= %d", dc, vec);
+        if (!aligned16(q_cls) || !aligned16(k_cls)) return fail(MD_EALIGN, "encode_merge: q_cls / k_cls must be 16-byte aligned");
+    } else if (q_cls || k_cls) {
+        return fail(MD_EINVAL, "encode_merge: q_cls / k_cls given but key_budget == 0");
+    }
+    const size_t xbytes = (size_t)B * M * D * xe;
+    if (overlaps(x, xbytes, out_x, xbytes)) return fail(MD_EALIAS, "encode_merge: out_x overlaps x");
+    const EncodeWorkspace wsp = carve_encode(workspace, B, M, W, key_budget > 0 ? Hc : 0);
+    if (!workspace || workspace_bytes < wsp.bytes)
+        return fail(MD_EWORKSPACE, "encode_merge: workspace of %zu bytes needed, %zu given", wsp.bytes, workspace ? workspace_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(MD_EALIGN, "encode_merge: workspace must be 256-byte aligned");
+
+    EncodeDims p;
+    p.B = B; p.T = T; p.Hg = Hg; p.Wg = Wg; p.D = D; p.Hc = key_budget > 0 ? Hc : 0; p.dc = dc;
+    p.kt = kt; p.kh = kh; p.kw = kw; p.M = M; p.W = W; p.ws = ws;
+    p.nwx = Wg / kw; p.nwy = Hg / kh; p.nwt = T / kt;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (key_budget > 0) {
+        const long rows = (long)B * (M + 1);
+        dim3 grid((unsigned)((rows + 3) / 4));
+        if (qk_dtype == MD_BF16) cls_logits_kernel<true><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits);
+        else cls_logits_kernel<false><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits);
+    }
+    dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
+    if (x_dtype == MD_BF16) launch_window_sim<true>(ws, wgrid, st, x, valid, p, wsp.sim);
+    else launch_window_sim<false>(ws, wgrid, st, x, valid, p, wsp.sim);
+    encode_decide_kernel<<<B, 1024, 0, st>>>(p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget,
+                                             wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
+                                             out_index, out_mass, out_is_key, out_valid, out_count, key_index,
+                                             a_cls_out, window_sim_out);
+    if (x_dtype == MD_BF16) encode_emit_kernel<true><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
+    else encode_emit_kernel<false><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
+    return check_launch("encode_merge");
+}

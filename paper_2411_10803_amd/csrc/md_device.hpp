@@ -1,0 +1,167 @@
+// Device-side building blocks shared by the three stages: bf16 storage helpers, 64-lane wavefront
+// reductions, deterministic block reductions / scans and a block-wide radix select.
+// Written for gfx950 (wave64) only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace md {
+
+constexpr int kWave = 64;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN)
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+// Block reductions: fixed tree (lanes by xor butterfly, then waves in index order) -> the result is
+// the same on every run and on every thread.  `red` holds >= blockDim.x/64 floats.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane_id() == 0) red[wave_id()] = v;
+    __syncthreads();
+    float t = 0.f;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) t += red[w];
+    return t;
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+    v = wave_max(v);
+    __syncthreads();
+    if (lane_id() == 0) red[wave_id()] = v;
+    __syncthreads();
+    float t = -INFINITY;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) t = fmaxf(t, red[w]);
+    return t;
+}
+__device__ __forceinline__ int block_sum_i(int v, int* red) {
+    v = wave_sum_i(v);
+    __syncthreads();
+    if (lane_id() == 0) red[wave_id()] = v;
+    __syncthreads();
+    int t = 0;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) t += red[w];
+    return t;
+}
+
+// Exclusive scan of a 0/1 flag over the block, in thread order.  Returns this thread's rank and
+// the block total.  `red` holds >= blockDim.x/64 ints.
+__device__ __forceinline__ int block_rank(bool flag, int* red, int& total) {
+    const unsigned long long bal = __ballot(flag);
+    const int lane = lane_id();
+    const int below = __popcll(bal & ((1ull << lane) - 1ull));
+    __syncthreads();
+    if (lane == 0) red[wave_id()] = __popcll(bal);
+    __syncthreads();
+    int off = 0, tot = 0;
+    const int nw = blockDim.x >> 6, w = wave_id();
+    for (int i = 0; i < nw; ++i) {
+        const int c = red[i];
+        if (i < w) off += c;
+        tot += c;
+    }
+    total = tot;
+    return off + below;
+}
+
+// Order-preserving composite key: larger score first, then smaller tie value first.
+// `score` must be >= 0 (its bit pattern is then monotone); `tie` in [0, 2^31).
+__device__ __forceinline__ uint64_t rank_key(float score, int tie) {
+    return ((uint64_t)__float_as_uint(score) << 32) | (uint32_t)(0x7FFFFFFF - tie);
+}
+
+// Block-wide radix select: the k-th largest (k >= 1) of the distinct 64-bit keys produced by
+// `key(i, ok)` for i in [0, n) (ok=false: item absent).  8-bit digits from the top; stops as
+// soon as the chosen bin is taken whole.  Returns `bound` such that item i is among the k largest
+// iff (key_i >> shift) >= bound.  If fewer than k items exist every item is selected.
+// `hist` is 256 ints of shared memory.  All threads of the block must call it.
+struct SelectBound { uint64_t bound; int shift; };
+
+template <class KeyFn>
+__device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int k, int* hist) {
+    uint64_t prefix = 0;
+    int shift = 64;
+    __shared__ int s_digit, s_k, s_done;
+    int kk = k;
+    for (int pass = 0; pass < 8; ++pass) {
+        const int sh = 56 - 8 * pass;
+        __syncthreads();
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            bool ok;
+            const uint64_t kv = key(i, ok);
+            if (ok && (pass == 0 || (kv >> shift) == prefix)) atomicAdd(&hist[(kv >> sh) & 0xFF], 1);
+        }
+        __syncthreads();
+        if (threadIdx.x < kWave) {
+            // digits 255..0 handled 4 per lane, high digits in low lanes
+            const int lane = threadIdx.x;
+            int c[4], s = 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { c[t] = hist[255 - (lane * 4 + t)]; s += c[t]; }
+            int incl = s;                                   // inclusive scan over lanes
+#pragma unroll
+            for (int m = 1; m < kWave; m <<= 1) {
+                const int o = __shfl_up(incl, m, kWave);
+                if (lane >= m) incl += o;
+            }
+            int run = incl - s;                             // items in strictly higher digits
+            const int total = __shfl(incl, kWave - 1, kWave);
+            if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }   // fewer than k items
+            if (total >= kk) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (run < kk && run + c[t] >= kk) {
+                        s_digit = 255 - (lane * 4 + t);
+                        s_k = kk - run;
+                        s_done = (run + c[t] == kk) ? 1 : 0;
+                    }
+                    run += c[t];
+                }
+            }
+        }
+        __syncthreads();
+        if (s_done == 2) return SelectBound{0ull, 63};      // select everything (keys < 2^63)
+        prefix = (prefix << 8) | (uint64_t)s_digit;
+        shift = sh;
+        kk = s_k;
+        if (s_done == 1) break;
+    }
+    return SelectBound{prefix, shift};
+}
+
+}  // namespace md

@@ -1,0 +1,114 @@
+"""GPU parity: mustdrop_prefill_filter (HIP, through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from oracle import FILTER_BUDGET, FILTER_THRESHOLD
+from parity import check_prefill
+
+pytestmark = pytest.mark.gpu
+
+
+def run(t, Mv, budget, mode=FILTER_BUDGET, vis_valid=None, txt_len=None, is_key=None, gamma=None, alpha=None,
+        Rcap=None, scale=None, d=128):
+    from paper_2411_10803_amd import harness
+    N = t["q_txt"].shape[1]
+    gamma = 1.0 / Mv if gamma is None else gamma
+    alpha = 2.0 / (Mv + N) if alpha is None else alpha
+    scale = 1.0 / np.sqrt(t["q_txt"].shape[3]) if scale is None else scale
+    if Rcap is None:
+        Rcap = budget if mode == FILTER_BUDGET else Mv
+    g = harness.prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, mode, budget, gamma, alpha, Rcap)
+    o = oracle.prefill_filter(t["q_txt"], t["k"], t["v"], t["hidden"], vis_valid, txt_len, is_key, Mv, scale, mode,
+                              budget, gamma, alpha, Rcap)
+    s = check_prefill(g, o, t, Mv, vis_valid, is_key, mode, budget, gamma, alpha, Rcap)
+    return g, o, s
+
+
+def test_config1_single_sample():
+    cfg = wl.CONFIGS[1]
+    t = wl.prefill_inputs(cfg)
+    is_key = wl.random_key_mask(cfg, cfg.key_budget)
+    g, o, s = run(t, cfg.M, 192, is_key=is_key)
+    assert g["kept_count"][0] == 192
+
+
+def test_config2_three_budgets_on_a_batch_slice():
+    cfg = wl.CONFIGS[2]
+    t = wl.prefill_inputs(cfg, samples=[0, 1, 2, 15])
+    is_key = wl.random_key_mask(cfg, cfg.key_budget)[[0, 1, 2, 15]]
+    for R in cfg.budgets:
+        g, o, s = run(t, cfg.M, R, is_key=is_key)
+        assert np.all(g["kept_count"] == R)
+
+
+def test_config3_long_sequence_128_text_rows():
+    cfg = wl.CONFIGS[3]
+    t = wl.prefill_inputs(cfg, samples=[0])
+    is_key = wl.random_key_mask(cfg, cfg.key_budget)[[0]]
+    g, o, s = run(t, cfg.M, 320, is_key=is_key)
+    assert g["kept_count"][0] == 320
+
+
+def test_ragged_padding_and_odd_shapes():
+    # Mv and N not multiples of the 32-wide tiles, padded vision slots and padded text tail, NaN in padding
+    cfg = wl.tiny(wl.CONFIGS[2], B=3, Hg=7, Wg=11, N=45, H=6, d=64, C=264)
+    Mv = cfg.M
+    t = wl.prefill_inputs(cfg)
+    rng = np.random.default_rng(3)
+    vis_valid = (rng.random((cfg.B, Mv)) > 0.3).astype(np.uint8)
+    txt_len = np.array([45, 17, 1], dtype=np.int32)
+    is_key = wl.random_key_mask(cfg, 5, valid=vis_valid)
+    bad = vis_valid == 0
+    t["k"][:, :Mv][bad] = 0x7FC0
+    t["v"][:, :Mv][bad] = 0x7F80
+    t["hidden"][:, :Mv][bad] = 0xFFFF
+    for b in range(cfg.B):
+        t["k"][b, Mv + txt_len[b]:] = 0x7FC0
+        t["q_txt"][b, txt_len[b]:] = 0x7FC0
+    for R in (5, 20, 40):
+        run(t, Mv, R, vis_valid=vis_valid, txt_len=txt_len, is_key=is_key)
+    g, o, s = run(t, Mv, 0, mode=FILTER_THRESHOLD, vis_valid=vis_valid, txt_len=txt_len, is_key=is_key,
+                  gamma=1.0 / Mv, alpha=1.5 / Mv)
+    assert len(set(g["kept_count"].tolist())) > 1          # dynamic |D|
+    # budget >= number of valid tokens: everything valid is kept
+    g, o, s = run(t, Mv, Mv, vis_valid=vis_valid, txt_len=txt_len, is_key=is_key)
+    assert np.array_equal(g["kept_count"], vis_valid.sum(1))
+
+
+def test_threshold_mode_and_special_cases():
+    cfg = wl.tiny(wl.CONFIGS[2], B=2, Hg=8, Wg=12, N=32, H=4, d=128, C=512)
+    Mv = cfg.M
+    t = wl.prefill_inputs(cfg)
+    is_key = wl.random_key_mask(cfg, 4)
+    g, _, _ = run(t, Mv, 0, mode=FILTER_THRESHOLD, gamma=-1.0, alpha=0.5, is_key=is_key)
+    assert np.all(g["kept_count"] == Mv)
+    g, _, _ = run(t, Mv, 0, mode=FILTER_THRESHOLD, gamma=1.0, alpha=np.inf, is_key=is_key)
+    assert np.all(g["kept_count"] == 4)
+    run(t, Mv, 0, mode=FILTER_THRESHOLD, gamma=1.0 / Mv, alpha=2.0 / Mv, is_key=is_key)
+    # more keys than budget: true count reported, storage stops at Rcap
+    g, o, _ = run(t, Mv, 2, is_key=is_key)
+    assert np.all(g["kept_count"] == 4) and np.all(g["out_len"] == 2 + 32)
+    # zero queries: every score ties -> lowest indices win, harmonic-number closed form
+    t0 = dict(t)
+    t0["q_txt"] = np.zeros_like(t["q_txt"])
+    g, o, _ = run(t0, Mv, 10)
+    assert g["kept_index"].tolist() == [list(range(10))] * 2
+    H_ = sum(1.0 / (Mv + i + 1) for i in range(32))
+    assert np.allclose(g["score_global"], H_, rtol=1e-5) and np.allclose(g["score_indiv"], 1.0 / (Mv + 1), rtol=1e-5)
+    # literal N(0,1)/sqrt(d) inputs: near-uniform softmax, graded on counts and invariants
+    tl = wl.prefill_inputs(cfg, literal_scale=True)
+    g, o, s = run(tl, Mv, 24, is_key=is_key)
+    assert np.all(g["kept_count"] == 24)
+
+
+def test_determinism():
+    from paper_2411_10803_amd import harness
+    cfg = wl.tiny(wl.CONFIGS[2], B=2)
+    t = wl.prefill_inputs(cfg)
+    runs = [harness.prefill_on_gpu(t, cfg.M, None, None, None, 1 / np.sqrt(128), FILTER_BUDGET, 128,
+                                   1.0 / cfg.M, 2.0 / cfg.L) for _ in range(3)]
+    for r in runs[1:]:
+        for name in ("kept_index", "score_global", "score_indiv", "k_out", "hidden_out"):
+            assert np.array_equal(runs[0][name], r[name]), name
