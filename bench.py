@@ -1,0 +1,333 @@
+#!/usr/bin/env python3
+"""Benchmark of the MustDrop token-reduction hot path on one MI355X.
+
+One "step" = one pass of the whole path over one batch of the LLaVA-1.5-7B prefill workload
+(batch 16, 576 vision tokens of dim 1024 bf16, 64 text tokens, 32 heads x 128, hidden 4096):
+
+    mustdrop_encode_merge  ->  mustdrop_prefill_filter (budget 192)  ->  mustdrop_decode_evict
+
+chained on the device (out_valid / out_is_key feed the prefill stage; its compacted K/V, out_len,
+out_protect and out_ids are the decode stage's cache state).  Inputs are seeded synthetic tensors
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-decode-loop] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+BENCH_TAU = 0.955          # lands the average merge rate near the paper's Table 3 (about 440 of 576 tokens)
+PREFILL_BUDGET = 192
+DECODE_VISION_BUDGET = 128
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Cfg2Pipeline:
+    """Device tensors and the chained three-stage step for the batch-16 LLaVA-1.5 workload."""
+
+    def __init__(self, cfg, torch, md, harness):
+        self.cfg, self.torch, self.md = cfg, torch, md
+        dev = "cuda"
+        t0 = time.time()
+        self.enc_np = wl.encode_inputs(cfg)
+        self.pre_np = wl.prefill_inputs(cfg)
+        rng = np.random.default_rng([cfg.seed, 11])
+        self.q_dec_np = wl.f32_to_bf16_bits(rng.standard_normal((cfg.B, cfg.H, cfg.d)).astype(np.float32))
+        log(f"[bench] generated inputs in {time.time() - t0:.1f}s")
+        bf = cfg.x_dtype == wl.BF16
+        self.x = harness.to_dev(self.enc_np["x"], bf)
+        self.q_cls = harness.to_dev(self.enc_np["q_cls"], bf)
+        self.k_cls = harness.to_dev(self.enc_np["k_cls"], bf)
+        self.q_txt = harness.to_dev(self.pre_np["q_txt"], True)
+        self.k = harness.to_dev(self.pre_np["k"], True)
+        self.v = harness.to_dev(self.pre_np["v"], True)
+        self.hidden = harness.to_dev(self.pre_np["hidden"], True)
+        self.q_dec = harness.to_dev(self.q_dec_np, True)
+        B, M, N, H, d = cfg.B, cfg.M, cfg.N, cfg.H, cfg.d
+        self.R = PREFILL_BUDGET
+        self.Lcap = self.R + N
+        self.decode_budget = DECODE_VISION_BUDGET + N
+        i32, u8, f32 = torch.int32, torch.uint8, torch.float32
+        z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=dev)
+        self.enc_out = {
+            "out_x": torch.zeros_like(self.x), "out_index": z((B, M), i32), "out_mass": z((B, M), f32),
+            "out_is_key": z((B, M), u8), "out_valid": z((B, M), u8), "out_count": z((B,), i32),
+            "key_index": z((B, cfg.key_budget), i32), "a_cls": None, "window_sim": None,
+        }
+        self.pre_out = {
+            "hidden_out": z((B, self.Lcap, cfg.C), torch.bfloat16), "k_out": z((B, self.Lcap, H, d), torch.bfloat16),
+            "v_out": z((B, self.Lcap, H, d), torch.bfloat16), "kept_index": z((B, self.R), i32),
+            "kept_count": z((B,), i32), "out_len": z((B,), i32), "out_protect": z((B, self.Lcap), u8),
+            "out_ids": z((B, self.Lcap), i32), "score_global": None, "score_indiv": None,
+        }
+        self.acc = z((B, self.Lcap), f32)
+        self.enc_ws = md.encode_workspace(B, cfg.T, cfg.Hg, cfg.Wg, cfg.Hc, cfg.kt, cfg.kh, cfg.kw)
+        self.pre_ws = md.prefill_workspace(B, M, N, H, self.R)
+        self.dec_ws = md.decode_workspace(B, self.Lcap, H)
+        self.scale = 1.0 / float(np.sqrt(d))
+        self.gamma, self.alpha = 1.0 / M, 2.0 / (M + N)
+
+    def encode(self):
+        c = self.cfg
+        self.md.mustdrop_encode_merge(self.x, self.q_cls, self.k_cls, None, None, c.T, c.Hg, c.Wg, c.kt, c.kh, c.kw,
+                                      BENCH_TAU, c.key_budget, out=self.enc_out, workspace=self.enc_ws)
+
+    def prefill(self):
+        c = self.cfg
+        self.md.mustdrop_prefill_filter(self.q_txt, self.k, self.v, self.hidden, self.enc_out["out_valid"], None,
+                                        self.enc_out["out_is_key"], c.M, self.scale, self.md.FILTER_BUDGET, self.R,
+                                        self.gamma, self.alpha, Rcap=self.R, out=self.pre_out, workspace=self.pre_ws)
+
+    def decode(self):
+        # decay 0: the running score is overwritten, so the step is idempotent across benchmark iterations
+        o = self.pre_out
+        self.md.mustdrop_decode_evict(self.q_dec, o["k_out"], o["v_out"], self.acc, o["out_ids"], o["out_protect"],
+                                      o["out_len"], self.scale, 0.0, self.decode_budget, workspace=self.dec_ws)
+
+    def step(self):
+        self.encode()
+        self.prefill()
+        self.decode()
+
+
+def timed(torch, fn, iters):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / iters
+
+
+def kernel_bytes(cfg, pipe, counts):
+    """Algorithmic bytes per launch of every kernel of the step (what the method itself must move)."""
+    B, M, N, H, d, C, D = cfg.B, cfg.M, cfg.N, cfg.H, cfg.d, cfg.C, cfg.D
+    e = 2 if cfg.x_dtype == wl.BF16 else 4
+    L = M + N
+    surv = counts["encode_survivors"]
+    rows = counts["prefill_rows"]
+    dec_len = counts["decode_entries"]
+    moves = counts["decode_moves"]
+    return {
+        "cls_logits": B * (M + 1) * D * e + B * (M + 1) * cfg.Hc * 4,
+        "window_sim": B * M * D * e,
+        "encode_decide": B * (M + 1) * cfg.Hc * 4 + B * M * 16,
+        "encode_emit": B * M * D * e + surv * D * e,
+        "prefill_rowstats": B * (L + N) * H * d * 2,
+        "prefill_colscore": B * (M + N) * H * d * 2,
+        "prefill_select": B * M * 16,
+        "prefill_compact": 2 * rows * (C + 2 * H * d) * 2,
+        "decode_logits": dec_len * H * d * 2 + dec_len * H * 4,
+        "decode_select": 3 * dec_len * H * 4,
+        "decode_move": 2 * moves * 2 * H * d * 2,
+    }
+
+
+def decode_loop_cfg5(torch, md, harness, steps):
+    """Decode-stage workload proper: batch 64, 4096-entry cache, 256 steps, budget 1024."""
+    cfg = wl.CONFIGS[5]
+    steps = min(steps, cfg.steps)
+    t0 = time.time()
+    t = wl.decode_inputs(cfg, steps=steps)
+    log(f"[bench] generated decode workload in {time.time() - t0:.1f}s")
+    B, Lcap, H, d = cfg.B, t["Lcap"], cfg.H, cfg.d
+    kc, vc = harness.to_dev(t["k_cache"], True), harness.to_dev(t["v_cache"], True)
+    qs, kn, vn = (harness.to_dev(t[n], True) for n in ("q_steps", "k_new", "v_new"))
+    prot0 = harness.to_dev(t["protect"])
+    del t
+    acc = torch.zeros((B, Lcap), dtype=torch.float32, device="cuda")
+    ids = torch.arange(Lcap, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+    protect = prot0.clone()
+    length = torch.full((B,), cfg.L0, dtype=torch.int32, device="cuda")
+    ws = md.decode_workspace(B, Lcap, H)
+    scale = 1.0 / float(np.sqrt(d))
+    # untimed warm-up call on a scratch state (no eviction: huge budget) to load the code objects
+    md.mustdrop_decode_evict(qs[0], kc, vc, acc.clone(), ids.clone(), protect.clone(), length.clone(), scale, 1.0,
+                             1 << 30, workspace=ws)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    md.mustdrop_decode_evict(qs[0], kc, vc, acc, ids, protect, length, scale, 1.0, cfg.decode_budget, workspace=ws)
+    ev[1].record()
+    for s in range(1, steps):
+        md.mustdrop_decode_append(kn[s], vn[s], kc, vc, acc, ids, protect, length, cfg.L0 + s, 1)
+        md.mustdrop_decode_evict(qs[s], kc, vc, acc, ids, protect, length, scale, 1.0, cfg.decode_budget, workspace=ws)
+    ev[2].record()
+    torch.cuda.synchronize()
+    total_ms = (time.perf_counter() - t0) * 1e3
+    first_ms = ev[0].elapsed_time(ev[1])
+    steady_ms = ev[1].elapsed_time(ev[2]) / max(steps - 1, 1)
+    entries = B * cfg.L0 + (steps - 1) * B * (cfg.decode_budget + 1)
+    assert int(length.min()) == cfg.decode_budget and int(length.max()) == cfg.decode_budget
+    steady_bytes = B * (cfg.decode_budget + 1) * H * d * 2
+    return {
+        "workload": cfg.name, "steps": steps, "entries_scored_per_s": entries / (total_ms * 1e-3),
+        "total_ms": total_ms, "first_step_ms": first_ms, "steady_us_per_step": steady_ms * 1e3,
+        "steady_k_read_GBps": steady_bytes / (steady_ms * 1e-3) / 1e9,
+        "first_step_k_read_GBps": B * cfg.L0 * H * d * 2 / (first_ms * 1e-3) / 1e9,
+    }
+
+
+def cpu_baseline(cfg, pipe, min_seconds=10.0):
+    """The oracle, as it stands, on this host: the same chained step on the full batch of 16."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    cores = min(os.cpu_count() or 1, 16, cfg.B)
+
+    def one(b):
+        e = {k: v[b:b + 1] for k, v in pipe.enc_np.items() if k != "ell"}
+        p = {k: v[b:b + 1] for k, v in pipe.pre_np.items()}
+        o1 = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
+                                 cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU, cfg.key_budget)
+        o2 = oracle.prefill_filter(p["q_txt"], p["k"], p["v"], p["hidden"], o1["out_valid"], None, o1["out_is_key"],
+                                   cfg.M, pipe.scale, oracle.FILTER_BUDGET, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
+        acc = np.zeros((1, pipe.Lcap), np.float32)
+        oracle.decode_evict(pipe.q_dec_np[b:b + 1], o2["k_out"], o2["v_out"], acc, o2["out_ids"], o2["out_protect"],
+                            o2["out_len"], pipe.scale, 0.0, pipe.decode_budget)
+        return o1, o2
+
+    oracle.lib()
+    reps, t0 = 0, time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:        # ctypes releases the GIL: samples run in parallel
+        while True:
+            list(ex.map(one, range(cfg.B)))
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= min_seconds or reps >= 20:
+                break
+    return {"value": reps * cfg.B * cfg.M / dt, "unit": "vision tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"the full batch of {cfg.B} samples through all three oracle stages, {reps} repetitions, "
+                      f"{dt:.1f}s, one thread per sample"}
+
+
+def parity_check(cfg, pipe, harness):
+    """Last step's GPU outputs against the oracle on the full batch (same rules as the GPU tests)."""
+    import oracle
+    from parity import check_encode, check_prefill
+    g1 = harness.outputs_to_host(pipe.enc_out)
+    e = pipe.enc_np
+    o1 = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
+                             cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU, cfg.key_budget)
+    # the timed step does not ask for the optional score outputs: rerun once with them for the margin rule
+    gs = harness.encode_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
+                               cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU, cfg.key_budget)
+    assert np.array_equal(gs["out_count"], g1["out_count"]) and np.array_equal(gs["key_index"], g1["key_index"])
+    for b in range(cfg.B):                      # rows beyond out_count are never written: compare the live part
+        n = int(g1["out_count"][b])
+        for name in ("out_index", "out_is_key", "out_x"):
+            assert np.array_equal(gs[name][b, :n], g1[name][b, :n]), f"timed step and checked step differ in {name}"
+    s1 = check_encode(gs, o1, e["x"], cfg.x_dtype, None, cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU,
+                      cfg.key_budget)
+    p = pipe.pre_np
+    vv, kk = g1["out_valid"], g1["out_is_key"]
+    gp = harness.prefill_on_gpu(p, cfg.M, vv, None, kk, pipe.scale, 0, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
+    o2 = oracle.prefill_filter(p["q_txt"], p["k"], p["v"], p["hidden"], vv, None, kk, cfg.M, pipe.scale, 0, pipe.R,
+                               pipe.gamma, pipe.alpha, pipe.R)
+    s2 = check_prefill(gp, o2, p, cfg.M, vv, kk, 0, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
+    return {"encode": s1, "prefill": s2, "status": "pass"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-decode-loop", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every stage is per-sample independent; multi-GPU is batch "
+              "sharding with no exchange and is not built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    import paper_2411_10803_amd as md
+    from paper_2411_10803_amd import binding, harness
+    md.library()
+    cfg = wl.CONFIGS[2]
+    pipe = Cfg2Pipeline(cfg, torch, md, harness)
+
+    for _ in range(args.warmup):
+        pipe.step()
+    ms_per_step = timed(torch, pipe.step, args.steps)
+    stage_ms = {"encode": timed(torch, pipe.encode, args.steps), "prefill": timed(torch, pipe.prefill, args.steps)}
+    pipe.prefill()
+    stage_ms["decode"] = timed(torch, lambda: (pipe.prefill(), pipe.decode()), args.steps) - stage_ms["prefill"]
+
+    # per-kernel durations with HIP events on the launch stream, over the same steps
+    binding.profile_start()
+    for _ in range(args.steps):
+        pipe.step()
+    prof = binding.profile_stop()
+    torch.cuda.synchronize()
+
+    out_count = pipe.enc_out["out_count"].cpu().numpy()
+    kept = np.minimum(pipe.pre_out["kept_count"].cpu().numpy(), pipe.R)
+    pipe.prefill()
+    torch.cuda.synchronize()
+    dec_len = pipe.pre_out["out_len"].cpu().numpy().copy()
+    pipe.decode()
+    torch.cuda.synchronize()
+    dec_after = pipe.pre_out["out_len"].cpu().numpy()
+    counts = {"encode_survivors": int(out_count.sum()), "prefill_rows": int((kept + cfg.N).sum()),
+              "decode_entries": int(dec_len.sum()), "decode_moves": int(np.minimum(dec_after, dec_len - dec_after).sum())}
+    kb = kernel_bytes(cfg, pipe, counts)
+    kernels = {}
+    for name, r in prof.items():
+        us = r["ms"] * 1e3 / max(r["calls"], 1)
+        gbs = kb.get(name, 0) / (us * 1e-6) / 1e9 if us > 0 else 0.0
+        kernels[name] = {"avg_us": round(us, 2), "calls": r["calls"], "algorithmic_MB": round(kb.get(name, 0) / 1e6, 3),
+                         "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    dominant = max(kernels, key=lambda n: kernels[n]["avg_us"])
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"], "traffic": None,
+                "avg_us": kernels[dominant]["avg_us"]}
+
+    tokens = cfg.B * cfg.M
+    result = {
+        "metric": "vision tokens processed/sec per pipeline stage; achieved % of HBM/MFMA roofline",
+        "value": tokens / (ms_per_step * 1e-3), "unit": "vision tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.B, "vision_tokens": cfg.M, "text_tokens": cfg.N,
+                   "vision_dim": cfg.D, "heads": cfg.H, "head_dim": cfg.d, "hidden": cfg.C, "window": "1x2x2",
+                   "tau": BENCH_TAU, "key_budget": cfg.key_budget, "prefill_budget": pipe.R,
+                   "decode_budget": pipe.decode_budget, "step": "encode_merge -> prefill_filter -> decode_evict"},
+        "stages": {s: {"ms": round(m, 4), "vision_tokens_per_s": tokens / (m * 1e-3)} for s, m in stage_ms.items()},
+        "counts": counts,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_decode_loop:
+        result["decode_loop"] = decode_loop_cfg5(torch, md, harness, args.decode_steps)
+    if not args.no_parity:
+        result["parity"] = parity_check(cfg, pipe, harness)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, pipe)
+        result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

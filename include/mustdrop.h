@@ -121,6 +121,8 @@ int mustdrop_encode_merge(
  *   kept_count [B]   number of vision tokens the rule keeps; if it exceeds Rcap only the first
  *                    Rcap (lowest indices) are stored -- an overflow the caller can detect
  *   out_len    [B] or NULL   = min(kept_count, Rcap) + txt_len: live rows of the outputs
+ *   out_ids    [B, Rcap+N] i32 or NULL: original sequence position of every output row (vision index j,
+ *              or Mv+i for text row i; -1 for rows that are not live) -- usable as the decode stage's ids
  *   out_protect[B, Rcap+N] u8 or NULL: 1 for key tokens and text rows (the decode stage's protect flags)
  *   score_global, score_indiv [B, Mv] f32 or NULL: V_j and I_j (0 for invalid tokens)
  *
@@ -135,7 +137,7 @@ int mustdrop_prefill_filter(
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,
     void* hidden_out, void* k_out, void* v_out,
-    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect,
+    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
     float* score_global, float* score_indiv,
     void* workspace, size_t workspace_bytes, void* stream);
 
@@ -156,7 +158,7 @@ int mustdrop_prefill_filter(
  *   evicted_ids [B, Lcap] or NULL: ids of the evicted entries in ascending (pre-compaction) slot order
  *   evicted_count [B] or NULL
  *
- * Limits: d*2 a multiple of 16 bytes, H*d*2 <= 16384*... (row of one entry) a multiple of 512 bytes.
+ * Limits: d a power of two in [8, 512]; H divides 1024.
  */
 size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H);
 
@@ -177,6 +179,17 @@ int mustdrop_decode_append(
     void* k_cache, void* v_cache,
     float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
     int B, int Lcap, int H, int d, int32_t new_id, int protect_new, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Benchmarking aid (not part of the method): per-kernel timing with HIP events.
+ * Between mustdrop_profile_start() and mustdrop_profile_stop() every kernel the library launches
+ * is bracketed by an event pair recorded on the launch stream.  _stop waits for the events,
+ * destroys them and reports, per distinct kernel name, the summed milliseconds and the number of
+ * launches: names is a host array of cap*64 chars, total_ms / calls host arrays of cap entries,
+ * *n_out the number of names filled.  Host pointers.  Not thread-safe; do not use while another
+ * thread is inside the library. */
+int mustdrop_profile_start(void);
+int mustdrop_profile_stop(char* names, float* total_ms, int* calls, int cap, int* n_out);
 
 #ifdef __cplusplus
 }

@@ -102,6 +102,7 @@ def prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_
         "kept_count": np.zeros((B,), dtype=np.int32),
         "out_len": np.zeros((B,), dtype=np.int32),
         "out_protect": np.zeros((B, Rcap + N), dtype=np.uint8),
+        "out_ids": np.full((B, Rcap + N), -1, dtype=np.int32),
         "score_global": np.zeros((B, Mv), dtype=np.float64),
         "score_indiv": np.zeros((B, Mv), dtype=np.float64),
     }
@@ -111,7 +112,7 @@ def prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_
         C.c_float(softmax_scale), C.c_int(mode), C.c_int(budget), C.c_float(gamma), C.c_float(alpha),
         C.c_int(Rcap),
         _p(out["hidden_out"]), _p(out["k_out"]), _p(out["v_out"]),
-        _p(out["kept_index"]), _p(out["kept_count"]), _p(out["out_len"]), _p(out["out_protect"]),
+        _p(out["kept_index"]), _p(out["kept_count"]), _p(out["out_len"]), _p(out["out_protect"]), _p(out["out_ids"]),
         _p(out["score_global"]), _p(out["score_indiv"]))
     if rc != 0:
         raise ValueError(f"mustdrop_prefill_filter_ref: error {rc}")

@@ -252,7 +252,7 @@ int mustdrop_prefill_filter_ref(
     int Rcap,
     uint16_t* hidden_out, uint16_t* k_out, uint16_t* v_out,
     int32_t* kept_index, int32_t* kept_count,
-    int32_t* out_len, uint8_t* out_protect,
+    int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
     double* score_global, double* score_indiv)
 {
     if (B <= 0 || Mv <= 0 || N <= 0 || H <= 0 || d <= 0 || C <= 0 || Rcap <= 0) return REF_EINVAL;
@@ -353,6 +353,7 @@ int mustdrop_prefill_filter_ref(
             memcpy(v_out + dst * kv_row, v + src * kv_row, kv_row * 2);
             kept_index[(size_t)b * Rcap + o] = j;
             if (out_protect) out_protect[(size_t)b * (Rcap + N) + o] = (uint8_t)(kb && kb[j]);
+            if (out_ids) out_ids[(size_t)b * (Rcap + N) + o] = j;
             ++o;
         }
         for (int i = 0; i < tl; ++i) {
@@ -362,7 +363,9 @@ int mustdrop_prefill_filter_ref(
             memcpy(k_out + dst * kv_row, k + src * kv_row, kv_row * 2);
             memcpy(v_out + dst * kv_row, v + src * kv_row, kv_row * 2);
             if (out_protect) out_protect[(size_t)b * (Rcap + N) + o + i] = 1;
+            if (out_ids) out_ids[(size_t)b * (Rcap + N) + o + i] = Mv + i;
         }
+        if (out_ids) for (int r = o + tl; r < Rcap + N; ++r) out_ids[(size_t)b * (Rcap + N) + r] = -1;
         if (out_len) out_len[b] = o + tl;
     }
     free(a); free(lg); free(Vj); free(Ij); free(keep); free(order);

@@ -17,6 +17,7 @@ EXPORTS = [
     "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge",
     "mustdrop_prefill_filter_workspace_bytes", "mustdrop_prefill_filter",
     "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append",
+    "mustdrop_profile_start", "mustdrop_profile_stop",
 ]
 
 
@@ -156,6 +157,7 @@ def mustdrop_prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv,
             "kept_count": torch.zeros((B,), dtype=torch.int32, device=dev),
             "out_len": torch.zeros((B,), dtype=torch.int32, device=dev),
             "out_protect": torch.zeros((B, Rcap + N), dtype=torch.uint8, device=dev),
+            "out_ids": torch.full((B, Rcap + N), -1, dtype=torch.int32, device=dev),
             "score_global": torch.zeros((B, Mv), dtype=torch.float32, device=dev) if want_scores else None,
             "score_indiv": torch.zeros((B, Mv), dtype=torch.float32, device=dev) if want_scores else None,
         }
@@ -168,7 +170,7 @@ def mustdrop_prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv,
         C.c_float(softmax_scale), C.c_int(mode), C.c_int(budget), C.c_float(gamma), C.c_float(alpha),
         C.c_int(Rcap),
         _ptr(out["hidden_out"]), _ptr(out["k_out"]), _ptr(out["v_out"]),
-        _ptr(out["kept_index"]), _ptr(out["kept_count"]), _ptr(out.get("out_len")), _ptr(out.get("out_protect")),
+        _ptr(out["kept_index"]), _ptr(out["kept_count"]), _ptr(out.get("out_len")), _ptr(out.get("out_protect")), _ptr(out.get("out_ids")),
         _ptr(out.get("score_global")), _ptr(out.get("score_indiv")),
         _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
     return out
@@ -197,3 +199,22 @@ def mustdrop_decode_append(k_new, v_new, k_cache, v_cache, acc, ids, protect, le
         _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
         C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d), C.c_int(int(new_id)), C.c_int(int(protect_new)),
         _stream(stream)))
+
+
+def profile_start():
+    """Benchmarking aid: bracket every kernel launch with HIP events until profile_stop()."""
+    _check(library().mustdrop_profile_start())
+
+
+def profile_stop(cap: int = 64) -> Dict[str, Dict[str, float]]:
+    """Returns {kernel name: {"ms": summed milliseconds, "calls": launches}}."""
+    names = C.create_string_buffer(64 * cap)
+    ms = (C.c_float * cap)()
+    calls = (C.c_int * cap)()
+    n = C.c_int(0)
+    _check(library().mustdrop_profile_stop(names, ms, calls, C.c_int(cap), C.byref(n)))
+    out = {}
+    for i in range(n.value):
+        nm = names.raw[64 * i:64 * (i + 1)].split(b"\0", 1)[0].decode()
+        out[nm] = {"ms": float(ms[i]), "calls": int(calls[i])}
+    return out

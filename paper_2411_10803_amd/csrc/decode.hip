@@ -300,20 +300,20 @@ extern "C" int mustdrop_decode_evict(
     const uint16_t* qp = static_cast<const uint16_t*>(q);
     const uint16_t* kp = static_cast<const uint16_t*>(k_cache);
     switch (d / 8) {
-        case 1: decode_logits_kernel<1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-        case 2: decode_logits_kernel<2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-        case 4: decode_logits_kernel<4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-        case 8: decode_logits_kernel<8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-        case 16: decode_logits_kernel<16><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-        case 32: decode_logits_kernel<32><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-        default: decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+        case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
     }
     const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);
-    decode_select_kernel<<<B, 1024, lds, st>>>(p, w.logits, decay, budget, acc, ids, protect, len,
-                                              w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
+    MD_LAUNCH("decode_select", st, (decode_select_kernel<<<B, 1024, lds, st>>>(
+        p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count)));
     dim3 g3(32, B);
-    decode_move_kernel<<<g3, 256, 0, st>>>(p, w.holes, w.movers, w.n_move,
-                                          static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache));
+    MD_LAUNCH("decode_move", st, (decode_move_kernel<<<g3, 256, 0, st>>>(
+        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache))));
     return check_launch("decode_evict");
 }
 
@@ -331,8 +331,9 @@ extern "C" int mustdrop_decode_append(
     if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
         return fail(MD_EALIGN, "decode_append: tensors must be 16-byte aligned");
     DecodeDims p{B, Lcap, H, d};
-    decode_append_kernel<<<B, 256, 0, static_cast<hipStream_t>(stream)>>>(
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MD_LAUNCH("decode_append", st, (decode_append_kernel<<<B, 256, 0, st>>>(
         p, static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
-        static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new);
+        static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new)));
     return check_launch("decode_append");
 }

@@ -404,10 +404,10 @@ EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
 template <bool BF>
 void launch_window_sim(int ws, dim3 grid, hipStream_t st, const void* x, const uint8_t* valid,
                        const EncodeDims& p, float* sim) {
-    if (ws <= 2) window_sim_kernel<2, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
-    else if (ws <= 4) window_sim_kernel<4, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
-    else if (ws <= 8) window_sim_kernel<8, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
-    else window_sim_kernel<16, BF><<<grid, 256, 0, st>>>(x, valid, p, sim);
+    if (ws <= 2) MD_LAUNCH("window_sim", st, (window_sim_kernel<2, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
+    else if (ws <= 4) MD_LAUNCH("window_sim", st, (window_sim_kernel<4, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
+    else if (ws <= 8) MD_LAUNCH("window_sim", st, (window_sim_kernel<8, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
+    else MD_LAUNCH("window_sim", st, (window_sim_kernel<16, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
 }
 
 }  // namespace
@@ -480,17 +480,16 @@ extern "C" int mustdrop_encode_merge(
     if (key_budget > 0) {
         const long rows = (long)B * (M + 1);
         dim3 grid((unsigned)((rows + 3) / 4));
-        if (qk_dtype == MD_BF16) cls_logits_kernel<true><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits);
-        else cls_logits_kernel<false><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits);
+        if (qk_dtype == MD_BF16) MD_LAUNCH("cls_logits", st, (cls_logits_kernel<true><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits)));
+        else MD_LAUNCH("cls_logits", st, (cls_logits_kernel<false><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits)));
     }
     dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
     if (x_dtype == MD_BF16) launch_window_sim<true>(ws, wgrid, st, x, valid, p, wsp.sim);
     else launch_window_sim<false>(ws, wgrid, st, x, valid, p, wsp.sim);
-    encode_decide_kernel<<<B, 1024, 0, st>>>(p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget,
-                                             wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
-                                             out_index, out_mass, out_is_key, out_valid, out_count, key_index,
-                                             a_cls_out, window_sim_out);
-    if (x_dtype == MD_BF16) encode_emit_kernel<true><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
-    else encode_emit_kernel<false><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
+    MD_LAUNCH("encode_decide", st, (encode_decide_kernel<<<B, 1024, 0, st>>>(
+        p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
+        out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)));
+    if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x)));
+    else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x)));
     return check_launch("encode_merge");
 }

@@ -45,4 +45,17 @@ inline int check_launch(const char* what) {
 
 inline size_t elt_size(int dtype) { return dtype == MD_BF16 ? 2 : 4; }
 
+// Optional per-kernel timing (mustdrop_profile_start / _stop): when enabled, every launch is
+// bracketed by a pair of HIP events on the launch stream.  Off by default: two branches per launch.
+bool profiling();
+void profile_mark_begin(const char* kernel_name, hipStream_t st);
+void profile_mark_end(hipStream_t st);
+
+#define MD_LAUNCH(name, st, ...)                                   \
+    do {                                                           \
+        if (md::profiling()) md::profile_mark_begin(name, st);     \
+        __VA_ARGS__;                                               \
+        if (md::profiling()) md::profile_mark_end(st);             \
+    } while (0)
+
 }  // namespace md

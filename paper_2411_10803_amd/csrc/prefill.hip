@@ -399,8 +399,8 @@ int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t s
                   const uint8_t* vis_valid, const int32_t* txt_len, float scale_log2e) {
     constexpr int NW = 8;
     dim3 g1(p.nch, p.H, p.B);
-    prefill_rowstats_kernel<NB, KS><<<g1, 256, 0, st>>>(
-        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, p, scale_log2e, w.partial);
+    MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NB, KS><<<g1, 256, 0, st>>>(
+        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, p, scale_log2e, w.partial)));
     const size_t lds = sizeof(float) * ((size_t)2 * p.H * 32 * NB + 32 * (32 * NB + 1) + 2 * (2 * NW * 32));
     auto kern = prefill_colscore_kernel<NB, KS, NW>;
     if (lds > 48 * 1024) {
@@ -408,8 +408,9 @@ int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t s
         if (e != hipSuccess) return fail(MD_EHIP, "prefill_filter: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
     }
     dim3 g2((p.Mv + 31) / 32, p.B);
-    kern<<<g2, 64 * NW, lds, st>>>(static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k),
-                                  vis_valid, txt_len, w.partial, p, scale_log2e, w.V, w.I);
+    MD_LAUNCH("prefill_colscore", st, (kern<<<g2, 64 * NW, lds, st>>>(
+        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, w.partial, p,
+        scale_log2e, w.V, w.I)));
     return MD_OK;
 }
 
@@ -430,7 +431,7 @@ extern "C" int mustdrop_prefill_filter(
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,
     void* hidden_out, void* k_out, void* v_out,
-    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect,
+    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
     float* score_global, float* score_indiv,
     void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -494,12 +495,13 @@ extern "C" int mustdrop_prefill_filter(
         else rc = launch_scores<4, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
     }
     if (rc != MD_OK) return rc;
-    prefill_select_kernel<<<B, 1024, 0, st>>>(p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,
-                                             w.score, w.src_row, kept_index, kept_count, out_len, out_protect,
-                                             score_global, score_indiv);
+    int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
+    MD_LAUNCH("prefill_select", st, (prefill_select_kernel<<<B, 1024, 0, st>>>(
+        p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,
+        w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)));
     dim3 gc(Rcap + N, B);
-    prefill_compact_kernel<<<gc, 256, 0, st>>>(p, w.src_row,
+    MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel<<<gc, 256, 0, st>>>(p, src_row,
         static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
-        static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out));
+        static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out))));
     return check_launch("prefill_filter");
 }

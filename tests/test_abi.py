@@ -1,0 +1,124 @@
+"""The C ABI on a machine without a GPU: the library loads, exports every symbol the header
+declares, sizes workspaces with pure host arithmetic, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2411_10803_amd as md
+    return md.library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mustdrop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mustdrop_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    syms = declared_symbols()
+    assert {"mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict"} <= set(syms)
+    for s in syms:
+        assert hasattr(lib, s), f"{s} is declared in mustdrop.h but not exported"
+    from paper_2411_10803_amd import binding
+    assert sorted(binding.EXPORTS) == syms
+
+
+def test_workspace_sizes_are_host_arithmetic(lib):
+    a = lib.mustdrop_encode_merge_workspace_bytes(16, 1, 24, 24, 16, 1, 2, 2)
+    b = lib.mustdrop_encode_merge_workspace_bytes(32, 1, 24, 24, 16, 1, 2, 2)
+    assert 0 < a < b and a % 256 == 0
+    assert lib.mustdrop_encode_merge_workspace_bytes(0, 1, 24, 24, 16, 1, 2, 2) == 0
+    assert lib.mustdrop_prefill_filter_workspace_bytes(16, 576, 64, 32, 192) > 0
+    assert lib.mustdrop_decode_evict_workspace_bytes(64, 4352, 32) >= 64 * 4352 * 32 * 4
+
+
+F = C.c_float
+P = C.c_void_p
+X = P(0x10000)        # a non-null, 16-byte aligned fake device pointer: never dereferenced on the host
+
+
+def encode(lib, **kw):
+    a = dict(x=X, x_dtype=1, q=X, k=X, qk_dtype=1, mass=None, valid=None, B=2, T=1, Hg=24, Wg=24, D=1024, Hc=16, dc=64,
+             kt=1, kh=2, kw=2, tau=0.85, key_budget=32, out_x=P(0x9000000), oi=X, om=X, ok=X, ov=X, oc=X, ki=X,
+             ws=P(0x20000000), wsb=1 << 30)
+    a.update(kw)
+    return lib.mustdrop_encode_merge(a["x"], a["x_dtype"], a["q"], a["k"], a["qk_dtype"], a["mass"], a["valid"],
+                                     a["B"], a["T"], a["Hg"], a["Wg"], a["D"], a["Hc"], a["dc"], a["kt"], a["kh"], a["kw"],
+                                     F(a["tau"]), a["key_budget"], a["out_x"], a["oi"], a["om"], a["ok"], a["ov"], a["oc"],
+                                     a["ki"], None, None, a["ws"], C.c_size_t(a["wsb"]), None)
+
+
+def test_encode_argument_errors(lib):
+    E = dict(OK=0, EINVAL=1, ESHAPE=2, EALIGN=3, EALIAS=4, EWORKSPACE=5, EDTYPE=6)
+    assert encode(lib, x=None) == E["EINVAL"] and b"required" in lib.mustdrop_last_error()
+    assert encode(lib, B=0) == E["EINVAL"]
+    assert encode(lib, x_dtype=7) == E["EDTYPE"]
+    assert encode(lib, Hg=25) == E["ESHAPE"] and b"divisible" in lib.mustdrop_last_error()
+    assert encode(lib, kh=8, kw=3, Hg=24, Wg=24) == E["ESHAPE"]                 # 24-token window > limit
+    assert encode(lib, key_budget=-1) == E["EINVAL"]
+    assert encode(lib, key_budget=577) == E["EINVAL"]
+    assert encode(lib, q=None) == E["EINVAL"]
+    assert encode(lib, Hc=8) == E["ESHAPE"]                                      # Hc*dc != D
+    assert encode(lib, Hc=1024 // 48, dc=48, D=1008) == E["ESHAPE"]             # dc not a power of two
+    assert encode(lib, D=1020, Hc=15, dc=68) in (E["EALIGN"], E["ESHAPE"])
+    assert encode(lib, x=P(0x10008)) == E["EALIGN"]
+    assert encode(lib, out_x=X) == E["EALIAS"]
+    assert encode(lib, ws=None) == E["EWORKSPACE"]
+    assert encode(lib, wsb=1024) == E["EWORKSPACE"] and b"needed" in lib.mustdrop_last_error()
+    assert encode(lib, ws=P(0x20000010)) == E["EALIGN"]
+    assert encode(lib, tau=float("nan")) == E["EINVAL"]
+    assert encode(lib, key_budget=0) == E["EINVAL"]                              # q/k given without a key budget
+
+
+def prefill(lib, **kw):
+    a = dict(q=P(0x1000000), k=P(0x2000000), v=P(0x8000000), h=P(0x10000000), B=1, Mv=576, N=64, H=32, d=128, C=4096,
+             scale=0.088, mode=0, budget=192, gamma=1 / 576, alpha=2 / 640, Rcap=192,
+             ho=P(0x20000000), ko=P(0x28000000), vo=P(0x30000000), ki=X, kc=X, ws=P(0x40000000), wsb=1 << 30)
+    a.update(kw)
+    return lib.mustdrop_prefill_filter(a["q"], a["k"], a["v"], a["h"], None, None, None, a["B"], a["Mv"], a["N"], a["H"],
+                                       a["d"], a["C"], F(a["scale"]), a["mode"], a["budget"], F(a["gamma"]), F(a["alpha"]),
+                                       a["Rcap"], a["ho"], a["ko"], a["vo"], a["ki"], a["kc"], None, None, None, None, None,
+                                       a["ws"], C.c_size_t(a["wsb"]), None)
+
+
+def test_prefill_argument_errors(lib):
+    assert prefill(lib, k=None) == 1
+    assert prefill(lib, mode=3) == 6
+    assert prefill(lib, d=96) == 2
+    assert prefill(lib, N=129) == 2
+    assert prefill(lib, C=4100) == 3
+    assert prefill(lib, budget=-1) == 1
+    assert prefill(lib, gamma=0.0) == 1 and b"gamma" in lib.mustdrop_last_error()
+    assert prefill(lib, Rcap=100) == 1
+    assert prefill(lib, ko=P(0x2000000)) == 4
+    assert prefill(lib, wsb=16) == 5
+    assert prefill(lib, q=P(0x1000004)) == 3
+
+
+def decode(lib, **kw):
+    a = dict(q=P(0x1000), k=P(0x10000000), v=P(0x80000000), B=2, Lcap=4096, H=32, d=128, budget=1024,
+             ws=P(0x100000000), wsb=1 << 30)
+    a.update(kw)
+    return lib.mustdrop_decode_evict(a["q"], a["k"], a["v"], X, X, X, X, a["B"], a["Lcap"], a["H"], a["d"],
+                                     F(0.088), F(1.0), a["budget"], None, None, a["ws"], C.c_size_t(a["wsb"]), None)
+
+
+def test_decode_argument_errors(lib):
+    assert decode(lib, q=None) == 1
+    assert decode(lib, d=96) == 2
+    assert decode(lib, H=48) == 2
+    assert decode(lib, budget=-5) == 1
+    assert decode(lib, v=P(0x10000000)) == 4
+    assert decode(lib, wsb=0) == 5
+    assert decode(lib, k=P(0x10000008)) == 3
+    rc = lib.mustdrop_decode_append(None, X, X, X, X, X, X, X, 2, 64, 32, 128, 5, 1, None)
+    assert rc == 1
+    rc = lib.mustdrop_decode_append(X, X, X, X, X, X, X, X, 2, 64, 32, 128, -1, 1, None)
+    assert rc == 1
