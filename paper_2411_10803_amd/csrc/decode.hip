@@ -21,7 +21,7 @@ constexpr float kLog2eD = 1.4426950408889634f;
 struct DecodeDims { int B, Lcap, H, d; };
 
 // logits[b][j][h] = scale * q[b][h] . k[b][j][h]      (token-major so an entry's H logits are contiguous)
-// LPH = lanes per head slice = d / 8.
+// LPH = lanes per head slice = d / 8.  Generic shape: walks an entry's row in 1 KiB pieces.
 template <int LPH>
 __global__ __launch_bounds__(256) void decode_logits_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
@@ -68,6 +68,64 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
 #pragma unroll
             for (int m = 1; m < LPH; m <<= 1) part += __shfl_xor(part, m, kWave);
             if (idx < nvec && (lane & (LPH - 1)) == 0) lb[(long)j * p.H + head] = part * scale;
+        }
+    }
+}
+
+__device__ __forceinline__ float dot8(const u32x4& a, const float (&qv)[8]) {
+    float s = qv[0] * bf16_lo(a.x);
+    s = fmaf(qv[1], bf16_hi(a.x), s);
+    s = fmaf(qv[2], bf16_lo(a.y), s);
+    s = fmaf(qv[3], bf16_hi(a.y), s);
+    s = fmaf(qv[4], bf16_lo(a.z), s);
+    s = fmaf(qv[5], bf16_hi(a.z), s);
+    s = fmaf(qv[6], bf16_lo(a.w), s);
+    s = fmaf(qv[7], bf16_hi(a.w), s);
+    return s;
+}
+
+// Streaming shape: an entry's row is NIT KiB (H*d*2 = NIT*1024 bytes).  A wave keeps the whole query
+// in registers and reads each entry's row in one go: NIT independent 16-byte loads per lane, every
+// load instruction covering 1 KiB of consecutive addresses.  Waves stride over the sample's entries.
+template <int LPH, int NIT>
+__global__ __launch_bounds__(256) void decode_logits_stream_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
+    DecodeDims p, float scale, float* __restrict__ logits)
+{
+    const int lane = lane_id();
+    const int b = blockIdx.y;
+    const int n = min(len[b], p.Lcap);
+    const int wave_global = blockIdx.x * 4 + wave_id();
+    const int nwaves = gridDim.x * 4;
+    if (wave_global >= n) return;
+    const int row = p.H * p.d;
+    const u32x4* qb = reinterpret_cast<const u32x4*>(q + (long)b * row);
+    const u32x4* kb = reinterpret_cast<const u32x4*>(k_cache + (long)b * p.Lcap * row);
+    float* lb = logits + (long)b * p.Lcap * p.H;
+
+    float qv[NIT][8];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const u32x4 w = qb[it * kWave + lane];
+        qv[it][0] = bf16_lo(w.x); qv[it][1] = bf16_hi(w.x); qv[it][2] = bf16_lo(w.y); qv[it][3] = bf16_hi(w.y);
+        qv[it][4] = bf16_lo(w.z); qv[it][5] = bf16_hi(w.z); qv[it][6] = bf16_lo(w.w); qv[it][7] = bf16_hi(w.w);
+    }
+    constexpr int HPI = kWave / LPH;                 // heads per load instruction
+    for (int j = wave_global; j < n; j += nwaves) {
+        const u32x4* kr = kb + (long)j * (row / 8);
+        u32x4 kv[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) kv[it] = kr[it * kWave + lane];
+        float part[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) part[it] = dot8(kv[it], qv[it]);
+#pragma unroll
+        for (int m = 1; m < LPH; m <<= 1)
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) part[it] += __shfl_xor(part[it], m, kWave);
+        if ((lane & (LPH - 1)) == 0) {
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) lb[(long)j * p.H + it * HPI + lane / LPH] = part[it] * scale;
         }
     }
 }
@@ -295,18 +353,37 @@ extern "C" int mustdrop_decode_evict(
 
     DecodeDims p{B, Lcap, H, d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int tpb = 32;
-    dim3 g1((Lcap + tpb - 1) / tpb, B);
     const uint16_t* qp = static_cast<const uint16_t*>(q);
     const uint16_t* kp = static_cast<const uint16_t*>(k_cache);
-    switch (d / 8) {
-        case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-        case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-        case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-        case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-        case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-        case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-        default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+    const int row_bytes = H * d * 2;
+    const int nit = row_bytes % 1024 == 0 ? row_bytes / 1024 : 0;
+    if (d == 128 && (nit == 1 || nit == 2 || nit == 4 || nit == 8)) {
+        // streaming shape: about 16 waves per CU in flight, each striding over its sample's entries
+        int blocks_x = (4096 + B - 1) / B;
+        const int max_x = (Lcap + 3) / 4;
+        if (blocks_x > max_x) blocks_x = max_x;
+        if (blocks_x < 1) blocks_x = 1;
+        dim3 g1(blocks_x, B);
+        switch (nit) {
+            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
+            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
+            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
+            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
+            default: break;
+        }
+    } else {
+        int tpb = (int)(((long)B * Lcap + 4095) / 4096);
+        tpb = tpb < 4 ? 4 : (tpb > 32 ? 32 : tpb);
+        dim3 g1((Lcap + tpb - 1) / tpb, B);
+        switch (d / 8) {
+            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+        }
     }
     const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);
     MD_LAUNCH("decode_select", st, (decode_select_kernel<<<B, 1024, lds, st>>>(

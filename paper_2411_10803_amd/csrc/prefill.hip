@@ -36,31 +36,63 @@ struct PrefillDims {
 // key row of accumulator register r in the 32x32 result tile
 __device__ __forceinline__ int tile_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-// Loads the 32x(16*KS) operand tile of `rows` consecutive rows starting at row0 (row stride in
-// elements), this lane's 8-element slices; rows >= nrows give zeros.
+// A 32-row operand tile (32 keys or 32 text rows of one head, 16*KS bf16 each) on its way from
+// global memory to MFMA fragments.  Global loads are coalesced: a row's head slice is CH = 2*KS
+// consecutive 16-byte chunks, 64/CH rows per load instruction.  The tile is then written to a
+// wave-private LDS buffer (row pitch padded by 16 bytes: conflict-free 128-bit reads) and read back
+// in fragment layout: lane (g = lane/32, r = lane%32) holds row r, chunks 2*ks+g, ks = 0..KS-1.
 template <int KS>
-__device__ __forceinline__ void load_frag(const uint16_t* base, long row_stride, int row0, int nrows, int lane,
-                                          bf16x8 (&f)[KS]) {
-    const int r = row0 + (lane & 31);
-    if (r < nrows) {
-        const uint16_t* p = base + (long)r * row_stride + 8 * (lane >> 5);
+struct OperandTile {
+    static constexpr int CH = 2 * KS;
+    static constexpr int ROWS_PER_LOAD = kWave / CH;
+    static constexpr int PITCH = CH * 16 + 16;
+    static constexpr int BYTES = 32 * PITCH;
+
+    // rows row0..row0+31 of a matrix whose rows are `row_stride` elements apart; rows >= nrows read as zero
+    __device__ static __forceinline__ void gload(const uint16_t* base, long row_stride, int row0, int nrows, int lane,
+                                                 u32x4 (&st)[KS]) {
+        const int chunk = lane % CH, sub = lane / CH;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
-    } else {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) f[ks][e] = (__bf16)0.0f;
+        for (int t = 0; t < KS; ++t) {
+            const int r = row0 + t * ROWS_PER_LOAD + sub;
+            if (r < nrows) st[t] = *reinterpret_cast<const u32x4*>(base + (long)r * row_stride + chunk * 8);
+            else st[t] = u32x4{0u, 0u, 0u, 0u};
+        }
     }
+    __device__ static __forceinline__ void to_lds(char* tile, int lane, const u32x4 (&st)[KS]) {
+        const int chunk = lane % CH, sub = lane / CH;
+#pragma unroll
+        for (int t = 0; t < KS; ++t)
+            *reinterpret_cast<u32x4*>(tile + (t * ROWS_PER_LOAD + sub) * PITCH + chunk * 16) = st[t];
+    }
+    __device__ static __forceinline__ void frags(const char* tile, int lane, bf16x8 (&f)[KS]) {
+        const char* p = tile + (lane & 31) * PITCH + (lane >> 5) * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) f[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 32);
+    }
+};
+
+// LDS traffic between lanes of one wave: LDS operations of a wave execute in order, the fence keeps
+// the compiler from moving the reads above the writes.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // ---------------------------------------------------------------------------------------------
+// Sweep 1: row statistics.  Block = (key chunk, head, sample), 4 waves; every wave walks its share
+// of the chunk's 32-key tiles with the next tile's global loads in flight during the MFMAs.
+// Chunk 0 also stores the text-query fragments in fragment-major order (qfrag) so that sweep 2
+// reads them with fully coalesced 16-byte loads.
 template <int NB, int KS>
 __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const uint16_t* __restrict__ q_txt, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, PrefillDims p, float scale_log2e,
-    float2* __restrict__ partial)
+    float2* __restrict__ partial, bf16x8* __restrict__ qfrag)
 {
+    using Tile = OperandTile<KS>;
+    __shared__ __attribute__((aligned(16))) char s_tile[4][Tile::BYTES];
     __shared__ float s_m[4][32 * NB], s_z[4][32 * NB];
     const int lane = lane_id(), wv = wave_id();
     const int ch = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -68,20 +100,42 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const uint16_t* kb = k + ((long)b * p.L * p.H + h) * p.d;
     const uint16_t* qb = q_txt + ((long)b * p.N * p.H + h) * p.d;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
+    char* tile = s_tile[wv];
 
+    const int c0 = ch * p.chunk;
+    const int c1 = min(c0 + p.chunk, p.L);
+    int j0 = c0 + 32 * wv;
+    u32x4 st[KS];
+    if (j0 < c1) Tile::gload(kb, tok_stride, j0, p.L, lane, st);
+
+    // text-query fragments of this head: through the same LDS tile, one 32-row block at a time
     bf16x8 qf[NB][KS];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) load_frag<KS>(qb, tok_stride, 32 * nb, p.N, lane, qf[nb]);
+    for (int nb = 0; nb < NB; ++nb) {
+        u32x4 sq[KS];
+        Tile::gload(qb, tok_stride, 32 * nb, p.N, lane, sq);
+        Tile::to_lds(tile, lane, sq);
+        wave_lds_sync();
+        Tile::frags(tile, lane, qf[nb]);
+        wave_lds_sync();
+        if (ch == 0 && wv == 0) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                qfrag[((((long)b * p.H + h) * NB + nb) * KS + ks) * kWave + lane] = qf[nb][ks];
+        }
+    }
 
     float m[NB], z[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) { m[nb] = -INFINITY; z[nb] = 0.f; }
 
-    const int c0 = ch * p.chunk;
-    const int c1 = min(c0 + p.chunk, p.L);
-    for (int j0 = c0 + 32 * wv; j0 < c1; j0 += 32 * 4) {
+    for (; j0 < c1; j0 += 32 * 4) {
+        Tile::to_lds(tile, lane, st);
+        wave_lds_sync();
         bf16x8 kf[KS];
-        load_frag<KS>(kb, tok_stride, j0, p.L, lane, kf);
+        Tile::frags(tile, lane, kf);
+        wave_lds_sync();
+        if (j0 + 32 * 4 < c1) Tile::gload(kb, tok_stride, j0 + 32 * 4, p.L, lane, st);   // prefetch
         // validity of the 32 keys of this tile as a bit mask (vision keys only)
         const int jl = j0 + (lane & 31);
         const bool v_ok = jl < p.Mv ? (!vb || vb[jl]) : false;
@@ -139,71 +193,104 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int NB, int KS, int NW>
+// Sweep 2: column scores.  Block = (tile of 32*MB vision keys, sample), NW waves; wave w takes heads
+// w, w+NW, ...  K tiles go global -> registers (prefetched one head ahead) -> wave-private LDS ->
+// fragments; text-query fragments come from qfrag with coalesced loads.
+template <int NB, int KS, int NW, int MB>
 __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
-    const uint16_t* __restrict__ q_txt, const uint16_t* __restrict__ k,
+    const bf16x8* __restrict__ qfrag, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len,
     const float2* __restrict__ partial, PrefillDims p, float scale_log2e,
     float* __restrict__ Vout, float* __restrict__ Iout)
 {
-    extern __shared__ float smem[];
-    constexpr int NP = 32 * NB;
-    float* s_m = smem;                       // [H][NP]  row max (log2 domain)
+    using Tile = OperandTile<KS>;
+    extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+    constexpr int NP = 32 * NB, TJ = 32 * MB, PARTS = 2 * NW;
+    char* s_tiles = smem_raw;                                                   // [NW][MB][Tile::BYTES]
+    float* s_m = reinterpret_cast<float*>(smem_raw + NW * MB * Tile::BYTES);    // [H][NP] row max (log2 domain)
     float* s_iz = s_m + p.H * NP;            // [H][NP]  1 / (Z * H)
-    float* s_a = s_iz + p.H * NP;            // [32][NP + 1] head-mean probabilities of this key tile
-    float* s_ps = s_a + 32 * (NP + 1);       // [2*NW][32] partial column sums
-    float* s_pm = s_ps + 2 * NW * 32;        // [2*NW][32] partial column maxima
+    float* s_a = s_iz + p.H * NP;            // [TJ][NP + 1] head-mean probabilities of this key tile
+    float* s_ps = s_a + TJ * (NP + 1);       // [PARTS][TJ] partial column sums
+    float* s_pm = s_ps + PARTS * TJ;         // [PARTS][TJ] partial column maxima
 
     const int lane = lane_id(), wv = wave_id(), tid = threadIdx.x;
-    const int j0 = blockIdx.x * 32, b = blockIdx.y;
+    const int j0 = blockIdx.x * TJ, b = blockIdx.y;
     const long tok_stride = (long)p.H * p.d;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
+    char* tile = s_tiles + wv * MB * Tile::BYTES;
+
+    // first head's K tiles are requested before anything else
+    u32x4 st[MB][KS];
+    {
+        const uint16_t* kb = k + ((long)b * p.L * p.H + wv) * p.d;
+        if (wv < p.H) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) Tile::gload(kb, tok_stride, j0 + 32 * mb, p.Mv, lane, st[mb]);
+        }
+    }
 
     // combine the chunk partials into the row statistics of every (head, text row) of this sample
     const float inv_h = 1.0f / (float)p.H;
     for (int e = tid; e < p.H * NP; e += blockDim.x) {
         const int h = e / NP, i = e % NP;
         const float2* pp = partial + ((long)b * p.H + h) * p.nch * p.Npad + i;
-        float mn = -INFINITY;
-        for (int c = 0; c < p.nch; ++c) mn = fmaxf(mn, pp[(long)c * p.Npad].x);
-        float zn = 0.f;
-        if (mn > -INFINITY)
-            for (int c = 0; c < p.nch; ++c) { const float2 v = pp[(long)c * p.Npad]; zn += v.y * exp2f(v.x - mn); }
+        float mn = -INFINITY, zn = 0.f;
+        for (int c = 0; c < p.nch; ++c) {
+            const float2 v = pp[(long)c * p.Npad];
+            const float m2 = fmaxf(mn, v.x);
+            if (m2 > -INFINITY) zn = zn * exp2f(mn - m2) + v.y * exp2f(v.x - m2);
+            mn = m2;
+        }
         s_m[e] = mn;
         s_iz[e] = zn > 0.f ? inv_h / zn : 0.f;
     }
     __syncthreads();
 
-    f32x16 a_acc[NB];
+    f32x16 a_acc[MB][NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) a_acc[nb][r] = 0.f;
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) a_acc[mb][nb][r] = 0.f;
 
     for (int h = wv; h < p.H; h += NW) {
-        const uint16_t* kb = k + ((long)b * p.L * p.H + h) * p.d;
-        const uint16_t* qb = q_txt + ((long)b * p.N * p.H + h) * p.d;
-        bf16x8 kf[KS];
-        load_frag<KS>(kb, tok_stride, j0, p.Mv, lane, kf);
+        bf16x8 kf[MB][KS];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) Tile::to_lds(tile + mb * Tile::BYTES, lane, st[mb]);
+        wave_lds_sync();
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) Tile::frags(tile + mb * Tile::BYTES, lane, kf[mb]);
+        wave_lds_sync();
+        if (h + NW < p.H) {                                                     // prefetch the next head's K tiles
+            const uint16_t* kb = k + ((long)b * p.L * p.H + (h + NW)) * p.d;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) Tile::gload(kb, tok_stride, j0 + 32 * mb, p.Mv, lane, st[mb]);
+        }
+        const bf16x8* qh = qfrag + ((long)b * p.H + h) * NB * KS * kWave + lane;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             bf16x8 qf[KS];
-            load_frag<KS>(qb, tok_stride, 32 * nb, p.N, lane, qf);
-            f32x16 acc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], acc, 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks) qf[ks] = qh[(nb * KS + ks) * kWave];
             const int i = 32 * nb + (lane & 31);
             const float mi = s_m[h * NP + i], izi = s_iz[h * NP + i];
             const bool row_ok = i < tl;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                // masking by select: padded rows / keys may hold NaN
-                const float pr = row_ok ? exp2f(acc[r] * scale_log2e - mi) * izi : 0.f;
-                a_acc[nb][r] += pr;
+            for (int mb = 0; mb < MB; ++mb) {
+                f32x16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][ks], qf[ks], acc, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    // masking by select: padded rows / keys may hold NaN
+                    const float pr = row_ok ? exp2f(acc[r] * scale_log2e - mi) * izi : 0.f;
+                    a_acc[mb][nb][r] += pr;
+                }
             }
         }
     }
@@ -212,20 +299,21 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
     for (int w = 0; w < NW; ++w) {
         if (wv == w) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float* cell = &s_a[tile_row(r, lane) * (NP + 1) + 32 * nb + (lane & 31)];
-                    if (w == 0) *cell = a_acc[nb][r];
-                    else *cell += a_acc[nb][r];
-                }
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float* cell = &s_a[(32 * mb + tile_row(r, lane)) * (NP + 1) + 32 * nb + (lane & 31)];
+                        if (w == 0) *cell = a_acc[mb][nb][r];
+                        else *cell += a_acc[mb][nb][r];
+                    }
         }
         __syncthreads();
     }
     // Eq. 8 / Eq. 10: column sum and column max over the text rows
-    {
-        constexpr int PARTS = 2 * NW;
-        const int r = tid & 31, part = tid >> 5;
+    for (int e = tid; e < PARTS * TJ; e += blockDim.x) {
+        const int r = e % TJ, part = e / TJ;
         const int per = (NP + PARTS - 1) / PARTS;
         float s = 0.f, mx = 0.f;
         for (int i = part * per; i < min((part + 1) * per, tl); ++i) {
@@ -233,15 +321,15 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
             s += a;
             mx = fmaxf(mx, a);
         }
-        s_ps[part * 32 + r] = s;
-        s_pm[part * 32 + r] = mx;
+        s_ps[e] = s;
+        s_pm[e] = mx;
     }
     __syncthreads();
-    if (tid < 32) {
+    if (tid < TJ) {
         const int j = j0 + tid;
         if (j < p.Mv) {
             float s = 0.f, mx = 0.f;
-            for (int part = 0; part < 2 * NW; ++part) { s += s_ps[part * 32 + tid]; mx = fmaxf(mx, s_pm[part * 32 + tid]); }
+            for (int part = 0; part < PARTS; ++part) { s += s_ps[part * TJ + tid]; mx = fmaxf(mx, s_pm[part * TJ + tid]); }
             const bool ok = !vb || vb[j];
             Vout[(long)b * p.Mv + j] = ok ? s : 0.f;
             Iout[(long)b * p.Mv + j] = ok ? mx : 0.f;
@@ -367,16 +455,24 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
 }
 
 struct PrefillWorkspace {
-    float2* partial; float* V; float* I; float* score; int32_t* src_row;
+    float2* partial; bf16x8* qfrag; float* V; float* I; float* score; int32_t* src_row;
     size_t bytes;
 };
 
+#ifndef MD_PF_NW
+#define MD_PF_NW 4      // waves per block in the column-score sweep
+#endif
+#ifndef MD_PF_MB
+#define MD_PF_MB 1      // 32-key tiles per block in the column-score sweep
+#endif
+
 int pick_chunks(int B, int H, int L) {
     // enough (sample, head, chunk) blocks to cover the 256 CUs several times; chunks of whole tiles
+    // about two resident blocks per CU (512 in all); at least 4 tiles per chunk so every wave has work
     const int tiles = (L + 31) / 32;
-    int nch = (1024 + B * H - 1) / (B * H);
+    int nch = (512 + B * H - 1) / (B * H);
+    if (nch > tiles / 4) nch = tiles / 4;
     if (nch < 1) nch = 1;
-    if (nch > tiles) nch = tiles;
     if (nch > 64) nch = 64;
     return nch;
 }
@@ -386,6 +482,7 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
     PrefillWorkspace w;
     const int Npad = (N + 31) / 32 * 32;
     w.partial = c.take<float2>((size_t)B * H * 64 * Npad);
+    w.qfrag = c.take<bf16x8>((size_t)B * H * Npad * 16);      // [B][H][NB][KS][64] fragments, d <= 128
     w.V = c.take<float>((size_t)B * Mv);
     w.I = c.take<float>((size_t)B * Mv);
     w.score = c.take<float>((size_t)B * Mv);
@@ -397,20 +494,24 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
 template <int NB, int KS>
 int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t st, const void* q_txt, const void* k,
                   const uint8_t* vis_valid, const int32_t* txt_len, float scale_log2e) {
-    constexpr int NW = 8;
+    constexpr int NW = MD_PF_NW, MB = MD_PF_MB, TJ = 32 * MB;
     dim3 g1(p.nch, p.H, p.B);
     MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NB, KS><<<g1, 256, 0, st>>>(
-        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, p, scale_log2e, w.partial)));
-    const size_t lds = sizeof(float) * ((size_t)2 * p.H * 32 * NB + 32 * (32 * NB + 1) + 2 * (2 * NW * 32));
-    auto kern = prefill_colscore_kernel<NB, KS, NW>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return fail(MD_EHIP, "prefill_filter: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
+        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, p, scale_log2e, w.partial,
+        w.qfrag)));
+    const size_t lds = (size_t)NW * MB * OperandTile<KS>::BYTES +
+                       sizeof(float) * ((size_t)2 * p.H * 32 * NB + TJ * (32 * NB + 1) + 2 * (2 * NW * TJ));
+    auto kern = prefill_colscore_kernel<NB, KS, NW, MB>;
+    static bool attr_set = false;             // per template instance: raise the dynamic-LDS limit once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return fail(MD_EHIP, "prefill_filter: cannot raise the LDS limit: %s", hipGetErrorString(e));
+        attr_set = true;
     }
-    dim3 g2((p.Mv + 31) / 32, p.B);
+    if (lds > 160 * 1024) return fail(MD_ESHAPE, "prefill_filter: H=%d, N=%d need %zu bytes of LDS (limit 160 KiB)", p.H, p.N, lds);
+    dim3 g2((p.Mv + TJ - 1) / TJ, p.B);
     MD_LAUNCH("prefill_colscore", st, (kern<<<g2, 64 * NW, lds, st>>>(
-        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, w.partial, p,
-        scale_log2e, w.V, w.I)));
+        w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.partial, p, scale_log2e, w.V, w.I)));
     return MD_OK;
 }
 
