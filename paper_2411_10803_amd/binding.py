@@ -9,7 +9,8 @@ F32, BF16 = 0, 1
 FILTER_BUDGET, FILTER_THRESHOLD = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmustdrop.so")
+# MUSTDROP_LIBRARY selects another build of the same ABI (e.g. one compiled with different tile parameters)
+_LIB_PATH = os.environ.get("MUSTDROP_LIBRARY") or os.path.join(_HERE, "libmustdrop.so")
 _lib = None
 
 EXPORTS = [

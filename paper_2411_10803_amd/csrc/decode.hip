@@ -19,6 +19,7 @@ namespace {
 constexpr float kLog2eD = 1.4426950408889634f;
 
 struct DecodeDims { int B, Lcap, H, d; };
+constexpr int kMaxStatParts = 256;               // blocks per sample of the streaming logits kernel
 
 // logits[b][j][h] = scale * q[b][h] . k[b][j][h]      (token-major so an entry's H logits are contiguous)
 // LPH = lanes per head slice = d / 8.  Generic shape: walks an entry's row in 1 KiB pieces.
@@ -87,21 +88,26 @@ __device__ __forceinline__ float dot8(const u32x4& a, const float (&qv)[8]) {
 // Streaming shape: an entry's row is NIT KiB (H*d*2 = NIT*1024 bytes).  A wave keeps the whole query
 // in registers and reads each entry's row in one go: NIT independent 16-byte loads per lane, every
 // load instruction covering 1 KiB of consecutive addresses.  Waves stride over the sample's entries.
+// Each wave also keeps online softmax statistics (max, sum of exp2) of every head over the entries
+// it has seen; the block's four waves are merged and written as one partial per (sample, block, head),
+// so the selection kernel does not have to sweep the logits for them.
 template <int LPH, int NIT>
 __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
-    DecodeDims p, float scale, float* __restrict__ logits)
+    DecodeDims p, float scale, float* __restrict__ logits, float2* __restrict__ stat_partial)
 {
-    const int lane = lane_id();
+    constexpr int HPI = kWave / LPH;                 // heads per load instruction
+    __shared__ float s_m[4][NIT * HPI], s_z[4][NIT * HPI];
+    const int lane = lane_id(), wv = wave_id();
     const int b = blockIdx.y;
-    const int n = min(len[b], p.Lcap);
-    const int wave_global = blockIdx.x * 4 + wave_id();
+    const int n = min(max(len[b], 0), p.Lcap);
+    const int wave_global = blockIdx.x * 4 + wv;
     const int nwaves = gridDim.x * 4;
-    if (wave_global >= n) return;
     const int row = p.H * p.d;
     const u32x4* qb = reinterpret_cast<const u32x4*>(q + (long)b * row);
     const u32x4* kb = reinterpret_cast<const u32x4*>(k_cache + (long)b * p.Lcap * row);
     float* lb = logits + (long)b * p.Lcap * p.H;
+    const float scale_l2 = scale * kLog2eD;
 
     float qv[NIT][8];
 #pragma unroll
@@ -110,7 +116,10 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
         qv[it][0] = bf16_lo(w.x); qv[it][1] = bf16_hi(w.x); qv[it][2] = bf16_lo(w.y); qv[it][3] = bf16_hi(w.y);
         qv[it][4] = bf16_lo(w.z); qv[it][5] = bf16_hi(w.z); qv[it][6] = bf16_lo(w.w); qv[it][7] = bf16_hi(w.w);
     }
-    constexpr int HPI = kWave / LPH;                 // heads per load instruction
+    float m[NIT], z[NIT];                            // log2 domain; every lane of a head's group holds the same values
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) { m[it] = -INFINITY; z[it] = 0.f; }
+
     for (int j = wave_global; j < n; j += nwaves) {
         const u32x4* kr = kb + (long)j * (row / 8);
         u32x4 kv[NIT];
@@ -120,13 +129,195 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
 #pragma unroll
         for (int it = 0; it < NIT; ++it) part[it] = dot8(kv[it], qv[it]);
 #pragma unroll
-        for (int m = 1; m < LPH; m <<= 1)
+        for (int mm = 1; mm < LPH; mm <<= 1)
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) part[it] += __shfl_xor(part[it], m, kWave);
+            for (int it = 0; it < NIT; ++it) part[it] += __shfl_xor(part[it], mm, kWave);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const float t2 = part[it] * scale_l2;
+            const float dlt = t2 - m[it];            // +inf on the first entry
+            const float e = exp2f(-fabsf(dlt));
+            z[it] = dlt > 0.f ? fmaf(z[it], e, 1.0f) : z[it] + e;
+            m[it] = fmaxf(m[it], t2);
+        }
         if ((lane & (LPH - 1)) == 0) {
 #pragma unroll
             for (int it = 0; it < NIT; ++it) lb[(long)j * p.H + it * HPI + lane / LPH] = part[it] * scale;
         }
+    }
+    if ((lane & (LPH - 1)) == 0) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) { s_m[wv][it * HPI + lane / LPH] = m[it]; s_z[wv][it * HPI + lane / LPH] = z[it]; }
+    }
+    __syncthreads();
+    for (int h = threadIdx.x; h < NIT * HPI; h += blockDim.x) {
+        float mn = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mn = fmaxf(mn, s_m[w][h]);
+        float zn = 0.f;
+        if (mn > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) zn += s_z[w][h] * exp2f(s_m[w][h] - mn);
+        }
+        stat_partial[((long)b * gridDim.x + blockIdx.x) * p.H + h] = make_float2(mn, zn);
+    }
+}
+
+// Selection with everything in registers: thread t owns the consecutive entries [t*ipt, (t+1)*ipt),
+// ipt = ceil(n / 1024) <= IPT.  One round of global loads, then block-level phases only.
+template <int IPT>
+__global__ __launch_bounds__(1024) void decode_select_fast_kernel(
+    DecodeDims p, const float* __restrict__ logits, const float2* __restrict__ stat_partial, int n_part,
+    float decay, int budget,
+    float* __restrict__ acc, int32_t* __restrict__ ids, uint8_t* __restrict__ protect, int32_t* __restrict__ len,
+    int32_t* __restrict__ holes, int32_t* __restrict__ movers, int32_t* __restrict__ n_move,
+    int32_t* __restrict__ evicted_ids, int32_t* __restrict__ evicted_count)
+{
+    extern __shared__ int s_holes[];                 // [Lcap] evicted slots below the new length
+    __shared__ float s_cm[1024], s_cz[1024];         // per-(part, head) partial statistics, then per head
+    __shared__ int s_red[16];
+    __shared__ int s_hist[256];
+    __shared__ uint64_t s_red64[16];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int H = p.H;
+    const int n = min(max(len[b], 0), p.Lcap);
+    const float* lb = logits + (long)b * p.Lcap * H;
+    float* ab = acc + (long)b * p.Lcap;
+    int32_t* ib = ids + (long)b * p.Lcap;
+    uint8_t* pb = protect + (long)b * p.Lcap;
+    int32_t* hb = holes + (long)b * p.Lcap;
+    int32_t* mvb = movers + (long)b * p.Lcap;
+    if (n == 0) {
+        if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
+        return;
+    }
+    const int ipt = (n + 1023) / 1024;
+    const int j0 = tid * ipt;
+
+    // own entries' state: all loads are independent and go out together with the statistics loads
+    float a_old[IPT];
+    int id[IPT];
+    bool prot[IPT], live[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = j0 + t;
+        live[t] = t < ipt && j < n;
+        a_old[t] = live[t] ? ab[j] : 0.f;
+        id[t] = live[t] ? ib[j] : 0;
+        prot[t] = live[t] ? pb[j] != 0 : false;
+    }
+    // merge the logits kernel's partial statistics: thread = (slice q, head h)
+    {
+        const int parts = 1024 / H, h = tid % H, q = tid / H;
+        const float2* sp = stat_partial + (long)b * n_part * H + h;
+        float mn = -INFINITY, zn = 0.f;
+        for (int c = q; c < n_part; c += parts) {
+            const float2 v = sp[(long)c * H];
+            const float m2 = fmaxf(mn, v.x);
+            if (m2 > -INFINITY) zn = zn * exp2f(mn - m2) + v.y * exp2f(v.x - m2);
+            mn = m2;
+        }
+        s_cm[q * H + h] = mn;
+        s_cz[q * H + h] = zn;
+        __syncthreads();
+        float mh = -INFINITY, zh = 0.f;
+        if (tid < H) {
+            for (int c = 0; c < parts; ++c) mh = fmaxf(mh, s_cm[c * H + tid]);
+            for (int c = 0; c < parts; ++c) zh += s_cz[c * H + tid] * exp2f(s_cm[c * H + tid] - mh);
+        }
+        __syncthreads();
+        if (tid < H) { s_cm[tid] = mh; s_cz[tid] = 1.0f / (zh * (float)H); }
+        __syncthreads();
+    }
+    // a_t[j] = mean_h softmax ; acc <- decay*acc + a_t
+    float a_new[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        a_new[t] = 0.f;
+        if (live[t]) {
+            const float* lj = lb + (long)(j0 + t) * H;
+            float a = 0.f;
+            for (int hh = 0; hh < H; ++hh) a += exp2f(lj[hh] * kLog2eD - s_cm[hh]) * s_cz[hh];
+            a_new[t] = fmaf(decay, a_old[t], a);
+        }
+    }
+    int np = 0;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) np += prot[t];
+    np = block_sum_i(np, s_red);
+
+    bool keep[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) keep[t] = live[t];
+    int new_len = n;
+    if (n > budget) {
+        const int nu = n - np;
+        const int extra = min(max(budget - np, 0), nu);
+        new_len = np + extra;
+        uint64_t key[IPT];
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) key[t] = (live[t] && !prot[t]) ? rank_key(a_new[t], id[t]) : 0ull;
+        if (nu - extra == 1) {
+            // steady state of a decode loop: exactly one entry leaves -> the smallest key
+            uint64_t mine = ~0ull;
+#pragma unroll
+            for (int t = 0; t < IPT; ++t) if (key[t] != 0 && key[t] < mine) mine = key[t];
+            const uint64_t victim = block_min_u64(mine, s_red64);
+#pragma unroll
+            for (int t = 0; t < IPT; ++t) keep[t] = live[t] && key[t] != victim;
+        } else {
+            const SelectBound sb = block_radix_select_reg<IPT>(key, extra, s_hist);
+#pragma unroll
+            for (int t = 0; t < IPT; ++t)
+                keep[t] = live[t] && (prot[t] || (extra > 0 && (key[t] >> sb.shift) >= sb.bound));
+        }
+    }
+    // holes / movers / evicted: three counters packed into one 64-bit scan (21 bits each)
+    uint64_t cnt = 0;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = j0 + t;
+        if (live[t]) {
+            if (!keep[t] && j < new_len) cnt += 1ull;
+            if (keep[t] && j >= new_len) cnt += 1ull << 21;
+            if (!keep[t]) cnt += 1ull << 42;
+        }
+    }
+    uint64_t total;
+    const uint64_t pre = block_exscan_u64(cnt, s_red64, total);
+    int rh = (int)(pre & 0x1FFFFF), rm = (int)((pre >> 21) & 0x1FFFFF), re = (int)(pre >> 42);
+    const int n_mv = (int)((total >> 21) & 0x1FFFFF), n_ev = (int)(total >> 42);
+    int mrank[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = j0 + t;
+        mrank[t] = -1;
+        if (live[t]) {
+            if (!keep[t] && j < new_len) { s_holes[rh] = j; hb[rh] = j; ++rh; }
+            if (keep[t] && j >= new_len) { mrank[t] = rm; mvb[rm] = j; ++rm; }
+            if (!keep[t]) { if (evicted_ids) evicted_ids[(long)b * p.Lcap + re] = id[t]; ++re; }
+        }
+    }
+    __syncthreads();
+    // write the scores back; a mover's state goes straight to its hole (no overlap: holes < new_len <= movers)
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = j0 + t;
+        if (!live[t]) continue;
+        if (mrank[t] >= 0) {
+            const int dst = s_holes[mrank[t]];
+            ab[dst] = a_new[t];
+            ib[dst] = id[t];
+            pb[dst] = prot[t] ? 1 : 0;
+            ab[j] = a_new[t];
+        } else if (keep[t] || j >= new_len) {
+            ab[j] = a_new[t];
+        }
+    }
+    if (tid == 0) {
+        n_move[b] = n_mv;
+        len[b] = new_len;
+        if (evicted_count) evicted_count[b] = n_ev;
     }
 }
 
@@ -290,7 +481,7 @@ __global__ __launch_bounds__(256) void decode_append_kernel(
 }
 
 struct DecodeWorkspace {
-    float* logits; uint8_t* keep; int32_t* holes; int32_t* movers; int32_t* n_move;
+    float* logits; float2* stat_partial; uint8_t* keep; int32_t* holes; int32_t* movers; int32_t* n_move;
     size_t bytes;
 };
 
@@ -298,6 +489,7 @@ DecodeWorkspace carve_decode(void* base, int B, int Lcap, int H) {
     Carver c(base);
     DecodeWorkspace w;
     w.logits = c.take<float>((size_t)B * Lcap * H);
+    w.stat_partial = c.take<float2>((size_t)B * kMaxStatParts * H);
     w.keep = c.take<uint8_t>((size_t)B * Lcap);
     w.holes = c.take<int32_t>((size_t)B * Lcap);
     w.movers = c.take<int32_t>((size_t)B * Lcap);
@@ -357,20 +549,22 @@ extern "C" int mustdrop_decode_evict(
     const uint16_t* kp = static_cast<const uint16_t*>(k_cache);
     const int row_bytes = H * d * 2;
     const int nit = row_bytes % 1024 == 0 ? row_bytes / 1024 : 0;
+    int n_part = 0;                                   // > 0: the logits kernel left per-block softmax statistics
     if (d == 128 && (nit == 1 || nit == 2 || nit == 4 || nit == 8)) {
         // streaming shape: about 16 waves per CU in flight, each striding over its sample's entries
         int blocks_x = (4096 + B - 1) / B;
         const int max_x = (Lcap + 3) / 4;
         if (blocks_x > max_x) blocks_x = max_x;
+        if (blocks_x > kMaxStatParts) blocks_x = kMaxStatParts;
         if (blocks_x < 1) blocks_x = 1;
         dim3 g1(blocks_x, B);
         switch (nit) {
-            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
-            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
-            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
-            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits))); break;
-            default: break;
+            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
+            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
+            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
+            default: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
         }
+        n_part = blocks_x;
     } else {
         int tpb = (int)(((long)B * Lcap + 4095) / 4096);
         tpb = tpb < 4 ? 4 : (tpb > 32 ? 32 : tpb);
@@ -385,9 +579,23 @@ extern "C" int mustdrop_decode_evict(
             default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
         }
     }
-    const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);
-    MD_LAUNCH("decode_select", st, (decode_select_kernel<<<B, 1024, lds, st>>>(
-        p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count)));
+    if (n_part > 0 && Lcap <= 8192) {
+        const size_t lds = sizeof(int) * (size_t)Lcap;
+        const int ipt = (Lcap + 1023) / 1024;
+#define MD_SELECT_FAST(I)                                                                                          \
+    MD_LAUNCH("decode_select", st, (decode_select_fast_kernel<I><<<B, 1024, lds, st>>>(                             \
+        p, w.logits, w.stat_partial, n_part, decay, budget, acc, ids, protect, len, w.holes, w.movers, w.n_move,   \
+        evicted_ids, evicted_count)))
+        if (ipt <= 1) MD_SELECT_FAST(1);
+        else if (ipt <= 2) MD_SELECT_FAST(2);
+        else if (ipt <= 4) MD_SELECT_FAST(4);
+        else MD_SELECT_FAST(8);
+#undef MD_SELECT_FAST
+    } else {
+        const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);
+        MD_LAUNCH("decode_select", st, (decode_select_kernel<<<B, 1024, lds, st>>>(
+            p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count)));
+    }
     dim3 g3(32, B);
     MD_LAUNCH("decode_move", st, (decode_move_kernel<<<g3, 256, 0, st>>>(
         p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache))));

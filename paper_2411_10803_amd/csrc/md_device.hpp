@@ -116,6 +116,7 @@ __device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int 
     int shift = 64;
     __shared__ int s_digit, s_k, s_done;
     int kk = k;
+    if (k <= 0) return SelectBound{~0ull, 0};               // nothing selected
     for (int pass = 0; pass < 8; ++pass) {
         const int sh = 56 - 8 * pass;
         __syncthreads();
@@ -162,6 +163,108 @@ __device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int 
         if (s_done == 1) break;
     }
     return SelectBound{prefix, shift};
+}
+
+// Same selection with the keys held in registers (IPT per thread, 0 = absent; real keys are never 0
+// as long as the tie value is below 2^31 - 1): no memory traffic inside the passes.
+template <int IPT>
+__device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&key)[IPT], int k, int* hist) {
+    uint64_t prefix = 0;
+    int shift = 64;
+    __shared__ int s_digit, s_k, s_done;
+    int kk = k;
+    if (k <= 0) return SelectBound{~0ull, 0};               // nothing selected
+    for (int pass = 0; pass < 8; ++pass) {
+        const int sh = 56 - 8 * pass;
+        __syncthreads();
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const uint64_t kv = key[t];
+            if (kv != 0 && (pass == 0 || (kv >> shift) == prefix)) atomicAdd(&hist[(kv >> sh) & 0xFF], 1);
+        }
+        __syncthreads();
+        if (threadIdx.x < kWave) {
+            const int lane = threadIdx.x;
+            int c[4], s = 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { c[t] = hist[255 - (lane * 4 + t)]; s += c[t]; }
+            int incl = s;
+#pragma unroll
+            for (int m = 1; m < kWave; m <<= 1) {
+                const int o = __shfl_up(incl, m, kWave);
+                if (lane >= m) incl += o;
+            }
+            int run = incl - s;
+            const int total = __shfl(incl, kWave - 1, kWave);
+            if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }
+            if (total >= kk) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (run < kk && run + c[t] >= kk) {
+                        s_digit = 255 - (lane * 4 + t);
+                        s_k = kk - run;
+                        s_done = (run + c[t] == kk) ? 1 : 0;
+                    }
+                    run += c[t];
+                }
+            }
+        }
+        __syncthreads();
+        if (s_done == 2) return SelectBound{0ull, 63};
+        prefix = (prefix << 8) | (uint64_t)s_digit;
+        shift = sh;
+        kk = s_k;
+        if (s_done == 1) break;
+    }
+    return SelectBound{prefix, shift};
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
+    const uint32_t lo = __shfl_xor((uint32_t)v, m, kWave), hi = __shfl_xor((uint32_t)(v >> 32), m, kWave);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int m) {
+    const uint32_t lo = __shfl_up((uint32_t)v, m, kWave), hi = __shfl_up((uint32_t)(v >> 32), m, kWave);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Block-wide minimum of 64-bit values (same result on every thread).  `red` holds >= blockDim.x/64 entries.
+__device__ __forceinline__ uint64_t block_min_u64(uint64_t v, uint64_t* red) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) { const uint64_t o = shfl_xor_u64(v, m); v = o < v ? o : v; }
+    __syncthreads();
+    if (lane_id() == 0) red[wave_id()] = v;
+    __syncthreads();
+    uint64_t t = ~0ull;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) t = red[w] < t ? red[w] : t;
+    return t;
+}
+
+// Exclusive prefix sum over the block, in thread order, of a 64-bit value (used with several small
+// counters packed into one word).  Returns this thread's prefix; `total` = block sum.
+__device__ __forceinline__ uint64_t block_exscan_u64(uint64_t v, uint64_t* red, uint64_t& total) {
+    const int lane = lane_id();
+    uint64_t incl = v;
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        const uint64_t o = shfl_up_u64(incl, m);
+        if (lane >= m) incl += o;
+    }
+    __syncthreads();
+    if (lane == kWave - 1) red[wave_id()] = incl;
+    __syncthreads();
+    uint64_t off = 0, tot = 0;
+    const int nw = blockDim.x >> 6, w = wave_id();
+    for (int i = 0; i < nw; ++i) {
+        const uint64_t c = red[i];
+        if (i < w) off += c;
+        tot += c;
+    }
+    total = tot;
+    return off + incl - v;
 }
 
 }  // namespace md

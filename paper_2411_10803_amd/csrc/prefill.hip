@@ -72,6 +72,12 @@ struct OperandTile {
     }
 };
 
+// Row statistics folded into one constant: a probability of the head mean is
+// exp2(s*scale*log2e + c) with c = -m - log2(Z) - log2(H); text rows beyond txt_len get -inf (-> 0).
+__device__ __forceinline__ float fold_stats(float m, float z, bool row_ok, int H) {
+    return (row_ok && z > 0.f) ? -m - log2f(z) - log2f((float)H) : -INFINITY;
+}
+
 // LDS traffic between lanes of one wave: LDS operations of a wave execute in order, the fence keeps
 // the compiler from moving the reads above the writes.
 __device__ __forceinline__ void wave_lds_sync() {
@@ -81,25 +87,28 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Sweep 1: row statistics.  Block = (key chunk, head, sample), 4 waves; every wave walks its share
-// of the chunk's 32-key tiles with the next tile's global loads in flight during the MFMAs.
-// Chunk 0 also stores the text-query fragments in fragment-major order (qfrag) so that sweep 2
-// reads them with fully coalesced 16-byte loads.
+// Sweep 1: row statistics.  Block = (key chunk x text group, head, sample), 4 waves; every wave
+// walks its share of the chunk's 32-key tiles with the next tile's global loads in flight during
+// the MFMAs.  A block covers NB <= 2 blocks of 32 text rows (one "text group"); longer prompts are
+// split over blockIdx.x.  Chunk 0 also stores the text-query fragments in fragment-major order
+// (qfrag), rows beyond txt_len zeroed, so that sweep 2 reads them with coalesced 16-byte loads.
 template <int NB, int KS>
 __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const uint16_t* __restrict__ q_txt, const uint16_t* __restrict__ k,
-    const uint8_t* __restrict__ vis_valid, PrefillDims p, float scale_log2e,
-    float2* __restrict__ partial, bf16x8* __restrict__ qfrag)
+    const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len, PrefillDims p, float scale_log2e,
+    float2* __restrict__ partial, float* __restrict__ cstat, bf16x8* __restrict__ qfrag)
 {
     using Tile = OperandTile<KS>;
     __shared__ __attribute__((aligned(16))) char s_tile[4][Tile::BYTES];
     __shared__ float s_m[4][32 * NB], s_z[4][32 * NB];
     const int lane = lane_id(), wv = wave_id();
-    const int ch = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y, b = blockIdx.z;
+    const int i_base = tg * 32 * NB;                 // first text row of this block's group
     const long tok_stride = (long)p.H * p.d;
     const uint16_t* kb = k + ((long)b * p.L * p.H + h) * p.d;
     const uint16_t* qb = q_txt + ((long)b * p.N * p.H + h) * p.d;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
+    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
     char* tile = s_tile[wv];
 
     const int c0 = ch * p.chunk;
@@ -113,15 +122,16 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         u32x4 sq[KS];
-        Tile::gload(qb, tok_stride, 32 * nb, p.N, lane, sq);
+        Tile::gload(qb, tok_stride, i_base + 32 * nb, tl, lane, sq);      // rows >= txt_len read as zero
         Tile::to_lds(tile, lane, sq);
         wave_lds_sync();
         Tile::frags(tile, lane, qf[nb]);
         wave_lds_sync();
-        if (ch == 0 && wv == 0) {
+        const int nbg = tg * NB + nb;                // 32-row block index within the padded text axis
+        if (ch == 0 && wv == 0 && nbg < p.Npad / 32) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                qfrag[((((long)b * p.H + h) * NB + nb) * KS + ks) * kWave + lane] = qf[nb][ks];
+                qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[nb][ks];
         }
     }
 
@@ -140,6 +150,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         const int jl = j0 + (lane & 31);
         const bool v_ok = jl < p.Mv ? (!vb || vb[jl]) : false;
         const uint32_t vmask = (uint32_t)__ballot(v_ok);
+        const bool all_visible = (j0 + 32 <= p.Mv) && vmask == 0xFFFFFFFFu;   // wave-uniform
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             f32x16 acc;
@@ -148,16 +159,21 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nb][ks], acc, 0, 0, 0);
-            const int i = 32 * nb + (lane & 31);
             float t[16];
             float bm = -INFINITY;
+            if (all_visible) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile_row(r, lane);
-                const int j = j0 + row;
-                const bool vis = j < p.Mv ? ((vmask >> row) & 1u) : (j < p.L && (j - p.Mv) <= i);
-                t[r] = vis ? acc[r] * scale_log2e : -INFINITY;
-                bm = fmaxf(bm, t[r]);
+                for (int r = 0; r < 16; ++r) { t[r] = acc[r] * scale_log2e; bm = fmaxf(bm, t[r]); }
+            } else {
+                const int i = i_base + 32 * nb + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile_row(r, lane);
+                    const int j = j0 + row;
+                    const bool vis = j < p.Mv ? ((vmask >> row) & 1u) : (j < p.L && (j - p.Mv) <= i);
+                    t[r] = vis ? acc[r] * scale_log2e : -INFINITY;
+                    bm = fmaxf(bm, t[r]);
+                }
             }
             const float mn = fmaxf(m[nb], bm);
             if (mn > -INFINITY) {
@@ -188,148 +204,162 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
 #pragma unroll
             for (int w = 0; w < 4; ++w) zn += s_z[w][i] * exp2f(s_m[w][i] - mn);
         }
-        partial[(((long)b * p.H + h) * p.nch + ch) * p.Npad + i] = make_float2(mn, zn);
+        if (i_base + i < p.Npad) {
+            if (p.nch == 1)     // the only chunk: fold the statistics right away (see fold_stats)
+                cstat[((long)b * p.H + h) * p.Npad + i_base + i] = fold_stats(mn, zn, i_base + i < tl, p.H);
+            else
+                partial[(((long)b * p.H + h) * p.nch + ch) * p.Npad + i_base + i] = make_float2(mn, zn);
+        }
     }
 }
 
+// Several key chunks per (sample, head): merge their partial statistics.  One thread per text row.
+__global__ __launch_bounds__(256) void prefill_cstat_kernel(
+    const float2* __restrict__ partial, const int32_t* __restrict__ txt_len, PrefillDims p, float* __restrict__ cstat)
+{
+    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (long)p.B * p.H * p.Npad) return;
+    const int i = (int)(e % p.Npad);
+    const long bh = e / p.Npad;
+    const int b = (int)(bh / p.H);
+    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
+    const float2* pp = partial + bh * p.nch * p.Npad + i;
+    float mn = -INFINITY, zn = 0.f;
+    for (int c = 0; c < p.nch; ++c) {
+        const float2 v = pp[(long)c * p.Npad];
+        const float m2 = fmaxf(mn, v.x);
+        if (m2 > -INFINITY) zn = zn * exp2f(mn - m2) + v.y * exp2f(v.x - m2);
+        mn = m2;
+    }
+    cstat[e] = fold_stats(mn, zn, i < tl, p.H);
+}
+
 // ---------------------------------------------------------------------------------------------
-// Sweep 2: column scores.  Block = (tile of 32*MB vision keys, sample), NW waves; wave w takes heads
-// w, w+NW, ...  K tiles go global -> registers (prefetched one head ahead) -> wave-private LDS ->
-// fragments; text-query fragments come from qfrag with coalesced loads.
-template <int NB, int KS, int NW, int MB>
+// Sweep 2: column scores.  Block = (32 vision keys, sample), NW waves; wave w takes heads w, w+NW, ...
+// K tiles go global -> registers (prefetched one head ahead) -> wave-private LDS -> fragments;
+// text-query fragments come from qfrag with coalesced loads.  The row statistics are folded into one
+// constant per (head, text row): p = exp2(s*scale*log2e + c), c = -m - log2(Z*H), so a probability
+// costs one FMA and one exp2.  NB = number of 32-row text blocks (all of them: the column sum and
+// max run over every text row).
+template <int NB, int KS, int NW>
 __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
     const bf16x8* __restrict__ qfrag, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len,
-    const float2* __restrict__ partial, PrefillDims p, float scale_log2e,
+    const float* __restrict__ cstat, PrefillDims p, float scale_log2e,
     float* __restrict__ Vout, float* __restrict__ Iout)
 {
     using Tile = OperandTile<KS>;
-    extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    constexpr int NP = 32 * NB, TJ = 32 * MB, PARTS = 2 * NW;
-    char* s_tiles = smem_raw;                                                   // [NW][MB][Tile::BYTES]
-    float* s_m = reinterpret_cast<float*>(smem_raw + NW * MB * Tile::BYTES);    // [H][NP] row max (log2 domain)
-    float* s_iz = s_m + p.H * NP;            // [H][NP]  1 / (Z * H)
-    float* s_a = s_iz + p.H * NP;            // [TJ][NP + 1] head-mean probabilities of this key tile
-    float* s_ps = s_a + TJ * (NP + 1);       // [PARTS][TJ] partial column sums
-    float* s_pm = s_ps + PARTS * TJ;         // [PARTS][TJ] partial column maxima
+    constexpr int PARTS = 2 * NW;
+    constexpr int HALF = NB > 2 ? 2 : NB;            // text blocks dumped per reduction round (8 KiB per wave)
+    static_assert(32 * 32 * HALF * 4 <= Tile::BYTES || KS < 8, "reduction buffer must fit the K tile");
+    constexpr int WBUF = (Tile::BYTES > 32 * 32 * HALF * 4) ? Tile::BYTES : 32 * 32 * HALF * 4;
+    __shared__ __attribute__((aligned(16))) char s_buf[NW][WBUF];   // K tile of each wave; later its a_acc dump
+    __shared__ float s_ps[PARTS][32], s_pm[PARTS][32];
 
     const int lane = lane_id(), wv = wave_id(), tid = threadIdx.x;
-    const int j0 = blockIdx.x * TJ, b = blockIdx.y;
+    const int j0 = blockIdx.x * 32, b = blockIdx.y;
     const long tok_stride = (long)p.H * p.d;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
-    char* tile = s_tiles + wv * MB * Tile::BYTES;
+    char* tile = s_buf[wv];
 
-    // first head's K tiles are requested before anything else
-    u32x4 st[MB][KS];
-    {
-        const uint16_t* kb = k + ((long)b * p.L * p.H + wv) * p.d;
-        if (wv < p.H) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) Tile::gload(kb, tok_stride, j0 + 32 * mb, p.Mv, lane, st[mb]);
-        }
-    }
+    u32x4 st[KS];
+    if (wv < p.H) Tile::gload(k + ((long)b * p.L * p.H + wv) * p.d, tok_stride, j0, p.Mv, lane, st);
 
-    // combine the chunk partials into the row statistics of every (head, text row) of this sample
-    const float inv_h = 1.0f / (float)p.H;
-    for (int e = tid; e < p.H * NP; e += blockDim.x) {
-        const int h = e / NP, i = e % NP;
-        const float2* pp = partial + ((long)b * p.H + h) * p.nch * p.Npad + i;
-        float mn = -INFINITY, zn = 0.f;
-        for (int c = 0; c < p.nch; ++c) {
-            const float2 v = pp[(long)c * p.Npad];
-            const float m2 = fmaxf(mn, v.x);
-            if (m2 > -INFINITY) zn = zn * exp2f(mn - m2) + v.y * exp2f(v.x - m2);
-            mn = m2;
-        }
-        s_m[e] = mn;
-        s_iz[e] = zn > 0.f ? inv_h / zn : 0.f;
-    }
-    __syncthreads();
+    f32x16 a_acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a_acc[nb][r] = 0.f;
 
-    f32x16 a_acc[MB][NB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) a_acc[mb][nb][r] = 0.f;
-
+    constexpr int TP = (NB + 1) / 2;                 // text blocks are processed in pairs (64 registers of fragments)
     for (int h = wv; h < p.H; h += NW) {
-        bf16x8 kf[MB][KS];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) Tile::to_lds(tile + mb * Tile::BYTES, lane, st[mb]);
-        wave_lds_sync();
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) Tile::frags(tile + mb * Tile::BYTES, lane, kf[mb]);
-        wave_lds_sync();
-        if (h + NW < p.H) {                                                     // prefetch the next head's K tiles
-            const uint16_t* kb = k + ((long)b * p.L * p.H + (h + NW)) * p.d;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) Tile::gload(kb, tok_stride, j0 + 32 * mb, p.Mv, lane, st[mb]);
-        }
         const bf16x8* qh = qfrag + ((long)b * p.H + h) * NB * KS * kWave + lane;
+        const float* ch = cstat + ((long)b * p.H + h) * p.Npad + (lane & 31);
+        bf16x8 qf[2][KS];
+        float c[2];
+        auto load_pair = [&](int tp) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            bf16x8 qf[KS];
+            for (int e = 0; e < 2; ++e) {
+                const int nb = 2 * tp + e;
+                if (nb < NB) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) qf[ks] = qh[(nb * KS + ks) * kWave];
-            const int i = 32 * nb + (lane & 31);
-            const float mi = s_m[h * NP + i], izi = s_iz[h * NP + i];
-            const bool row_ok = i < tl;
+                    for (int ks = 0; ks < KS; ++ks) qf[e][ks] = qh[(nb * KS + ks) * kWave];
+                    c[e] = ch[32 * nb];
+                }
+            }
+        };
+        // the first pair's query fragments and folded row statistics are requested before the K tile
+        // goes through LDS, so they are in flight meanwhile
+        load_pair(0);
+        bf16x8 kf[KS];
+        Tile::to_lds(tile, lane, st);
+        wave_lds_sync();
+        Tile::frags(tile, lane, kf);
+        wave_lds_sync();
+        if (h + NW < p.H)                                                      // prefetch the next head's K tile
+            Tile::gload(k + ((long)b * p.L * p.H + (h + NW)) * p.d, tok_stride, j0, p.Mv, lane, st);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                f32x16 acc;
+        for (int tp = 0; tp < TP; ++tp) {
+            if (tp > 0) load_pair(tp);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            for (int e = 0; e < 2; ++e) {
+                const int nb = 2 * tp + e;
+                if (nb < NB) {
+                    f32x16 acc;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][ks], qf[ks], acc, 0, 0, 0);
+                    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // masking by select: padded rows / keys may hold NaN
-                    const float pr = row_ok ? exp2f(acc[r] * scale_log2e - mi) * izi : 0.f;
-                    a_acc[mb][nb][r] += pr;
+                    for (int ks = 0; ks < KS; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[e][ks], acc, 0, 0, 0);
+                    // text rows beyond txt_len have zero query fragments and c = -inf: exp2(-inf) = 0 exactly
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        a_acc[nb < NB ? nb : 0][r] += exp2f(fmaf(acc[r], scale_log2e, c[e]));
                 }
             }
         }
     }
 
-    // sum the waves' head groups in wave order (fixed order -> reproducible bits)
-    for (int w = 0; w < NW; ++w) {
-        if (wv == w) {
+    // Column statistics (Eq. 8 / Eq. 10).  Every wave dumps its accumulators into its own buffer;
+    // the waves' head groups are then summed in wave order while the text rows are reduced
+    // (fixed order -> reproducible bits).
+    float col_s = 0.f, col_m = 0.f;                  // this thread's (key, text-row slice) partial results
+    const int rr = tid & 31, part = tid >> 5;
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+    for (int half = 0; half < NB; half += HALF) {
+        __syncthreads();
+        float* mine = reinterpret_cast<float*>(tile);
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < HALF; ++nb) {
+            if (half + nb < NB) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float* cell = &s_a[(32 * mb + tile_row(r, lane)) * (NP + 1) + 32 * nb + (lane & 31)];
-                        if (w == 0) *cell = a_acc[mb][nb][r];
-                        else *cell += a_acc[mb][nb][r];
-                    }
+                for (int r = 0; r < 16; ++r)
+                    mine[((nb * 32) + (lane & 31)) * 32 + ((tile_row(r, lane) + (lane & 31)) & 31)] =
+                        a_acc[(half + nb) < NB ? (half + nb) : 0][r];
+            }
         }
         __syncthreads();
-    }
-    // Eq. 8 / Eq. 10: column sum and column max over the text rows
-    for (int e = tid; e < PARTS * TJ; e += blockDim.x) {
-        const int r = e % TJ, part = e / TJ;
-        const int per = (NP + PARTS - 1) / PARTS;
-        float s = 0.f, mx = 0.f;
-        for (int i = part * per; i < min((part + 1) * per, tl); ++i) {
-            const float a = s_a[r * (NP + 1) + i];
-            s += a;
-            mx = fmaxf(mx, a);
+        constexpr int per = (32 * HALF + PARTS - 1) / PARTS;
+        for (int ii = part * per; ii < min((part + 1) * per, 32 * HALF); ++ii) {
+            if (half * 32 + ii >= tl) break;
+            float a = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+                a += reinterpret_cast<const float*>(s_buf[w])[ii * 32 + ((rr + (ii & 31)) & 31)];
+            col_s += a;
+            col_m = fmaxf(col_m, a);
         }
-        s_ps[e] = s;
-        s_pm[e] = mx;
     }
+    s_ps[part][rr] = col_s;
+    s_pm[part][rr] = col_m;
     __syncthreads();
-    if (tid < TJ) {
+    if (tid < 32) {
         const int j = j0 + tid;
         if (j < p.Mv) {
             float s = 0.f, mx = 0.f;
-            for (int part = 0; part < PARTS; ++part) { s += s_ps[part * TJ + tid]; mx = fmaxf(mx, s_pm[part * TJ + tid]); }
+#pragma unroll
+            for (int q = 0; q < PARTS; ++q) { s += s_ps[q][tid]; mx = fmaxf(mx, s_pm[q][tid]); }
             const bool ok = !vb || vb[j];
             Vout[(long)b * p.Mv + j] = ok ? s : 0.f;
             Iout[(long)b * p.Mv + j] = ok ? mx : 0.f;
@@ -455,15 +485,12 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
 }
 
 struct PrefillWorkspace {
-    float2* partial; bf16x8* qfrag; float* V; float* I; float* score; int32_t* src_row;
+    float2* partial; float* cstat; bf16x8* qfrag; float* V; float* I; float* score; int32_t* src_row;
     size_t bytes;
 };
 
 #ifndef MD_PF_NW
-#define MD_PF_NW 4      // waves per block in the column-score sweep
-#endif
-#ifndef MD_PF_MB
-#define MD_PF_MB 1      // 32-key tiles per block in the column-score sweep
+#define MD_PF_NW 8      // waves per block in the column-score sweep
 #endif
 
 int pick_chunks(int B, int H, int L) {
@@ -482,6 +509,7 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
     PrefillWorkspace w;
     const int Npad = (N + 31) / 32 * 32;
     w.partial = c.take<float2>((size_t)B * H * 64 * Npad);
+    w.cstat = c.take<float>((size_t)B * H * Npad);
     w.qfrag = c.take<bf16x8>((size_t)B * H * Npad * 16);      // [B][H][NB][KS][64] fragments, d <= 128
     w.V = c.take<float>((size_t)B * Mv);
     w.I = c.take<float>((size_t)B * Mv);
@@ -491,27 +519,24 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
     return w;
 }
 
-template <int NB, int KS>
+template <int NBW, int NB, int KS>
 int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t st, const void* q_txt, const void* k,
                   const uint8_t* vis_valid, const int32_t* txt_len, float scale_log2e) {
-    constexpr int NW = MD_PF_NW, MB = MD_PF_MB, TJ = 32 * MB;
-    dim3 g1(p.nch, p.H, p.B);
-    MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NB, KS><<<g1, 256, 0, st>>>(
-        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, p, scale_log2e, w.partial,
-        w.qfrag)));
-    const size_t lds = (size_t)NW * MB * OperandTile<KS>::BYTES +
-                       sizeof(float) * ((size_t)2 * p.H * 32 * NB + TJ * (32 * NB + 1) + 2 * (2 * NW * TJ));
-    auto kern = prefill_colscore_kernel<NB, KS, NW, MB>;
-    static bool attr_set = false;             // per template instance: raise the dynamic-LDS limit once
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return fail(MD_EHIP, "prefill_filter: cannot raise the LDS limit: %s", hipGetErrorString(e));
-        attr_set = true;
+    // NBW: 32-row text blocks per block of sweep 1 (<= 2); NB: all text blocks (sweep 2)
+    constexpr int NW = MD_PF_NW;
+    const int ntg = (NB + NBW - 1) / NBW;
+    dim3 g1(p.nch * ntg, p.H, p.B);
+    MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW, KS><<<g1, 256, 0, st>>>(
+        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
+        w.partial, w.cstat, w.qfrag)));
+    if (p.nch > 1) {
+        const long n = (long)p.B * p.H * p.Npad;
+        MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+            w.partial, txt_len, p, w.cstat)));
     }
-    if (lds > 160 * 1024) return fail(MD_ESHAPE, "prefill_filter: H=%d, N=%d need %zu bytes of LDS (limit 160 KiB)", p.H, p.N, lds);
-    dim3 g2((p.Mv + TJ - 1) / TJ, p.B);
-    MD_LAUNCH("prefill_colscore", st, (kern<<<g2, 64 * NW, lds, st>>>(
-        w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.partial, p, scale_log2e, w.V, w.I)));
+    dim3 g2((p.Mv + 31) / 32, p.B);
+    MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB, KS, NW><<<g2, 64 * NW, 0, st>>>(
+        w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, w.V, w.I)));
     return MD_OK;
 }
 
@@ -585,15 +610,15 @@ extern "C" int mustdrop_prefill_filter(
     int rc = MD_OK;
     const int NB = p.Npad / 32;
     if (d == 128) {
-        if (NB == 1) rc = launch_scores<1, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 2) rc = launch_scores<2, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 3) rc = launch_scores<3, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else rc = launch_scores<4, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        if (NB == 1) rc = launch_scores<1, 1, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        else if (NB == 2) rc = launch_scores<2, 2, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        else if (NB == 3) rc = launch_scores<2, 3, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        else rc = launch_scores<2, 4, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
     } else {
-        if (NB == 1) rc = launch_scores<1, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 2) rc = launch_scores<2, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 3) rc = launch_scores<3, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else rc = launch_scores<4, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        if (NB == 1) rc = launch_scores<1, 1, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        else if (NB == 2) rc = launch_scores<2, 2, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        else if (NB == 3) rc = launch_scores<2, 3, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+        else rc = launch_scores<2, 4, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
     }
     if (rc != MD_OK) return rc;
     int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
