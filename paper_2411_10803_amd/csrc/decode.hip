@@ -18,6 +18,15 @@ namespace {
 
 constexpr float kLog2eD = 1.4426950408889634f;
 
+#ifdef MD_TRACE   // debug builds only: phase timestamps of block 0 / thread 0
+}  // namespace
+__device__ unsigned long long g_trace[32];
+namespace {
+#define MD_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[i] = wall_clock64(); } while (0)
+#else
+#define MD_STAMP(i) do { } while (0)
+#endif
+
 struct DecodeDims { int B, Lcap, H, d; };
 constexpr int kMaxStatParts = 256;               // blocks per sample of the streaming logits kernel
 
@@ -66,8 +75,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
                 part = fmaf(qv[6], bf16_lo(w.w), part);
                 part = fmaf(qv[7], bf16_hi(w.w), part);
             }
-#pragma unroll
-            for (int m = 1; m < LPH; m <<= 1) part += __shfl_xor(part, m, kWave);
+            part = group_sum<LPH>(part);
             if (idx < nvec && (lane & (LPH - 1)) == 0) lb[(long)j * p.H + head] = part * scale;
         }
     }
@@ -129,14 +137,12 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
 #pragma unroll
         for (int it = 0; it < NIT; ++it) part[it] = dot8(kv[it], qv[it]);
 #pragma unroll
-        for (int mm = 1; mm < LPH; mm <<= 1)
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) part[it] += __shfl_xor(part[it], mm, kWave);
+        for (int it = 0; it < NIT; ++it) part[it] = group_sum<LPH>(part[it]);
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const float t2 = part[it] * scale_l2;
             const float dlt = t2 - m[it];            // +inf on the first entry
-            const float e = exp2f(-fabsf(dlt));
+            const float e = fast_exp2(-fabsf(dlt));
             z[it] = dlt > 0.f ? fmaf(z[it], e, 1.0f) : z[it] + e;
             m[it] = fmaxf(m[it], t2);
         }
@@ -157,14 +163,14 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
         float zn = 0.f;
         if (mn > -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < 4; ++w) zn += s_z[w][h] * exp2f(s_m[w][h] - mn);
+            for (int w = 0; w < 4; ++w) zn += s_z[w][h] * fast_exp2(s_m[w][h] - mn);
         }
         stat_partial[((long)b * gridDim.x + blockIdx.x) * p.H + h] = make_float2(mn, zn);
     }
 }
 
-// Selection with everything in registers: thread t owns the consecutive entries [t*ipt, (t+1)*ipt),
-// ipt = ceil(n / 1024) <= IPT.  One round of global loads, then block-level phases only.
+// Selection with everything in registers: thread t owns the consecutive entries [t*IPT, (t+1)*IPT),
+// IPT >= ceil(Lcap / 1024).  One round of global loads, then block-level phases only.
 template <int IPT>
 __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     DecodeDims p, const float* __restrict__ logits, const float2* __restrict__ stat_partial, int n_part,
@@ -173,78 +179,119 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     int32_t* __restrict__ holes, int32_t* __restrict__ movers, int32_t* __restrict__ n_move,
     int32_t* __restrict__ evicted_ids, int32_t* __restrict__ evicted_count)
 {
-    extern __shared__ int s_holes[];                 // [Lcap] evicted slots below the new length
-    __shared__ float s_cm[1024], s_cz[1024];         // per-(part, head) partial statistics, then per head
+    extern __shared__ int s_holes[];                 // [Lcap] evicted slots below the new length, then [Lcap] a_t
+    float* s_at = reinterpret_cast<float*>(s_holes + p.Lcap);
+    __shared__ float s_cm[1024], s_cz[1024];         // per head: max (log2 domain), 1 / (Z * H)
     __shared__ int s_red[16];
     __shared__ int s_hist[256];
     __shared__ uint64_t s_red64[16];
     const int b = blockIdx.x, tid = threadIdx.x;
     const int H = p.H;
-    const int n = min(max(len[b], 0), p.Lcap);
     const float* lb = logits + (long)b * p.Lcap * H;
     float* ab = acc + (long)b * p.Lcap;
     int32_t* ib = ids + (long)b * p.Lcap;
     uint8_t* pb = protect + (long)b * p.Lcap;
     int32_t* hb = holes + (long)b * p.Lcap;
     int32_t* mvb = movers + (long)b * p.Lcap;
-    if (n == 0) {
-        if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
-        return;
-    }
-    const int ipt = (n + 1023) / 1024;
-    const int j0 = tid * ipt;
-
-    // own entries' state: all loads are independent and go out together with the statistics loads
+    // Everything this thread needs from memory is requested up front, before the sample's length is
+    // known: its own entries' state (entries [tid*IPT, tid*IPT+IPT), fixed by the capacity) and the
+    // logits of entry `tid` for the score phase.  Slots beyond the live length hold stale but
+    // readable data; they are masked once `n` has arrived.
+    const int j0 = tid * IPT;
     float a_old[IPT];
     int id[IPT];
     bool prot[IPT], live[IPT];
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
         const int j = j0 + t;
-        live[t] = t < ipt && j < n;
-        a_old[t] = live[t] ? ab[j] : 0.f;
-        id[t] = live[t] ? ib[j] : 0;
-        prot[t] = live[t] ? pb[j] != 0 : false;
+        const bool in = j < p.Lcap;
+        a_old[t] = in ? ab[j] : 0.f;
+        id[t] = in ? ib[j] : 0;
+        prot[t] = in ? pb[j] != 0 : false;
     }
-    // merge the logits kernel's partial statistics: thread = (slice q, head h)
-    {
-        const int parts = 1024 / H, h = tid % H, q = tid / H;
-        const float2* sp = stat_partial + (long)b * n_part * H + h;
-        float mn = -INFINITY, zn = 0.f;
-        for (int c = q; c < n_part; c += parts) {
+    constexpr int PF = 8;                            // prefetched 16-byte logit vectors (H <= 32)
+    const bool pf_ok = (H & 3) == 0 && H <= 4 * PF && tid < p.Lcap;
+    f32x4 lpf[PF];
+    if (pf_ok) {
+        const f32x4* l4 = reinterpret_cast<const f32x4*>(lb + (long)tid * H);
+#pragma unroll
+        for (int u = 0; u < PF; ++u) lpf[u] = (4 * u < H) ? l4[u] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // the logits kernel's partial statistics: `parts` consecutive lanes share a head and each takes
+    // a slice of the partials (also independent of the length)
+    const int parts = min(1024 / H, kWave), sh = tid / parts, sq = tid % parts;
+    float mn = -INFINITY, zn = 0.f;
+    if (sh < H) {
+        const float2* sp = stat_partial + (long)b * n_part * H + sh;
+        for (int c = sq; c < n_part; c += parts) {
             const float2 v = sp[(long)c * H];
             const float m2 = fmaxf(mn, v.x);
-            if (m2 > -INFINITY) zn = zn * exp2f(mn - m2) + v.y * exp2f(v.x - m2);
+            if (m2 > -INFINITY) zn = zn * fast_exp2(mn - m2) + v.y * fast_exp2(v.x - m2);
             mn = m2;
         }
-        s_cm[q * H + h] = mn;
-        s_cz[q * H + h] = zn;
-        __syncthreads();
-        float mh = -INFINITY, zh = 0.f;
-        if (tid < H) {
-            for (int c = 0; c < parts; ++c) mh = fmaxf(mh, s_cm[c * H + tid]);
-            for (int c = 0; c < parts; ++c) zh += s_cz[c * H + tid] * exp2f(s_cm[c * H + tid] - mh);
-        }
-        __syncthreads();
-        if (tid < H) { s_cm[tid] = mh; s_cz[tid] = 1.0f / (zh * (float)H); }
-        __syncthreads();
     }
-    // a_t[j] = mean_h softmax ; acc <- decay*acc + a_t
-    float a_new[IPT];
+    const int n = min(max(len[b], 0), p.Lcap);
+    MD_STAMP(0);
+    if (n == 0) {
+        if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
+        return;
+    }
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-        a_new[t] = 0.f;
-        if (live[t]) {
-            const float* lj = lb + (long)(j0 + t) * H;
-            float a = 0.f;
-            for (int hh = 0; hh < H; ++hh) a += exp2f(lj[hh] * kLog2eD - s_cm[hh]) * s_cz[hh];
-            a_new[t] = fmaf(decay, a_old[t], a);
-        }
+        live[t] = j0 + t < n;
+        if (!live[t]) { prot[t] = false; a_old[t] = 0.f; }
     }
+    MD_STAMP(1);
+    // a butterfly over the lanes of a head finishes the merge of the statistics
+    {
+        const int h = sh, q = sq;
+        for (int mm = 1; mm < parts; mm <<= 1) {
+            const float mo = __shfl_xor(mn, mm, kWave), zo = __shfl_xor(zn, mm, kWave);
+            const float m2 = fmaxf(mn, mo);
+            zn = m2 > -INFINITY ? zn * fast_exp2(mn - m2) + zo * fast_exp2(mo - m2) : 0.f;
+            mn = m2;
+        }
+        if (h < H && q == 0) { s_cm[h] = mn; s_cz[h] = 1.0f / (zn * (float)H); }
+        __syncthreads();
+    }
+    MD_STAMP(2);
+    // a_t[j] = mean_h softmax: entries are dealt round-robin to the threads for this phase (balanced);
+    // the first one's logits are already in registers
+    for (int j = tid; j < n; j += blockDim.x) {
+        const float* lj = lb + (long)j * H;
+        float a = 0.f;
+        if (pf_ok) {
+            if (j != tid) {
+                const f32x4* l4 = reinterpret_cast<const f32x4*>(lj);
+#pragma unroll
+                for (int u = 0; u < PF; ++u) lpf[u] = (4 * u < H) ? l4[u] : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int hh = 4 * u;
+                if (hh < H) {
+                    a += fast_exp2(lpf[u].x * kLog2eD - s_cm[hh]) * s_cz[hh];
+                    a += fast_exp2(lpf[u].y * kLog2eD - s_cm[hh + 1]) * s_cz[hh + 1];
+                    a += fast_exp2(lpf[u].z * kLog2eD - s_cm[hh + 2]) * s_cz[hh + 2];
+                    a += fast_exp2(lpf[u].w * kLog2eD - s_cm[hh + 3]) * s_cz[hh + 3];
+                }
+            }
+        } else {
+            for (int hh = 0; hh < H; ++hh) a += fast_exp2(lj[hh] * kLog2eD - s_cm[hh]) * s_cz[hh];
+        }
+        s_at[j] = a;
+    }
+    __syncthreads();
+    // acc <- decay*acc + a_t
+    float a_new[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) a_new[t] = live[t] ? fmaf(decay, a_old[t], s_at[j0 + t]) : 0.f;
     int np = 0;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) np += prot[t];
+    MD_STAMP(3);
     np = block_sum_i(np, s_red);
+    MD_STAMP(4);
 
     bool keep[IPT];
 #pragma unroll
@@ -272,21 +319,23 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
                 keep[t] = live[t] && (prot[t] || (extra > 0 && (key[t] >> sb.shift) >= sb.bound));
         }
     }
-    // holes / movers / evicted: three counters packed into one 64-bit scan (21 bits each)
-    uint64_t cnt = 0;
+    MD_STAMP(5);
+    // holes / movers (16 bits each in one word; both <= Lcap/2 <= 4096) and evicted entries: two scans
+    int cnt_hm = 0, cnt_e = 0;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
         const int j = j0 + t;
         if (live[t]) {
-            if (!keep[t] && j < new_len) cnt += 1ull;
-            if (keep[t] && j >= new_len) cnt += 1ull << 21;
-            if (!keep[t]) cnt += 1ull << 42;
+            if (!keep[t] && j < new_len) cnt_hm += 1;
+            if (keep[t] && j >= new_len) cnt_hm += 1 << 16;
+            if (!keep[t]) cnt_e += 1;
         }
     }
-    uint64_t total;
-    const uint64_t pre = block_exscan_u64(cnt, s_red64, total);
-    int rh = (int)(pre & 0x1FFFFF), rm = (int)((pre >> 21) & 0x1FFFFF), re = (int)(pre >> 42);
-    const int n_mv = (int)((total >> 21) & 0x1FFFFF), n_ev = (int)(total >> 42);
+    int tot_hm, tot_e;
+    const int pre_hm = block_exscan_i(cnt_hm, s_red, tot_hm);
+    int re = block_exscan_i(cnt_e, s_red, tot_e);
+    int rh = pre_hm & 0xFFFF, rm = pre_hm >> 16;
+    const int n_mv = tot_hm >> 16, n_ev = tot_e;
     int mrank[IPT];
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
@@ -298,6 +347,7 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
             if (!keep[t]) { if (evicted_ids) evicted_ids[(long)b * p.Lcap + re] = id[t]; ++re; }
         }
     }
+    MD_STAMP(6);
     __syncthreads();
     // write the scores back; a mover's state goes straight to its hole (no overlap: holes < new_len <= movers)
 #pragma unroll
@@ -314,6 +364,7 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
             ab[j] = a_new[t];
         }
     }
+    MD_STAMP(7);
     if (tid == 0) {
         n_move[b] = n_mv;
         len[b] = new_len;
@@ -366,7 +417,7 @@ __global__ __launch_bounds__(1024) void decode_select_kernel(
         const float mh = s_max[h];
         float z = 0.f;
         if (part < parts)
-            for (int j = part; j < n; j += parts) z += exp2f((lb[(long)j * H + h] - mh) * kLog2eD);
+            for (int j = part; j < n; j += parts) z += fast_exp2((lb[(long)j * H + h] - mh) * kLog2eD);
         if (part < parts) s_part[part * H + h] = z;
         __syncthreads();
         if (tid < H) {
@@ -379,7 +430,7 @@ __global__ __launch_bounds__(1024) void decode_select_kernel(
     // a_t[j] = mean_h softmax ; acc <- decay*acc + a_t
     for (int j = tid; j < n; j += blockDim.x) {
         float a = 0.f;
-        for (int hh = 0; hh < H; ++hh) a += exp2f((lb[(long)j * H + hh] - s_max[hh]) * kLog2eD) * s_inv[hh];
+        for (int hh = 0; hh < H; ++hh) a += fast_exp2((lb[(long)j * H + hh] - s_max[hh]) * kLog2eD) * s_inv[hh];
         ab[j] = fmaf(decay, ab[j], a);
     }
     __syncthreads();
@@ -512,6 +563,12 @@ int check_decode_dims(const char* who, int B, int Lcap, int H, int d) {
 
 using namespace md;
 
+#ifdef MD_TRACE
+extern "C" int mustdrop_debug_trace(unsigned long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(md::g_trace), sizeof(unsigned long long) * 32);
+}
+#endif
+
 extern "C" size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H) {
     if (B <= 0 || Lcap <= 0 || H <= 0) return 0;
     return carve_decode(nullptr, B, Lcap, H).bytes;
@@ -580,7 +637,7 @@ extern "C" int mustdrop_decode_evict(
         }
     }
     if (n_part > 0 && Lcap <= 8192) {
-        const size_t lds = sizeof(int) * (size_t)Lcap;
+        const size_t lds = 2 * sizeof(int) * (size_t)Lcap;
         const int ipt = (Lcap + 1023) / 1024;
 #define MD_SELECT_FAST(I)                                                                                          \
     MD_LAUNCH("decode_select", st, (decode_select_fast_kernel<I><<<B, 1024, lds, st>>>(                             \

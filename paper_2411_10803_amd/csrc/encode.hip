@@ -13,6 +13,7 @@
 namespace md {
 namespace {
 
+constexpr float kLog2eE = 1.4426950408889634f;
 constexpr int kMaxWindow = 16;
 constexpr int kMaxClsHeads = 256;
 
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void cls_logits_kernel(
             for (int e = 0; e < VEC; ++e) part = fmaf(qv[e], kv[e], part);
         }
         if (vph < kWave) {
-            for (int m = 1; m < vph; m <<= 1) part += __shfl_xor(part, m, kWave);
+            part = group_sum_rt(part, vph);
             if (idx < nvec && (lane & (vph - 1)) == 0) out[(size_t)(idx / vph) * (p.M + 1)] = part * scale;
         } else {
             acc += part;
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
             mx = wave_max(mx);
             float z = 0.f;
             for (int j = lane; j <= M; j += kWave)
-                if (j == 0 || !vb || vb[j - 1]) z += __expf(l[j] - mx);
+                if (j == 0 || !vb || vb[j - 1]) z += fast_exp2(kLog2eE * (l[j] - mx));
             z = wave_sum(z);
             if (lane == 0) { s_max[h] = mx; s_inv[h] = 1.0f / (z * (float)p.Hc); }
         }
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
             float a = -INFINITY;
             if (!vb || vb[j]) {
                 a = 0.f;
-                for (int h = 0; h < p.Hc; ++h) a += __expf(lg[(size_t)h * (M + 1) + j + 1] - s_max[h]) * s_inv[h];
+                for (int h = 0; h < p.Hc; ++h) a += fast_exp2(kLog2eE * (lg[(size_t)h * (M + 1) + j + 1] - s_max[h])) * s_inv[h];
             }
             acls_b[j] = a;
             if (a_cls_out) a_cls_out[(size_t)b * M + j] = a;

@@ -28,20 +28,81 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
+// v_exp_f32 / v_log_f32: base-2, about 1 ulp, results below 2^-126 flush to zero.  Used where the
+// argument is a (score - max) difference, so neither overflow nor denormal results matter.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Cross-lane steps on the DPP path (one VALU instruction each, no LDS round trip).
+// quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140:
+// after the four steps every lane of a 16-lane row holds the row's result; the four rows are then
+// combined in a fixed order from lanes 0, 16, 32, 48.
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF>
+__device__ __forceinline__ int dpp_i(int old, int src) {
+    return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, BANK_MASK, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v), __float_as_int(v))); }
+
+__device__ __forceinline__ float lane_bcast_f(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    v += dpp_f<0xB1>(v); v += dpp_f<0x4E>(v); v += dpp_f<0x141>(v); v += dpp_f<0x140>(v);
+    return (lane_bcast_f(v, 0) + lane_bcast_f(v, 16)) + (lane_bcast_f(v, 32) + lane_bcast_f(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
-    return v;
+    v = fmaxf(v, dpp_f<0xB1>(v)); v = fmaxf(v, dpp_f<0x4E>(v)); v = fmaxf(v, dpp_f<0x141>(v)); v = fmaxf(v, dpp_f<0x140>(v));
+    return fmaxf(fmaxf(lane_bcast_f(v, 0), lane_bcast_f(v, 16)), fmaxf(lane_bcast_f(v, 32), lane_bcast_f(v, 48)));
 }
 __device__ __forceinline__ int wave_sum_i(int v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    v += dpp_i<0xB1>(v, v); v += dpp_i<0x4E>(v, v); v += dpp_i<0x141>(v, v); v += dpp_i<0x140>(v, v);
+    return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+           (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, (uint32_t)dpp_i<0xB1>((int)v, (int)v)); v = min(v, (uint32_t)dpp_i<0x4E>((int)v, (int)v));
+    v = min(v, (uint32_t)dpp_i<0x141>((int)v, (int)v)); v = min(v, (uint32_t)dpp_i<0x140>((int)v, (int)v));
+    const uint32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const uint32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return min(min(a, b), min(c, d));
+}
+// Sum over aligned groups of G consecutive lanes (G a power of two); every lane of a group gets the
+// group's sum.  Up to 16 lanes this is pure DPP; wider groups finish with lane exchanges.
+template <int G>
+__device__ __forceinline__ float group_sum(float v) {
+    if (G >= 2) v += dpp_f<0xB1>(v);
+    if (G >= 4) v += dpp_f<0x4E>(v);
+    if (G >= 8) v += dpp_f<0x141>(v);
+    if (G >= 16) v += dpp_f<0x140>(v);
+    if (G >= 32) v += __shfl_xor(v, 16, kWave);
+    if (G >= 64) v += __shfl_xor(v, 32, kWave);
     return v;
+}
+__device__ __forceinline__ float group_sum_rt(float v, int g) {
+    if (g >= 2) v += dpp_f<0xB1>(v);
+    if (g >= 4) v += dpp_f<0x4E>(v);
+    if (g >= 8) v += dpp_f<0x141>(v);
+    if (g >= 16) v += dpp_f<0x140>(v);
+    if (g >= 32) v += __shfl_xor(v, 16, kWave);
+    if (g >= 64) v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+// 64-bit minimum: first the high words, then the low words of the lanes that hold the winning high word
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
+    const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    const uint32_t mh = wave_min_u32(hi);
+    const uint32_t ml = wave_min_u32(hi == mh ? lo : 0xFFFFFFFFu);
+    return ((uint64_t)mh << 32) | ml;
+}
+// Inclusive prefix sum over the 64 lanes: row_shr 1, 2, 4, 8 (0x111..0x118; lanes without a source
+// add 0), then row_bcast15 into rows 1 and 3 and row_bcast31 into rows 2 and 3.
+__device__ __forceinline__ int wave_incl_scan_i(int s) {
+    s += dpp_i<0x111>(0, s); s += dpp_i<0x112>(0, s); s += dpp_i<0x114>(0, s); s += dpp_i<0x118>(0, s);
+    s += dpp_i<0x142, 0xA>(0, s); s += dpp_i<0x143, 0xC>(0, s);
+    return s;
 }
 
 // Block reductions: fixed tree (lanes by xor butterfly, then waves in index order) -> the result is
@@ -134,14 +195,9 @@ __device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int 
             int c[4], s = 0;
 #pragma unroll
             for (int t = 0; t < 4; ++t) { c[t] = hist[255 - (lane * 4 + t)]; s += c[t]; }
-            int incl = s;                                   // inclusive scan over lanes
-#pragma unroll
-            for (int m = 1; m < kWave; m <<= 1) {
-                const int o = __shfl_up(incl, m, kWave);
-                if (lane >= m) incl += o;
-            }
+            const int incl = wave_incl_scan_i(s);           // inclusive scan over lanes
             int run = incl - s;                             // items in strictly higher digits
-            const int total = __shfl(incl, kWave - 1, kWave);
+            const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
             if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }   // fewer than k items
             if (total >= kk) {
 #pragma unroll
@@ -190,14 +246,9 @@ __device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&k
             int c[4], s = 0;
 #pragma unroll
             for (int t = 0; t < 4; ++t) { c[t] = hist[255 - (lane * 4 + t)]; s += c[t]; }
-            int incl = s;
-#pragma unroll
-            for (int m = 1; m < kWave; m <<= 1) {
-                const int o = __shfl_up(incl, m, kWave);
-                if (lane >= m) incl += o;
-            }
+            const int incl = wave_incl_scan_i(s);
             int run = incl - s;
-            const int total = __shfl(incl, kWave - 1, kWave);
+            const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
             if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }
             if (total >= kk) {
 #pragma unroll
@@ -221,19 +272,9 @@ __device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&k
     return SelectBound{prefix, shift};
 }
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
-    const uint32_t lo = __shfl_xor((uint32_t)v, m, kWave), hi = __shfl_xor((uint32_t)(v >> 32), m, kWave);
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int m) {
-    const uint32_t lo = __shfl_up((uint32_t)v, m, kWave), hi = __shfl_up((uint32_t)(v >> 32), m, kWave);
-    return ((uint64_t)hi << 32) | lo;
-}
-
 // Block-wide minimum of 64-bit values (same result on every thread).  `red` holds >= blockDim.x/64 entries.
 __device__ __forceinline__ uint64_t block_min_u64(uint64_t v, uint64_t* red) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) { const uint64_t o = shfl_xor_u64(v, m); v = o < v ? o : v; }
+    v = wave_min_u64(v);
     __syncthreads();
     if (lane_id() == 0) red[wave_id()] = v;
     __syncthreads();
@@ -243,23 +284,17 @@ __device__ __forceinline__ uint64_t block_min_u64(uint64_t v, uint64_t* red) {
     return t;
 }
 
-// Exclusive prefix sum over the block, in thread order, of a 64-bit value (used with several small
-// counters packed into one word).  Returns this thread's prefix; `total` = block sum.
-__device__ __forceinline__ uint64_t block_exscan_u64(uint64_t v, uint64_t* red, uint64_t& total) {
-    const int lane = lane_id();
-    uint64_t incl = v;
-#pragma unroll
-    for (int m = 1; m < kWave; m <<= 1) {
-        const uint64_t o = shfl_up_u64(incl, m);
-        if (lane >= m) incl += o;
-    }
+// Exclusive prefix sum over the block, in thread order.  Returns this thread's prefix; `total` =
+// block sum.  `red` holds >= blockDim.x/64 ints.  Several small counters can share the word.
+__device__ __forceinline__ int block_exscan_i(int v, int* red, int& total) {
+    const int incl = wave_incl_scan_i(v);
     __syncthreads();
-    if (lane == kWave - 1) red[wave_id()] = incl;
+    if (lane_id() == kWave - 1) red[wave_id()] = incl;
     __syncthreads();
-    uint64_t off = 0, tot = 0;
+    int off = 0, tot = 0;
     const int nw = blockDim.x >> 6, w = wave_id();
     for (int i = 0; i < nw; ++i) {
-        const uint64_t c = red[i];
+        const int c = red[i];
         if (i < w) off += c;
         tot += c;
     }

@@ -75,7 +75,7 @@ struct OperandTile {
 // Row statistics folded into one constant: a probability of the head mean is
 // exp2(s*scale*log2e + c) with c = -m - log2(Z) - log2(H); text rows beyond txt_len get -inf (-> 0).
 __device__ __forceinline__ float fold_stats(float m, float z, bool row_ok, int H) {
-    return (row_ok && z > 0.f) ? -m - log2f(z) - log2f((float)H) : -INFINITY;
+    return (row_ok && z > 0.f) ? -m - fast_log2(z) - fast_log2((float)H) : -INFINITY;
 }
 
 // LDS traffic between lanes of one wave: LDS operations of a wave execute in order, the fence keeps
@@ -179,8 +179,8 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
             if (mn > -INFINITY) {
                 float s = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s += exp2f(t[r] - mn);
-                z[nb] = z[nb] * exp2f(m[nb] - mn) + s;
+                for (int r = 0; r < 16; ++r) s += fast_exp2(t[r] - mn);
+                z[nb] = z[nb] * fast_exp2(m[nb] - mn) + s;
                 m[nb] = mn;
             }
         }
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         const float mo = __shfl_xor(m[nb], 32, kWave), zo = __shfl_xor(z[nb], 32, kWave);
         const float mn = fmaxf(m[nb], mo);
         float zn = 0.f;
-        if (mn > -INFINITY) zn = z[nb] * exp2f(m[nb] - mn) + zo * exp2f(mo - mn);
+        if (mn > -INFINITY) zn = z[nb] * fast_exp2(m[nb] - mn) + zo * fast_exp2(mo - mn);
         if (lane < 32) { s_m[wv][32 * nb + lane] = mn; s_z[wv][32 * nb + lane] = zn; }
     }
     __syncthreads();
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         float zn = 0.f;
         if (mn > -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < 4; ++w) zn += s_z[w][i] * exp2f(s_m[w][i] - mn);
+            for (int w = 0; w < 4; ++w) zn += s_z[w][i] * fast_exp2(s_m[w][i] - mn);
         }
         if (i_base + i < p.Npad) {
             if (p.nch == 1)     // the only chunk: fold the statistics right away (see fold_stats)
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(256) void prefill_cstat_kernel(
     for (int c = 0; c < p.nch; ++c) {
         const float2 v = pp[(long)c * p.Npad];
         const float m2 = fmaxf(mn, v.x);
-        if (m2 > -INFINITY) zn = zn * exp2f(mn - m2) + v.y * exp2f(v.x - m2);
+        if (m2 > -INFINITY) zn = zn * fast_exp2(mn - m2) + v.y * fast_exp2(v.x - m2);
         mn = m2;
     }
     cstat[e] = fold_stats(mn, zn, i < tl, p.H);
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
                     // text rows beyond txt_len have zero query fragments and c = -inf: exp2(-inf) = 0 exactly
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        a_acc[nb < NB ? nb : 0][r] += exp2f(fmaf(acc[r], scale_log2e, c[e]));
+                        a_acc[nb < NB ? nb : 0][r] += fast_exp2(fmaf(acc[r], scale_log2e, c[e]));
                 }
             }
         }
