@@ -169,9 +169,11 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     }
 }
 
-// Selection with everything in registers: thread t owns the consecutive entries [t*IPT, (t+1)*IPT),
-// IPT >= ceil(Lcap / 1024).  One round of global loads, then block-level phases only.
-template <int IPT>
+// Selection with everything in registers.  Entries are dealt round-robin: thread t owns the entries
+// t, t+1024, ... (coalesced loads; the first one does not depend on the live length, so it is
+// requested before the length arrives).  IPT >= ceil(Lcap / 1024).  One round of global loads for
+// the common case, then block-level phases only.
+template <int IPT, int LPE>
 __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     DecodeDims p, const float* __restrict__ logits, const float2* __restrict__ stat_partial, int n_part,
     float decay, int budget,
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     __shared__ int s_red[16];
     __shared__ int s_hist[256];
     __shared__ uint64_t s_red64[16];
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id();
     const int H = p.H;
     const float* lb = logits + (long)b * p.Lcap * H;
     float* ab = acc + (long)b * p.Lcap;
@@ -193,32 +195,33 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     uint8_t* pb = protect + (long)b * p.Lcap;
     int32_t* hb = holes + (long)b * p.Lcap;
     int32_t* mvb = movers + (long)b * p.Lcap;
-    // Everything this thread needs from memory is requested up front, before the sample's length is
-    // known: its own entries' state (entries [tid*IPT, tid*IPT+IPT), fixed by the capacity) and the
-    // logits of entry `tid` for the score phase.  Slots beyond the live length hold stale but
-    // readable data; they are masked once `n` has arrived.
-    const int j0 = tid * IPT;
+
+    // ---- requests that do not depend on the live length
     float a_old[IPT];
     int id[IPT];
     bool prot[IPT], live[IPT];
+    // Logits are read the way they lie in memory: a wave takes 64 consecutive entries (64*H floats)
+    // with LPE = H/4 fully coalesced 16-byte loads per lane; lane l then holds heads 4*(l%LPE)..+3 of
+    // the entries u*(64/LPE) + l/LPE, u = 0..LPE-1.
+    constexpr int PFR = IPT < 2 ? IPT : 2;           // rounds requested before the length is known
+    constexpr int EPI = kWave / LPE;                 // entries per load instruction
+    f32x4 lpf[PFR][LPE];
 #pragma unroll
-    for (int t = 0; t < IPT; ++t) {
-        const int j = j0 + t;
-        const bool in = j < p.Lcap;
+    for (int t = 0; t < PFR; ++t) {
+        const int j = tid + t * 1024;
+        const bool in = j < p.Lcap;                  // readable whatever the live length is
         a_old[t] = in ? ab[j] : 0.f;
         id[t] = in ? ib[j] : 0;
         prot[t] = in ? pb[j] != 0 : false;
-    }
-    constexpr int PF = 8;                            // prefetched 16-byte logit vectors (H <= 32)
-    const bool pf_ok = (H & 3) == 0 && H <= 4 * PF && tid < p.Lcap;
-    f32x4 lpf[PF];
-    if (pf_ok) {
-        const f32x4* l4 = reinterpret_cast<const f32x4*>(lb + (long)tid * H);
+        const int base = t * 1024 + wv * kWave;
 #pragma unroll
-        for (int u = 0; u < PF; ++u) lpf[u] = (4 * u < H) ? l4[u] : f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int u = 0; u < LPE; ++u) {
+            const int e = base + u * EPI + lane / LPE;
+            lpf[t][u] = e < p.Lcap ? reinterpret_cast<const f32x4*>(lb + (long)base * H)[u * kWave + lane]
+                                   : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
     }
-    // the logits kernel's partial statistics: `parts` consecutive lanes share a head and each takes
-    // a slice of the partials (also independent of the length)
+    // the logits kernel's partial statistics: `parts` consecutive lanes share a head, each takes a slice
     const int parts = min(1024 / H, kWave), sh = tid / parts, sq = tid % parts;
     float mn = -INFINITY, zn = 0.f;
     if (sh < H) {
@@ -237,122 +240,154 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         return;
     }
 #pragma unroll
-    for (int t = 0; t < IPT; ++t) {
-        live[t] = j0 + t < n;
+    for (int t = 0; t < PFR; ++t) {
+        live[t] = tid + t * 1024 < n;
         if (!live[t]) { prot[t] = false; a_old[t] = 0.f; }
     }
-    MD_STAMP(1);
-    // a butterfly over the lanes of a head finishes the merge of the statistics
-    {
-        const int h = sh, q = sq;
-        for (int mm = 1; mm < parts; mm <<= 1) {
-            const float mo = __shfl_xor(mn, mm, kWave), zo = __shfl_xor(zn, mm, kWave);
-            const float m2 = fmaxf(mn, mo);
-            zn = m2 > -INFINITY ? zn * fast_exp2(mn - m2) + zo * fast_exp2(mo - m2) : 0.f;
-            mn = m2;
-        }
-        if (h < H && q == 0) { s_cm[h] = mn; s_cz[h] = 1.0f / (zn * (float)H); }
-        __syncthreads();
+#pragma unroll
+    for (int t = PFR; t < IPT; ++t) {                // further rounds only for long caches
+        const int j = tid + t * 1024;
+        live[t] = j < n;
+        a_old[t] = live[t] ? ab[j] : 0.f;
+        id[t] = live[t] ? ib[j] : 0;
+        prot[t] = live[t] ? pb[j] != 0 : false;
     }
-    MD_STAMP(2);
-    // a_t[j] = mean_h softmax: entries are dealt round-robin to the threads for this phase (balanced);
-    // the first one's logits are already in registers
-    for (int j = tid; j < n; j += blockDim.x) {
-        const float* lj = lb + (long)j * H;
-        float a = 0.f;
-        if (pf_ok) {
-            if (j != tid) {
-                const f32x4* l4 = reinterpret_cast<const f32x4*>(lj);
-#pragma unroll
-                for (int u = 0; u < PF; ++u) lpf[u] = (4 * u < H) ? l4[u] : f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-            for (int u = 0; u < PF; ++u) {
-                const int hh = 4 * u;
-                if (hh < H) {
-                    a += fast_exp2(lpf[u].x * kLog2eD - s_cm[hh]) * s_cz[hh];
-                    a += fast_exp2(lpf[u].y * kLog2eD - s_cm[hh + 1]) * s_cz[hh + 1];
-                    a += fast_exp2(lpf[u].z * kLog2eD - s_cm[hh + 2]) * s_cz[hh + 2];
-                    a += fast_exp2(lpf[u].w * kLog2eD - s_cm[hh + 3]) * s_cz[hh + 3];
-                }
-            }
-        } else {
-            for (int hh = 0; hh < H; ++hh) a += fast_exp2(lj[hh] * kLog2eD - s_cm[hh]) * s_cz[hh];
-        }
-        s_at[j] = a;
+    MD_STAMP(1);
+    // the lanes of a head finish the merge: group maximum, then the group sum of the rescaled sums
+    {
+        float gm = mn;
+        if (parts >= 2) gm = fmaxf(gm, dpp_f<0xB1>(gm));
+        if (parts >= 4) gm = fmaxf(gm, dpp_f<0x4E>(gm));
+        if (parts >= 8) gm = fmaxf(gm, dpp_f<0x141>(gm));
+        if (parts >= 16) gm = fmaxf(gm, dpp_f<0x140>(gm));
+        if (parts >= 32) gm = fmaxf(gm, __shfl_xor(gm, 16, kWave));
+        if (parts >= 64) gm = fmaxf(gm, __shfl_xor(gm, 32, kWave));
+        const float zs = group_sum_rt(gm > -INFINITY ? zn * fast_exp2(mn - gm) : 0.f, parts);
+        if (sh < H && sq == 0) { s_cm[sh] = gm; s_cz[sh] = __frcp_rn(zs * (float)H); }
     }
     __syncthreads();
-    // acc <- decay*acc + a_t
+    MD_STAMP(2);
+    // a_t[j] = mean_h softmax; acc <- decay*acc + a_t.  A lane always works on the same four heads,
+    // so their statistics sit in registers; LPE lanes add up an entry's heads and one of them drops
+    // the result in LDS, from where the entry's owner picks it up (same wave: LDS keeps program order).
     float a_new[IPT];
+    {
+        float cm[4], cz[4];
 #pragma unroll
-    for (int t = 0; t < IPT; ++t) a_new[t] = live[t] ? fmaf(decay, a_old[t], s_at[j0 + t]) : 0.f;
+        for (int c = 0; c < 4; ++c) { cm[c] = s_cm[4 * (lane % LPE) + c]; cz[c] = s_cz[4 * (lane % LPE) + c]; }
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            a_new[t] = 0.f;
+            if (t * 1024 >= n) continue;             // block-uniform: no entries in this round
+            const int base = t * 1024 + wv * kWave;
+#pragma unroll
+            for (int u = 0; u < LPE; ++u) {
+                const int e = base + u * EPI + lane / LPE;
+                f32x4 v;
+                if (t < PFR) v = lpf[t < PFR ? t : 0][u];
+                else v = e < n ? reinterpret_cast<const f32x4*>(lb + (long)base * H)[u * kWave + lane] : f32x4{0.f, 0.f, 0.f, 0.f};
+                float part = fast_exp2(fmaf(v.x, kLog2eD, -cm[0])) * cz[0];
+                part = fmaf(fast_exp2(fmaf(v.y, kLog2eD, -cm[1])), cz[1], part);
+                part = fmaf(fast_exp2(fmaf(v.z, kLog2eD, -cm[2])), cz[2], part);
+                part = fmaf(fast_exp2(fmaf(v.w, kLog2eD, -cm[3])), cz[3], part);
+                part = group_sum<LPE>(part);
+                if (lane % LPE == 0 && e < p.Lcap) s_at[e] = part;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int j = tid + t * 1024;
+            a_new[t] = live[t] ? fmaf(decay, a_old[t], s_at[j]) : 0.f;
+        }
+    }
+    MD_STAMP(3);
     int np = 0;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) np += prot[t];
-    MD_STAMP(3);
     np = block_sum_i(np, s_red);
     MD_STAMP(4);
 
+    if (n <= budget) {                               // nothing leaves: only the scores change
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) if (live[t]) ab[tid + t * 1024] = a_new[t];
+        if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
+        return;
+    }
+    const int nu = n - np;
+    const int extra = min(max(budget - np, 0), nu);
+    const int new_len = np + extra;
+    uint64_t key[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) key[t] = (live[t] && !prot[t]) ? rank_key(a_new[t], id[t]) : 0ull;
+
+    if (nu - extra == 1) {
+        // Steady state of a decode loop: exactly one entry leaves -- the smallest key.  If it is not
+        // the last live slot, the last entry (a survivor) moves into its place.
+        uint64_t mine = ~0ull;
+        int mine_slot = 0;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) if (key[t] != 0 && key[t] < mine) { mine = key[t]; mine_slot = tid + t * 1024; }
+        const uint64_t victim = block_min_u64(mine, s_red64);
+        __shared__ int s_vslot;
+        if (mine == victim) s_vslot = mine_slot;     // keys are unique: one writer
+        __syncthreads();
+        const int vslot = s_vslot, last = n - 1;
+        MD_STAMP(5);
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const int j = tid + t * 1024;
+            if (!live[t]) continue;
+            if (j == vslot) {
+                if (evicted_ids) evicted_ids[(long)b * p.Lcap] = id[t];
+                if (j == last) ab[j] = a_new[t];     // stays behind the new end, as the oracle leaves it
+            } else if (j == last && vslot != last) {
+                ab[vslot] = a_new[t]; ib[vslot] = id[t]; pb[vslot] = prot[t] ? 1 : 0;
+                ab[j] = a_new[t];
+                hb[0] = vslot; mvb[0] = last;
+            } else {
+                ab[j] = a_new[t];
+            }
+        }
+        MD_STAMP(7);
+        if (tid == 0) {
+            n_move[b] = vslot != last ? 1 : 0;
+            len[b] = new_len;
+            if (evicted_count) evicted_count[b] = 1;
+        }
+        return;
+    }
+
+    const SelectBound sb = block_radix_select_reg<IPT>(key, extra, s_hist);
     bool keep[IPT];
 #pragma unroll
-    for (int t = 0; t < IPT; ++t) keep[t] = live[t];
-    int new_len = n;
-    if (n > budget) {
-        const int nu = n - np;
-        const int extra = min(max(budget - np, 0), nu);
-        new_len = np + extra;
-        uint64_t key[IPT];
-#pragma unroll
-        for (int t = 0; t < IPT; ++t) key[t] = (live[t] && !prot[t]) ? rank_key(a_new[t], id[t]) : 0ull;
-        if (nu - extra == 1) {
-            // steady state of a decode loop: exactly one entry leaves -> the smallest key
-            uint64_t mine = ~0ull;
-#pragma unroll
-            for (int t = 0; t < IPT; ++t) if (key[t] != 0 && key[t] < mine) mine = key[t];
-            const uint64_t victim = block_min_u64(mine, s_red64);
-#pragma unroll
-            for (int t = 0; t < IPT; ++t) keep[t] = live[t] && key[t] != victim;
-        } else {
-            const SelectBound sb = block_radix_select_reg<IPT>(key, extra, s_hist);
-#pragma unroll
-            for (int t = 0; t < IPT; ++t)
-                keep[t] = live[t] && (prot[t] || (extra > 0 && (key[t] >> sb.shift) >= sb.bound));
-        }
-    }
+    for (int t = 0; t < IPT; ++t)
+        keep[t] = live[t] && (prot[t] || (extra > 0 && (key[t] >> sb.shift) >= sb.bound));
     MD_STAMP(5);
-    // holes / movers (16 bits each in one word; both <= Lcap/2 <= 4096) and evicted entries: two scans
-    int cnt_hm = 0, cnt_e = 0;
-#pragma unroll
-    for (int t = 0; t < IPT; ++t) {
-        const int j = j0 + t;
-        if (live[t]) {
-            if (!keep[t] && j < new_len) cnt_hm += 1;
-            if (keep[t] && j >= new_len) cnt_hm += 1 << 16;
-            if (!keep[t]) cnt_e += 1;
-        }
-    }
-    int tot_hm, tot_e;
-    const int pre_hm = block_exscan_i(cnt_hm, s_red, tot_hm);
-    int re = block_exscan_i(cnt_e, s_red, tot_e);
-    int rh = pre_hm & 0xFFFF, rm = pre_hm >> 16;
-    const int n_mv = tot_hm >> 16, n_ev = tot_e;
+    // hole / mover / evicted lists in ascending slot order: one pass of block scans per round of entries
+    int run_h = 0, run_m = 0, run_e = 0;
     int mrank[IPT];
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-        const int j = j0 + t;
         mrank[t] = -1;
-        if (live[t]) {
-            if (!keep[t] && j < new_len) { s_holes[rh] = j; hb[rh] = j; ++rh; }
-            if (keep[t] && j >= new_len) { mrank[t] = rm; mvb[rm] = j; ++rm; }
-            if (!keep[t]) { if (evicted_ids) evicted_ids[(long)b * p.Lcap + re] = id[t]; ++re; }
-        }
+        if (t * 1024 >= n) continue;                 // block-uniform
+        const int j = tid + t * 1024;
+        const bool is_hole = live[t] && !keep[t] && j < new_len;
+        const bool is_mover = live[t] && keep[t] && j >= new_len;
+        const bool is_ev = live[t] && !keep[t];
+        int tot_hm, tot_e;
+        const int pre_hm = block_exscan_i((is_hole ? 1 : 0) | (is_mover ? 1 << 16 : 0), s_red, tot_hm);
+        const int pre_e = block_exscan_i(is_ev ? 1 : 0, s_red, tot_e);
+        if (is_hole) { const int r = run_h + (pre_hm & 0xFFFF); s_holes[r] = j; hb[r] = j; }
+        if (is_mover) { mrank[t] = run_m + (pre_hm >> 16); mvb[mrank[t]] = j; }
+        if (is_ev && evicted_ids) evicted_ids[(long)b * p.Lcap + run_e + pre_e] = id[t];
+        run_h += tot_hm & 0xFFFF; run_m += tot_hm >> 16; run_e += tot_e;
     }
     MD_STAMP(6);
     __syncthreads();
     // write the scores back; a mover's state goes straight to its hole (no overlap: holes < new_len <= movers)
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-        const int j = j0 + t;
+        const int j = tid + t * 1024;
         if (!live[t]) continue;
         if (mrank[t] >= 0) {
             const int dst = s_holes[mrank[t]];
@@ -366,9 +401,9 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     }
     MD_STAMP(7);
     if (tid == 0) {
-        n_move[b] = n_mv;
+        n_move[b] = run_m;
         len[b] = new_len;
-        if (evicted_count) evicted_count[b] = n_ev;
+        if (evicted_count) evicted_count[b] = run_e;
     }
 }
 
@@ -636,17 +671,27 @@ extern "C" int mustdrop_decode_evict(
             default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
         }
     }
-    if (n_part > 0 && Lcap <= 8192) {
+    const bool fast_h = H == 4 || H == 8 || H == 16 || H == 32 || H == 64;
+    if (n_part > 0 && Lcap <= 8192 && fast_h) {
         const size_t lds = 2 * sizeof(int) * (size_t)Lcap;
         const int ipt = (Lcap + 1023) / 1024;
-#define MD_SELECT_FAST(I)                                                                                          \
-    MD_LAUNCH("decode_select", st, (decode_select_fast_kernel<I><<<B, 1024, lds, st>>>(                             \
+#define MD_SELECT_FAST(I, E)                                                                                       \
+    MD_LAUNCH("decode_select", st, (decode_select_fast_kernel<I, E><<<B, 1024, lds, st>>>(                          \
         p, w.logits, w.stat_partial, n_part, decay, budget, acc, ids, protect, len, w.holes, w.movers, w.n_move,   \
         evicted_ids, evicted_count)))
-        if (ipt <= 1) MD_SELECT_FAST(1);
-        else if (ipt <= 2) MD_SELECT_FAST(2);
-        else if (ipt <= 4) MD_SELECT_FAST(4);
-        else MD_SELECT_FAST(8);
+#define MD_SELECT_FAST_H(I)                                                                                        \
+    switch (H) {                                                                                                   \
+        case 4: MD_SELECT_FAST(I, 1); break;                                                                       \
+        case 8: MD_SELECT_FAST(I, 2); break;                                                                       \
+        case 16: MD_SELECT_FAST(I, 4); break;                                                                      \
+        case 32: MD_SELECT_FAST(I, 8); break;                                                                      \
+        default: MD_SELECT_FAST(I, 16); break;                                                                     \
+    }
+        if (ipt <= 1) { MD_SELECT_FAST_H(1) }
+        else if (ipt <= 2) { MD_SELECT_FAST_H(2) }
+        else if (ipt <= 4) { MD_SELECT_FAST_H(4) }
+        else { MD_SELECT_FAST_H(8) }
+#undef MD_SELECT_FAST_H
 #undef MD_SELECT_FAST
     } else {
         const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);

@@ -105,37 +105,41 @@ __device__ __forceinline__ int wave_incl_scan_i(int s) {
     return s;
 }
 
-// Block reductions: fixed tree (lanes by xor butterfly, then waves in index order) -> the result is
-// the same on every run and on every thread.  `red` holds >= blockDim.x/64 floats.
+// Block reductions: fixed tree (lanes by DPP steps, then the per-wave results -- one per lane --
+// by the same steps) -> the result is the same on every run and on every thread.
+// `red` holds >= blockDim.x/64 entries (at most 16 waves per block).
 __device__ __forceinline__ float block_sum(float v, float* red) {
     v = wave_sum(v);
     __syncthreads();
     if (lane_id() == 0) red[wave_id()] = v;
     __syncthreads();
-    float t = 0.f;
     const int nw = blockDim.x >> 6;
-    for (int w = 0; w < nw; ++w) t += red[w];
-    return t;
+    return wave_sum(lane_id() < nw ? red[lane_id()] : 0.f);
 }
 __device__ __forceinline__ float block_max(float v, float* red) {
     v = wave_max(v);
     __syncthreads();
     if (lane_id() == 0) red[wave_id()] = v;
     __syncthreads();
-    float t = -INFINITY;
     const int nw = blockDim.x >> 6;
-    for (int w = 0; w < nw; ++w) t = fmaxf(t, red[w]);
-    return t;
+    return wave_max(lane_id() < nw ? red[lane_id()] : -INFINITY);
 }
 __device__ __forceinline__ int block_sum_i(int v, int* red) {
     v = wave_sum_i(v);
     __syncthreads();
     if (lane_id() == 0) red[wave_id()] = v;
     __syncthreads();
-    int t = 0;
     const int nw = blockDim.x >> 6;
-    for (int w = 0; w < nw; ++w) t += red[w];
-    return t;
+    return wave_sum_i(lane_id() < nw ? red[lane_id()] : 0);
+}
+
+// Prefix of this wave among the per-wave totals in `red` (one LDS read per lane + a lane scan).
+__device__ __forceinline__ int wave_prefix_of_totals(const int* red, int& total) {
+    const int nw = blockDim.x >> 6, lane = lane_id(), w = wave_id();
+    const int mine = lane < nw ? red[lane] : 0;
+    const int incl = wave_incl_scan_i(mine);
+    total = __builtin_amdgcn_readlane(incl, kWave - 1);
+    return __builtin_amdgcn_readlane(incl, w) - __builtin_amdgcn_readlane(mine, w);
 }
 
 // Exclusive scan of a 0/1 flag over the block, in thread order.  Returns this thread's rank and
@@ -147,15 +151,7 @@ __device__ __forceinline__ int block_rank(bool flag, int* red, int& total) {
     __syncthreads();
     if (lane == 0) red[wave_id()] = __popcll(bal);
     __syncthreads();
-    int off = 0, tot = 0;
-    const int nw = blockDim.x >> 6, w = wave_id();
-    for (int i = 0; i < nw; ++i) {
-        const int c = red[i];
-        if (i < w) off += c;
-        tot += c;
-    }
-    total = tot;
-    return off + below;
+    return wave_prefix_of_totals(red, total) + below;
 }
 
 // Order-preserving composite key: larger score first, then smaller tie value first.
@@ -278,10 +274,8 @@ __device__ __forceinline__ uint64_t block_min_u64(uint64_t v, uint64_t* red) {
     __syncthreads();
     if (lane_id() == 0) red[wave_id()] = v;
     __syncthreads();
-    uint64_t t = ~0ull;
     const int nw = blockDim.x >> 6;
-    for (int w = 0; w < nw; ++w) t = red[w] < t ? red[w] : t;
-    return t;
+    return wave_min_u64(lane_id() < nw ? red[lane_id()] : ~0ull);
 }
 
 // Exclusive prefix sum over the block, in thread order.  Returns this thread's prefix; `total` =
@@ -291,15 +285,7 @@ __device__ __forceinline__ int block_exscan_i(int v, int* red, int& total) {
     __syncthreads();
     if (lane_id() == kWave - 1) red[wave_id()] = incl;
     __syncthreads();
-    int off = 0, tot = 0;
-    const int nw = blockDim.x >> 6, w = wave_id();
-    for (int i = 0; i < nw; ++i) {
-        const int c = red[i];
-        if (i < w) off += c;
-        tot += c;
-    }
-    total = tot;
-    return off + incl - v;
+    return wave_prefix_of_totals(red, total) + incl - v;
 }
 
 }  // namespace md
