@@ -48,7 +48,7 @@ def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget
     nwx, nwy = Wg // kw, Hg // kh
     tau64 = float(np.float32(tau))
     summary = {"ambiguous_windows": 0, "ambiguous_keys": 0, "max_sim_err": 0.0, "max_acls_rel": 0.0,
-               "max_feat_rel": 0.0}
+               "max_feat_rel": 0.0, "merged_rows_checked": 0, "copied_rows_checked": 0}
 
     def window_of(tok):
         xx, yy, tt = tok % Wg, (tok // Wg) % Hg, tok // (Wg * Hg)
@@ -108,12 +108,14 @@ def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget
                 # unmerged token: bit-identical copy
                 assert np.array_equal(grow.view(np.uint8), x[b, tok].view(np.uint8)), \
                     f"sample {b}: copied row of token {tok} is not bit-identical"
+                summary["copied_rows_checked"] += 1
             else:
                 rms = np.sqrt(np.mean(of * of))
                 row_rel = np.linalg.norm(gf - of) / max(np.linalg.norm(of), 1e-300)
                 assert row_rel <= RTOL, f"merged row {tok}: relative error {row_rel}"
                 assert np.max(np.abs(gf - of)) <= RTOL * rms, f"merged row {tok}: element error"
                 summary["max_feat_rel"] = max(summary["max_feat_rel"], float(row_rel))
+                summary["merged_rows_checked"] += 1
     return summary
 
 

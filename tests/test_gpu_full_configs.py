@@ -1,0 +1,147 @@
+"""GPU parity at the benchmark's full sizes and launch configurations (all five workloads).
+
+The GPU always runs the full batch; the oracle checks every sample where that takes seconds and a
+subset of samples otherwise; properties that hold at any size are checked on everything."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from oracle import FILTER_BUDGET
+from parity import check_decode, check_encode, check_prefill
+
+pytestmark = pytest.mark.gpu
+
+BENCH_TAU = 0.955
+
+
+def encode_both(cfg, tau, samples=None):
+    from paper_2411_10803_amd import harness
+    e = wl.encode_inputs(cfg)
+    args = (cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, cfg.key_budget)
+    g = harness.encode_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None, *args)
+    idx = list(range(cfg.B)) if samples is None else samples
+    sub = lambda a: np.ascontiguousarray(a[idx])
+    o = oracle.encode_merge(sub(e["x"]), cfg.x_dtype, sub(e["q_cls"]), sub(e["k_cls"]), cfg.x_dtype, None, None, *args)
+    gs = {k: (v[idx] if isinstance(v, np.ndarray) and v.shape[:1] == (cfg.B,) else v) for k, v in g.items()}
+    s = check_encode(gs, o, sub(e["x"]), cfg.x_dtype, None, *args)
+    return e, g, s
+
+
+def prefill_both(cfg, t, vis_valid, is_key, budget, samples=None):
+    from paper_2411_10803_amd import harness
+    scale, gamma, alpha = 1.0 / np.sqrt(cfg.d), 1.0 / cfg.M, 2.0 / cfg.L
+    g = harness.prefill_on_gpu(t, cfg.M, vis_valid, None, is_key, scale, FILTER_BUDGET, budget, gamma, alpha, budget)
+    idx = list(range(cfg.B)) if samples is None else samples
+    sub = lambda a: None if a is None else np.ascontiguousarray(a[idx])
+    ts = {k: sub(v) for k, v in t.items()}
+    o = oracle.prefill_filter(ts["q_txt"], ts["k"], ts["v"], ts["hidden"], sub(vis_valid), None, sub(is_key), cfg.M,
+                              scale, FILTER_BUDGET, budget, gamma, alpha, budget)
+    gs = {k: v[idx] for k, v in g.items()}
+    s = check_prefill(gs, o, ts, cfg.M, sub(vis_valid), sub(is_key), FILTER_BUDGET, budget, gamma, alpha, budget)
+    # properties on the whole batch: count = min(budget, valid tokens), keys kept, rows are exact copies
+    for b in range(cfg.B):
+        nv = cfg.M if vis_valid is None else int(vis_valid[b].sum())
+        assert g["kept_count"][b] == min(budget, nv)
+        n = int(g["kept_count"][b])
+        kept = g["kept_index"][b, :n]
+        assert np.all(np.diff(kept) > 0)
+        if is_key is not None:
+            keys = np.flatnonzero(is_key[b] & (1 if vis_valid is None else vis_valid[b]))
+            assert set(keys.tolist()) <= set(kept.tolist())
+        rows = np.concatenate([kept, cfg.M + np.arange(cfg.N)])
+        assert np.array_equal(g["k_out"][b, :rows.size], t["k"][b, rows])
+        assert np.array_equal(g["hidden_out"][b, :rows.size], t["hidden"][b, rows])
+        assert np.array_equal(g["out_ids"][b, :rows.size], rows)
+    return g, s
+
+
+def test_config2_full_batch_chained_three_budgets():
+    cfg = wl.CONFIGS[2]
+    e, g1, s1 = encode_both(cfg, BENCH_TAU)
+    assert s1["merged_rows_checked"] > 100 and s1["copied_rows_checked"] > 1000   # both kinds of rows were compared
+    assert 300 < g1["out_count"].mean() < 576                  # partial merging, near the paper's average of 440
+    t = wl.prefill_inputs(cfg)
+    for R in cfg.budgets:
+        prefill_both(cfg, t, g1["out_valid"], g1["out_is_key"], R)
+    # nominal shape as well: all 576 slots valid, seeded key set
+    prefill_both(cfg, t, None, wl.random_key_mask(cfg, cfg.key_budget), 192, samples=[0, 7, 15])
+
+
+def test_config1_full():
+    cfg = wl.CONFIGS[1]
+    e, g1, _ = encode_both(cfg, cfg.tau)
+    t = wl.prefill_inputs(cfg)
+    prefill_both(cfg, t, g1["out_valid"], g1["out_is_key"], 192)
+
+
+def test_config3_full_batch():
+    cfg = wl.CONFIGS[3]
+    e, g1, _ = encode_both(cfg, BENCH_TAU)
+    t = wl.prefill_inputs(cfg)
+    prefill_both(cfg, t, None, wl.random_key_mask(cfg, cfg.key_budget), 320, samples=[0, 5])
+
+
+def test_config4_full_batch_video_windows():
+    cfg = wl.CONFIGS[4]
+    e, g1, s1 = encode_both(cfg, cfg.tau)
+    assert s1["merged_rows_checked"] > 100
+    t = wl.prefill_inputs(cfg)
+    prefill_both(cfg, t, None, wl.random_key_mask(cfg, cfg.key_budget), 512, samples=[3])
+
+
+def test_config5_decode_full_size():
+    import torch
+    import paper_2411_10803_amd as md
+    from paper_2411_10803_amd import harness
+    cfg = wl.CONFIGS[5]
+    steps = 24
+    t = wl.decode_inputs(cfg, steps=steps, Lcap=cfg.L0 + cfg.steps)
+    B, Lcap = cfg.B, t["Lcap"]
+    scale = 1.0 / np.sqrt(cfg.d)
+    s0 = {"k": t["k_cache"], "v": t["v_cache"], "acc": np.zeros((B, Lcap), np.float32),
+          "ids": np.tile(np.arange(Lcap, dtype=np.int32), (B, 1)), "protect": t["protect"].copy(), "len": t["len0"].copy()}
+    d = harness.decode_state_to_dev(s0)
+    ws = md.decode_workspace(B, Lcap, cfg.H)
+    qs, kn, vn = (harness.to_dev(t[n], True) for n in ("q_steps", "k_new", "v_new"))
+    # step 1 (4096 -> 1024) on the full batch against the oracle on every sample
+    ev, evc = harness.decode_on_gpu(qs[0], d, scale, 1.0, cfg.decode_budget, ws)
+    g = harness.decode_state_to_host(d, ev, evc)
+    o = {k: v.copy() for k, v in s0.items()}
+    r = oracle.decode_evict(t["q_steps"][0], o["k"], o["v"], o["acc"], o["ids"], o["protect"], o["len"], scale, 1.0,
+                            cfg.decode_budget)
+    o["acc_all"] = r["a_t"].astype(np.float32)
+    o["evicted_ids"], o["evicted_count"] = r["evicted_ids"], r["evicted_count"]
+    summ = check_decode(g, o, s0, cfg.decode_budget)
+    assert np.all(g["len"] == cfg.decode_budget)
+    for b in range(B):
+        assert set(np.flatnonzero(t["heavy"][b]).tolist()) <= set(g["ids"][b, :cfg.decode_budget].tolist())
+    # free-running loop on the GPU: append + evict, then invariants and a teacher-forced oracle step
+    for s in range(1, steps - 1):
+        md.mustdrop_decode_append(kn[s], vn[s], d["k"], d["v"], d["acc"], d["ids"], d["protect"], d["len"], cfg.L0 + s)
+        harness.decode_on_gpu(qs[s], d, scale, 1.0, cfg.decode_budget, ws)
+    s = steps - 1
+    md.mustdrop_decode_append(kn[s], vn[s], d["k"], d["v"], d["acc"], d["ids"], d["protect"], d["len"], cfg.L0 + s)
+    torch.cuda.synchronize()
+    pre = harness.decode_state_to_host(d)
+    assert np.all(pre["len"] == cfg.decode_budget + 1)
+    for b in range(B):
+        ids = pre["ids"][b, :cfg.decode_budget + 1]
+        assert len(set(ids.tolist())) == ids.size                           # ids stay unique
+        prot_ids = set(np.flatnonzero(t["protect"][b]).tolist()) | set(range(cfg.L0 + 1, cfg.L0 + steps))
+        assert prot_ids <= set(ids.tolist())                                # protected entries never leave
+        old = ids[ids < cfg.L0]
+        slots = np.flatnonzero(ids < cfg.L0)
+        assert np.array_equal(pre["k"][b, slots], t["k_cache"][b, old])     # rows still paired with their ids
+        assert np.array_equal(pre["v"][b, slots], t["v_cache"][b, old])
+    ev, evc = harness.decode_on_gpu(qs[s], d, scale, 1.0, cfg.decode_budget, ws)
+    g = harness.decode_state_to_host(d, ev, evc)
+    sub = list(range(0, B, 8))
+    pre_s = {k: np.ascontiguousarray(v[sub]) for k, v in pre.items()}
+    o = {k: v.copy() for k, v in pre_s.items()}
+    r = oracle.decode_evict(np.ascontiguousarray(t["q_steps"][s][sub]), o["k"], o["v"], o["acc"], o["ids"], o["protect"],
+                            o["len"], scale, 1.0, cfg.decode_budget)
+    o["acc_all"] = (pre_s["acc"].astype(np.float64) + r["a_t"]).astype(np.float32)
+    o["evicted_ids"], o["evicted_count"] = r["evicted_ids"], r["evicted_count"]
+    check_decode({k: v[sub] for k, v in g.items()}, o, pre_s, cfg.decode_budget)
+    assert np.all(g["len"] == cfg.decode_budget) and np.all(g["evicted_count"] == 1)
