@@ -253,6 +253,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (known traffic) to scale rocprofv3 --pmc byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every stage is per-sample independent; multi-GPU is batch "
@@ -268,6 +270,13 @@ def main():
     cfg = wl.CONFIGS[2]
     pipe = Cfg2Pipeline(cfg, torch, md, harness)
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # plain copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         pipe.step()
     ms_per_step = timed(torch, pipe.step, args.steps)

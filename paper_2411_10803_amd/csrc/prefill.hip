@@ -257,7 +257,25 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
     __shared__ float s_ps[PARTS][32], s_pm[PARTS][32];
 
     const int lane = lane_id(), wv = wave_id(), tid = threadIdx.x;
-    const int j0 = blockIdx.x * 32, b = blockIdx.y;
+    // Workgroups go round-robin over the 8 XCDs (each with its own L2).  All key tiles of a sample
+    // share that sample's query fragments, so a sample is pinned to one XCD when the batch allows:
+    // its fragments are then fetched into one L2 instead of eight.
+    const int nt = (p.Mv + 31) / 32;
+    int b, tile_idx;
+    if (p.B % 8 == 0) {
+        const int xcd = blockIdx.x % 8, r = blockIdx.x / 8;
+        b = xcd + 8 * (r / nt);
+        tile_idx = r % nt;
+    } else if (8 % p.B == 0) {                       // small batch: a sample owns 8/B XCDs
+        const int g = 8 / p.B, xcd = blockIdx.x % 8, r = blockIdx.x / 8;
+        b = xcd / g;
+        tile_idx = r * g + xcd % g;
+        if (tile_idx >= nt) return;                  // grid padded to a multiple of 8 (whole block leaves)
+    } else {
+        b = blockIdx.x / nt;
+        tile_idx = blockIdx.x % nt;
+    }
+    const int j0 = tile_idx * 32;
     const long tok_stride = (long)p.H * p.d;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
@@ -534,7 +552,8 @@ int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t s
         MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
             w.partial, txt_len, p, w.cstat)));
     }
-    dim3 g2((p.Mv + 31) / 32, p.B);
+    const int nt = (p.Mv + 31) / 32;
+    dim3 g2(p.B % 8 == 0 || 8 % p.B != 0 ? nt * p.B : 8 * ((nt + 8 / p.B - 1) / (8 / p.B)));
     MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB, KS, NW><<<g2, 64 * NW, 0, st>>>(
         w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, w.V, w.I)));
     return MD_OK;
