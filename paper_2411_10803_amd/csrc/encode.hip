@@ -325,6 +325,173 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same decisions for M <= 1024*IPT with a sample's tokens in registers (thread t owns tokens
+// t, t+1024, ...): loads are issued in batches, the radix passes and prefix sums touch no memory,
+// key and merge flags are shared through LDS.
+template <int IPT>
+__global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
+    EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
+    const float* __restrict__ logits, const float* __restrict__ sim, float tau, int key_budget,
+    uint8_t* __restrict__ wmerged, int32_t* __restrict__ dstpos,
+    int32_t* __restrict__ out_index, float* __restrict__ out_mass, uint8_t* __restrict__ out_is_key,
+    uint8_t* __restrict__ out_valid, int32_t* __restrict__ out_count, int32_t* __restrict__ key_index,
+    float* __restrict__ a_cls_out, float* __restrict__ window_sim_out)
+{
+    extern __shared__ uint8_t s_flags[];             // [M] key flags, then [W] merged flags
+    __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
+    __shared__ int s_hist[256];
+    __shared__ int s_red[16];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
+    const int M = p.M, W = p.W;
+    uint8_t* s_key = s_flags;
+    uint8_t* s_merged = s_flags + M;
+    const uint8_t* vb = valid ? valid + (size_t)b * M : nullptr;
+    const float* mb = mass_in ? mass_in + (size_t)b * M : nullptr;
+
+    // own tokens' state and own windows' similarity: requested first
+    bool ok[IPT];
+    float mass[IPT], simv[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = tid + t * 1024;
+        ok[t] = j < M && (!vb || vb[j]);
+        mass[t] = (j < M && mb) ? mb[j] : 1.0f;
+        simv[t] = j < W ? sim[(size_t)b * W + j] : 0.f;
+    }
+    bool sel[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) sel[t] = false;
+
+    if (key_budget > 0) {
+        const float* lg = logits + (size_t)b * p.Hc * (M + 1);
+        // Eq. 6 denominators: one wave per head, online (max, sum) in the log2 domain, four loads in flight
+        for (int h = wv; h < p.Hc; h += nw) {
+            const float* l = lg + (size_t)h * (M + 1);
+            float mx = -INFINITY, z = 0.f;
+            for (int j0 = lane; j0 <= M; j0 += 4 * kWave) {
+                float x[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = j0 + u * kWave;
+                    x[u] = (j <= M && (j == 0 || !vb || vb[j - 1])) ? l[j] * kLog2eE : -INFINITY;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float mn = fmaxf(mx, x[u]);
+                    if (mn > -INFINITY) z = z * fast_exp2(mx - mn) + fast_exp2(x[u] - mn);
+                    mx = mn;
+                }
+            }
+            const float gm = wave_max(mx);
+            const float zs = wave_sum(gm > -INFINITY ? z * fast_exp2(mx - gm) : 0.f);
+            if (lane == 0) { s_max[h] = gm; s_inv[h] = 1.0f / (zs * (float)p.Hc); }
+        }
+        __syncthreads();
+        // a_cls of the own tokens (head mean of the probabilities), eight loads in flight
+        uint64_t rk[IPT];
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const int j = tid + t * 1024;
+            float a = -INFINITY;
+            if (ok[t]) {
+                a = 0.f;
+                for (int h0 = 0; h0 < p.Hc; h0 += 8) {
+                    float x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) x[u] = h0 + u < p.Hc ? lg[(size_t)(h0 + u) * (M + 1) + j + 1] : 0.f;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (h0 + u < p.Hc) a += fast_exp2(fmaf(x[u], kLog2eE, -s_max[h0 + u])) * s_inv[h0 + u];
+                }
+            }
+            if (j < M && a_cls_out) a_cls_out[(size_t)b * M + j] = a;
+            rk[t] = ok[t] ? rank_key(a, j) : 0ull;
+        }
+        const SelectBound sb = block_radix_select_reg<IPT>(rk, key_budget, s_hist);
+        int running = 0;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            if (t * 1024 >= M) continue;             // block-uniform
+            const int j = tid + t * 1024;
+            sel[t] = rk[t] != 0 && (rk[t] >> sb.shift) >= sb.bound;
+            if (j < M) s_key[j] = sel[t];
+            int total;
+            const int r = block_rank(sel[t], s_red, total);
+            if (sel[t]) key_index[(size_t)b * key_budget + running + r] = j;
+            running += total;
+        }
+        for (int r = running + tid; r < key_budget; r += blockDim.x) key_index[(size_t)b * key_budget + r] = -1;
+    } else {
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const int j = tid + t * 1024;
+            if (j < M) { s_key[j] = 0; if (a_cls_out) a_cls_out[(size_t)b * M + j] = 0.f; }
+        }
+    }
+    __syncthreads();
+
+    // ---- merge decision per window: S > tau, >= 2 valid members, no key member
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int w = tid + t * 1024;
+        if (w >= W) continue;
+        int n = 0;
+        bool has_key = false;
+        for (int m = 0; m < p.ws; ++m) {
+            const int tok = member_token(p, w, m);
+            if (vb && !vb[tok]) continue;
+            ++n;
+            has_key |= s_key[tok] != 0;
+        }
+        const bool mg = n >= 2 && !has_key && simv[t] > tau;
+        s_merged[w] = mg;
+        wmerged[(size_t)b * W + w] = mg;
+        if (window_sim_out) window_sim_out[(size_t)b * W + w] = simv[t];
+    }
+    __syncthreads();
+
+    // ---- survivors in ascending token index: prefix sum of the survivor flags, one round per 1024 tokens
+    int running = 0;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        if (t * 1024 >= M) continue;                 // block-uniform
+        const int j = tid + t * 1024;
+        bool surv = false, merged = false;
+        float ms = 0.f;
+        if (ok[t]) {
+            const int w = window_of_token(p, j);
+            merged = s_merged[w] != 0;
+            if (!merged) {
+                surv = true;
+                ms = mass[t];
+            } else {
+                int first = -1;
+                for (int m = 0; m < p.ws; ++m) {
+                    const int tok = member_token(p, w, m);
+                    if (vb && !vb[tok]) continue;
+                    if (first < 0) first = tok;
+                    ms += mb ? mb[tok] : 1.0f;
+                }
+                surv = (first == j);
+            }
+        }
+        int total;
+        const int r = block_rank(surv, s_red, total);
+        if (j < M) dstpos[(size_t)b * M + j] = surv ? running + r : -1;
+        if (surv) {
+            const size_t o = (size_t)b * M + running + r;
+            out_index[o] = j;
+            out_mass[o] = ms;
+            out_is_key[o] = merged ? 0 : (sel[t] ? 1 : 0);
+        }
+        running += total;
+    }
+    if (tid == 0) out_count[b] = running;
+    if (out_valid)
+        for (int s2 = tid; s2 < M; s2 += blockDim.x) out_valid[(size_t)b * M + s2] = s2 < running;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Writes the surviving rows.  One wave per window.
 template <bool BF>
 __global__ __launch_bounds__(256) void encode_emit_kernel(
@@ -487,9 +654,19 @@ extern "C" int mustdrop_encode_merge(
     dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
     if (x_dtype == MD_BF16) launch_window_sim<true>(ws, wgrid, st, x, valid, p, wsp.sim);
     else launch_window_sim<false>(ws, wgrid, st, x, valid, p, wsp.sim);
-    MD_LAUNCH("encode_decide", st, (encode_decide_kernel<<<B, 1024, 0, st>>>(
-        p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
-        out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)));
+#define MD_DECIDE_FAST(IPT_)                                                                                  \
+    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_><<<B, 1024, (size_t)M + W, st>>>(              \
+        p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.wmerged, wsp.dstpos,                          \
+        out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)))
+    if (M <= 1024) MD_DECIDE_FAST(1);
+    else if (M <= 2048) MD_DECIDE_FAST(2);
+    else if (M <= 4096) MD_DECIDE_FAST(4);
+    else if (M <= 8192) MD_DECIDE_FAST(8);
+    else
+        MD_LAUNCH("encode_decide", st, (encode_decide_kernel<<<B, 1024, 0, st>>>(
+            p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
+            out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)));
+#undef MD_DECIDE_FAST
     if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x)));
     else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x)));
     return check_launch("encode_merge");

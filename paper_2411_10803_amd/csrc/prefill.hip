@@ -481,6 +481,98 @@ __global__ __launch_bounds__(1024) void prefill_select_kernel(
     }
 }
 
+// The same selection with a sample's scores held in registers (Mv <= 1024*IPT): tokens are dealt
+// round-robin (thread t owns t, t+1024, ...), every global load is issued up front, the radix passes
+// and the prefix sums touch no memory.
+template <int IPT>
+__global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
+    PrefillDims p, const float* __restrict__ V, const float* __restrict__ I,
+    const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len, const uint8_t* __restrict__ is_key,
+    int mode, int budget, float gamma, float alpha,
+    int32_t* __restrict__ src_row,
+    int32_t* __restrict__ kept_index, int32_t* __restrict__ kept_count,
+    int32_t* __restrict__ out_len, uint8_t* __restrict__ out_protect,
+    float* __restrict__ score_global, float* __restrict__ score_indiv)
+{
+    __shared__ float s_redf[16];
+    __shared__ int s_red[16];
+    __shared__ int s_hist[256];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int Mv = p.Mv;
+    const int rows_cap = p.Rcap + p.N;
+    float v[IPT], iv[IPT];
+    bool ok[IPT], key[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = tid + t * 1024;
+        const bool in = j < Mv;
+        v[t] = in ? V[(long)b * Mv + j] : 0.f;
+        iv[t] = in ? I[(long)b * Mv + j] : 0.f;
+        ok[t] = in && (!vis_valid || vis_valid[(long)b * Mv + j]);
+        key[t] = ok[t] && is_key && is_key[(long)b * Mv + j];
+    }
+    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
+    // G = sum of V_j over valid vision tokens (Eq. 9, right-hand side); fixed summation tree
+    float part = 0.f;
+    int cnt = 0;                                     // keys in the low half, other valid tokens in the high half
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        part += v[t];                                // invalid tokens carry 0
+        cnt += (key[t] ? 1 : 0) + ((ok[t] && !key[t]) ? 1 << 16 : 0);
+        const int j = tid + t * 1024;
+        if (j < Mv) {
+            if (score_global) score_global[(long)b * Mv + j] = v[t];
+            if (score_indiv) score_indiv[(long)b * Mv + j] = iv[t];
+        }
+    }
+    const float G = block_sum(part, s_redf);
+    bool keep[IPT];
+    if (mode == MD_FILTER_BUDGET) {
+        cnt = block_sum_i(cnt, s_red);
+        const int nk = cnt & 0xFFFF, no = cnt >> 16;
+        const int extra = min(max(budget - nk, 0), no);
+        const float gG = gamma * G;
+        uint64_t rk[IPT];
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const float s1 = G > 0.f ? v[t] / gG : 0.f;
+            const float s2 = iv[t] / alpha;
+            rk[t] = (ok[t] && !key[t]) ? rank_key(fmaxf(s1, s2), tid + t * 1024) : 0ull;
+        }
+        const SelectBound sb = block_radix_select_reg<IPT>(rk, extra, s_hist);
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) keep[t] = key[t] || (rk[t] != 0 && extra > 0 && (rk[t] >> sb.shift) >= sb.bound);
+    } else {
+        const float thrV = gamma * G;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) keep[t] = ok[t] && !((v[t] <= thrV) && (iv[t] < alpha) && !key[t]);
+    }
+    int running = 0;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        if (t * 1024 >= Mv) continue;                // block-uniform
+        const int j = tid + t * 1024;
+        int total;
+        const int o = running + block_rank(keep[t], s_red, total);
+        if (keep[t] && o < p.Rcap) {
+            kept_index[(long)b * p.Rcap + o] = j;
+            src_row[(long)b * rows_cap + o] = j;
+            if (out_protect) out_protect[(long)b * rows_cap + o] = key[t] ? 1 : 0;
+        }
+        running += total;
+    }
+    const int nkept = min(running, p.Rcap);
+    for (int i = tid; i < rows_cap - nkept; i += blockDim.x) {
+        const int o = nkept + i;
+        src_row[(long)b * rows_cap + o] = i < tl ? Mv + i : -1;
+        if (out_protect && i < tl) out_protect[(long)b * rows_cap + o] = 1;
+    }
+    if (tid == 0) {
+        kept_count[b] = running;
+        if (out_len) out_len[b] = nkept + tl;
+    }
+}
+
 // One block per output row: copies the hidden, K and V rows named by the row map.
 __global__ __launch_bounds__(256) void prefill_compact_kernel(
     PrefillDims p, const int32_t* __restrict__ src_row,
@@ -641,9 +733,19 @@ extern "C" int mustdrop_prefill_filter(
     }
     if (rc != MD_OK) return rc;
     int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
-    MD_LAUNCH("prefill_select", st, (prefill_select_kernel<<<B, 1024, 0, st>>>(
-        p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,
-        w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)));
+#define MD_PSELECT_FAST(IPT_)                                                                               \
+    MD_LAUNCH("prefill_select", st, (prefill_select_fast_kernel<IPT_><<<B, 1024, 0, st>>>(                 \
+        p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,                          \
+        src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)))
+    if (Mv <= 1024) MD_PSELECT_FAST(1);
+    else if (Mv <= 2048) MD_PSELECT_FAST(2);
+    else if (Mv <= 4096) MD_PSELECT_FAST(4);
+    else if (Mv <= 8192) MD_PSELECT_FAST(8);
+    else
+        MD_LAUNCH("prefill_select", st, (prefill_select_kernel<<<B, 1024, 0, st>>>(
+            p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,
+            w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)));
+#undef MD_PSELECT_FAST
     dim3 gc(Rcap + N, B);
     MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel<<<gc, 256, 0, st>>>(p, src_row,
         static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
