@@ -125,11 +125,11 @@ def kernel_bytes(cfg, pipe, counts):
     dec_len = counts["decode_entries"]
     moves = counts["decode_moves"]
     return {
-        "cls_logits": B * (M + 1) * D * e + B * (M + 1) * cfg.Hc * 4,
-        "window_sim": B * M * D * e,
+        "encode_scores": B * M * D * e + B * (M + 1) * D * e + B * (M + 1) * cfg.Hc * 4,
         "encode_decide": B * (M + 1) * cfg.Hc * 4 + B * M * 16,
         "encode_emit": B * M * D * e + surv * D * e,
         "prefill_rowstats": B * (L + N) * H * d * 2,
+        "prefill_cstat": B * H * N * 12,
         "prefill_colscore": B * (M + N) * H * d * 2,
         "prefill_select": B * M * 16,
         "prefill_compact": 2 * rows * (C + 2 * H * d) * 2,

@@ -2,8 +2,9 @@
 // Merging (Eq. 5), followed by stable compaction of the survivors.
 //
 // Launch plan (all on the caller's stream, no host synchronisation):
-//   cls_logits_kernel   one wave per key row: q_cls . k_j per head            (HBM: reads k_cls once)
-//   window_sim_kernel   one wave per window: Gram matrix in registers -> S    (HBM: reads x once)
+//   encode_scores_kernel one launch, two kinds of waves:
+//       window waves     one wave per window: Gram matrix in registers -> S    (HBM: reads x once)
+//       key-row waves    one wave per key row: q_cls . k_j per head            (HBM: reads k_cls once)
 //   encode_decide_kernel one block per sample: softmax + head mean, radix top-k -> O, merge
 //                        decisions, prefix sum of survivors, small outputs    (tiny)
 //   encode_emit_kernel  one wave per window: row copies / mass-weighted means (re-reads x, writes out_x)
@@ -69,13 +70,12 @@ template <> struct Vec<true> {
 // One wave per key row.  A head covers vph = dc/VEC consecutive 16-byte vectors (a power of two),
 // so the per-head sums are segmented butterflies over vph lanes (or whole-wave sums if vph >= 64).
 template <bool BF>
-__global__ __launch_bounds__(256) void cls_logits_kernel(
-    const void* __restrict__ q_cls, const void* __restrict__ k_cls, const uint8_t* __restrict__ valid,
-    EncodeDims p, float* __restrict__ logits)
+__device__ __forceinline__ void cls_logits_row(
+    long item, const void* __restrict__ q_cls, const void* __restrict__ k_cls, const uint8_t* __restrict__ valid,
+    const EncodeDims& p, float* __restrict__ logits)
 {
     constexpr int VEC = Vec<BF>::N;
     const int lane = lane_id();
-    const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
     const long rows = (long)p.B * (p.M + 1);
     if (item >= rows) return;
     const int b = (int)(item / (p.M + 1)), j = (int)(item % (p.M + 1));
@@ -120,12 +120,11 @@ __global__ __launch_bounds__(256) void cls_logits_kernel(
 // each lane owns a strided slice of the feature dimension and keeps the upper triangle of the
 // Gram matrix (norms on the diagonal) in registers; one butterfly per entry at the end.
 template <int WSM, bool BF>
-__global__ __launch_bounds__(256) void window_sim_kernel(
-    const void* __restrict__ x, const uint8_t* __restrict__ valid, EncodeDims p, float* __restrict__ sim)
+__device__ __forceinline__ void window_sim_item(
+    long item, const void* __restrict__ x, const uint8_t* __restrict__ valid, const EncodeDims& p, float* __restrict__ sim)
 {
     constexpr int VEC = Vec<BF>::N;
     const int lane = lane_id();
-    const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
     if (item >= (long)p.B * p.W) return;
     const int b = (int)(item / p.W), w = (int)(item % p.W);
     const size_t esz = BF ? 2 : 4;
@@ -193,6 +192,19 @@ __global__ __launch_bounds__(256) void window_sim_kernel(
             }
         sim[(size_t)b * p.W + w] = npairs > 0 ? S / (float)npairs : 0.f;
     }
+}
+
+// One launch for both bandwidth-bound score passes: waves [0, B*W) take a window each (Eq. 5), the
+// following B*(1+M) waves a key row each (Eq. 6 logits; none when no key set is asked for).
+template <int WSM, bool XBF, bool QKBF>
+__global__ __launch_bounds__(256) void encode_scores_kernel(
+    const void* __restrict__ x, const void* __restrict__ q_cls, const void* __restrict__ k_cls,
+    const uint8_t* __restrict__ valid, EncodeDims p, int with_cls, float* __restrict__ sim, float* __restrict__ logits)
+{
+    const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
+    const long n_win = (long)p.B * p.W;
+    if (item < n_win) window_sim_item<WSM, XBF>(item, x, valid, p, sim);
+    else if (with_cls) cls_logits_row<QKBF>(item - n_win, q_cls, k_cls, valid, p, logits);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -569,13 +581,13 @@ EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
     return ws;
 }
 
-template <bool BF>
-void launch_window_sim(int ws, dim3 grid, hipStream_t st, const void* x, const uint8_t* valid,
-                       const EncodeDims& p, float* sim) {
-    if (ws <= 2) MD_LAUNCH("window_sim", st, (window_sim_kernel<2, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
-    else if (ws <= 4) MD_LAUNCH("window_sim", st, (window_sim_kernel<4, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
-    else if (ws <= 8) MD_LAUNCH("window_sim", st, (window_sim_kernel<8, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
-    else MD_LAUNCH("window_sim", st, (window_sim_kernel<16, BF><<<grid, 256, 0, st>>>(x, valid, p, sim)));
+template <int WSM>
+void launch_scores(dim3 grid, hipStream_t st, bool xbf, bool qkbf, const void* x, const void* q_cls, const void* k_cls,
+                   const uint8_t* valid, const EncodeDims& p, int with_cls, float* sim, float* logits) {
+    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
+    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
+    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
+    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
 }
 
 }  // namespace
@@ -645,15 +657,15 @@ extern "C" int mustdrop_encode_merge(
     p.nwx = Wg / kw; p.nwy = Hg / kh; p.nwt = T / kt;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    if (key_budget > 0) {
-        const long rows = (long)B * (M + 1);
-        dim3 grid((unsigned)((rows + 3) / 4));
-        if (qk_dtype == MD_BF16) MD_LAUNCH("cls_logits", st, (cls_logits_kernel<true><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits)));
-        else MD_LAUNCH("cls_logits", st, (cls_logits_kernel<false><<<grid, 256, 0, st>>>(q_cls, k_cls, valid, p, wsp.logits)));
-    }
+    const long items = (long)B * W + (key_budget > 0 ? (long)B * (M + 1) : 0);
+    dim3 sgrid((unsigned)((items + 3) / 4));
+    const bool xbf = x_dtype == MD_BF16, qkbf = qk_dtype == MD_BF16;
+    const int with_cls = key_budget > 0;
+    if (ws <= 2) launch_scores<2>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
+    else if (ws <= 4) launch_scores<4>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
+    else if (ws <= 8) launch_scores<8>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
+    else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
-    if (x_dtype == MD_BF16) launch_window_sim<true>(ws, wgrid, st, x, valid, p, wsp.sim);
-    else launch_window_sim<false>(ws, wgrid, st, x, valid, p, wsp.sim);
 #define MD_DECIDE_FAST(IPT_)                                                                                  \
     MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_><<<B, 1024, (size_t)M + W, st>>>(              \
         p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.wmerged, wsp.dstpos,                          \
