@@ -599,15 +599,18 @@ struct PrefillWorkspace {
     size_t bytes;
 };
 
+#ifndef MD_RS_BLOCKS
+#define MD_RS_BLOCKS 512   // target number of blocks of the row-statistics sweep
+#endif
 #ifndef MD_PF_NW
 #define MD_PF_NW 4      // waves per block in the column-score sweep (measured: 4 beats 8 and 16)
 #endif
 
-int pick_chunks(int B, int H, int L) {
+int pick_chunks(int B, int H, int L, int ntg) {
     // enough (sample, head, chunk) blocks to cover the 256 CUs several times; chunks of whole tiles
     // about two resident blocks per CU (512 in all); at least 4 tiles per chunk so every wave has work
     const int tiles = (L + 31) / 32;
-    int nch = (512 + B * H - 1) / (B * H);
+    int nch = (MD_RS_BLOCKS + B * H * ntg - 1) / (B * H * ntg);   // ntg: text groups, also spread over blocks
     if (nch > tiles / 4) nch = tiles / 4;
     if (nch < 1) nch = 1;
     if (nch > 64) nch = 64;
@@ -711,7 +714,7 @@ extern "C" int mustdrop_prefill_filter(
     PrefillDims p;
     p.B = B; p.Mv = Mv; p.N = N; p.H = H; p.d = d; p.C = C; p.L = Mv + N; p.Rcap = Rcap;
     p.Npad = (N + 31) / 32 * 32;
-    p.nch = pick_chunks(B, H, p.L);
+    p.nch = pick_chunks(B, H, p.L, (p.Npad / 32 + 1) / 2);
     const int tiles = (p.L + 31) / 32;
     p.chunk = (tiles + p.nch - 1) / p.nch * 32;
     p.nch = (p.L + p.chunk - 1) / p.chunk;
