@@ -349,14 +349,15 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     uint8_t* __restrict__ out_valid, int32_t* __restrict__ out_count, int32_t* __restrict__ key_index,
     float* __restrict__ a_cls_out, float* __restrict__ window_sim_out)
 {
-    extern __shared__ uint8_t s_flags[];             // [M] key flags, then [W] merged flags
+    extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];   // [M] merged-window mass (float), [M] key flags, [M] token state
     __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
     __shared__ int s_hist[256];
     __shared__ int s_red[16];
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
     const int M = p.M, W = p.W;
-    uint8_t* s_key = s_flags;
-    uint8_t* s_merged = s_flags + M;
+    float* s_tmass = reinterpret_cast<float*>(s_dyn);
+    uint8_t* s_key = s_dyn + 4 * (size_t)M;
+    uint8_t* s_state = s_key + M;                    // 0: not in a merged window, 1: first valid member, 2: merged away
     const uint8_t* vb = valid ? valid + (size_t)b * M : nullptr;
     const float* mb = mass_in ? mass_in + (size_t)b * M : nullptr;
 
@@ -376,23 +377,36 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
 
     if (key_budget > 0) {
         const float* lg = logits + (size_t)b * p.Hc * (M + 1);
-        // Eq. 6 denominators: one wave per head, online (max, sum) in the log2 domain, four loads in flight
+        // one token per thread and few heads: the own token's logits are requested before the
+        // denominators are computed, so that the two passes over the logits cost one round trip
+        constexpr int PRE = 16;
+        const bool pre = IPT == 1 && p.Hc <= PRE;    // block-uniform
+        float xl[PRE];
+        if (pre) {
+#pragma unroll
+            for (int u = 0; u < PRE; ++u) xl[u] = (u < p.Hc && tid < M) ? lg[(size_t)u * (M + 1) + tid + 1] : 0.f;
+        }
+        // Eq. 6 denominators: one wave per head, (max, sum) in the log2 domain, 16 loads in flight
         for (int h = wv; h < p.Hc; h += nw) {
             const float* l = lg + (size_t)h * (M + 1);
             float mx = -INFINITY, z = 0.f;
-            for (int j0 = lane; j0 <= M; j0 += 4 * kWave) {
-                float x[4];
+            for (int j0 = lane; j0 <= M; j0 += 16 * kWave) {
+                float x[16];
+                float bm = -INFINITY;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 16; ++u) {
                     const int j = j0 + u * kWave;
                     x[u] = (j <= M && (j == 0 || !vb || vb[j - 1])) ? l[j] * kLog2eE : -INFINITY;
+                    bm = fmaxf(bm, x[u]);
                 }
+                const float mn = fmaxf(mx, bm);
+                if (mn > -INFINITY) {
+                    float sacc = 0.f;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float mn = fmaxf(mx, x[u]);
-                    if (mn > -INFINITY) z = z * fast_exp2(mx - mn) + fast_exp2(x[u] - mn);
-                    mx = mn;
+                    for (int u = 0; u < 16; ++u) sacc += fast_exp2(x[u] - mn);
+                    z = z * fast_exp2(mx - mn) + sacc;
                 }
+                mx = mn;
             }
             const float gm = wave_max(mx);
             const float zs = wave_sum(gm > -INFINITY ? z * fast_exp2(mx - gm) : 0.f);
@@ -405,7 +419,12 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         for (int t = 0; t < IPT; ++t) {
             const int j = tid + t * 1024;
             float a = -INFINITY;
-            if (ok[t]) {
+            if (ok[t] && pre) {
+                a = 0.f;
+#pragma unroll
+                for (int u = 0; u < PRE; ++u)
+                    if (u < p.Hc) a += fast_exp2(fmaf(xl[u], kLog2eE, -s_max[u])) * s_inv[u];
+            } else if (ok[t]) {
                 a = 0.f;
                 for (int h0 = 0; h0 < p.Hc; h0 += 8) {
                     float x[8];
@@ -442,21 +461,39 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     }
     __syncthreads();
 
-    // ---- merge decision per window: S > tau, >= 2 valid members, no key member
+    // ---- merge decision per window: S > tau, >= 2 valid members, no key member.  The window's thread
+    // leaves each member's fate (and the merged mass at the first valid member) in LDS, so that the
+    // per-token pass below needs no index arithmetic.
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = tid + t * 1024;
+        if (j < M) s_state[j] = 0;
+    }
+    __syncthreads();
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
         const int w = tid + t * 1024;
         if (w >= W) continue;
-        int n = 0;
+        int n = 0, first = -1;
         bool has_key = false;
+        float total = 0.f;
         for (int m = 0; m < p.ws; ++m) {
             const int tok = member_token(p, w, m);
             if (vb && !vb[tok]) continue;
             ++n;
+            if (first < 0) first = tok;
             has_key |= s_key[tok] != 0;
+            total += mb ? mb[tok] : 1.0f;
         }
         const bool mg = n >= 2 && !has_key && simv[t] > tau;
-        s_merged[w] = mg;
+        if (mg) {
+            for (int m = 0; m < p.ws; ++m) {
+                const int tok = member_token(p, w, m);
+                if (vb && !vb[tok]) continue;
+                s_state[tok] = tok == first ? 1 : 2;
+            }
+            s_tmass[first] = total;
+        }
         wmerged[(size_t)b * W + w] = mg;
         if (window_sim_out) window_sim_out[(size_t)b * W + w] = simv[t];
     }
@@ -471,21 +508,10 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         bool surv = false, merged = false;
         float ms = 0.f;
         if (ok[t]) {
-            const int w = window_of_token(p, j);
-            merged = s_merged[w] != 0;
-            if (!merged) {
-                surv = true;
-                ms = mass[t];
-            } else {
-                int first = -1;
-                for (int m = 0; m < p.ws; ++m) {
-                    const int tok = member_token(p, w, m);
-                    if (vb && !vb[tok]) continue;
-                    if (first < 0) first = tok;
-                    ms += mb ? mb[tok] : 1.0f;
-                }
-                surv = (first == j);
-            }
+            const int stt = s_state[j];
+            merged = stt != 0;
+            surv = stt != 2;
+            ms = stt == 1 ? s_tmass[j] : mass[t];
         }
         int total;
         const int r = block_rank(surv, s_red, total);
@@ -667,7 +693,7 @@ extern "C" int mustdrop_encode_merge(
     else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
 #define MD_DECIDE_FAST(IPT_)                                                                                  \
-    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_><<<B, 1024, (size_t)M + W, st>>>(              \
+    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_><<<B, 1024, 6 * (size_t)M, st>>>(              \
         p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.wmerged, wsp.dstpos,                          \
         out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)))
     if (M <= 1024) MD_DECIDE_FAST(1);

@@ -26,7 +26,8 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
-__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+// wave index within the block, as a scalar (the compiler cannot see that threadIdx.x / 64 is wave-uniform)
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // v_exp_f32 / v_log_f32: base-2, about 1 ulp, results below 2^-126 flush to zero.  Used where the
 // argument is a (score - max) difference, so neither overflow nor denormal results matter.

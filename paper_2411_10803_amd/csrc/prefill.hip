@@ -115,7 +115,17 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const int c1 = min(c0 + p.chunk, p.L);
     int j0 = c0 + 32 * wv;
     u32x4 st[KS];
-    if (j0 < c1) Tile::gload(kb, tok_stride, j0, p.L, lane, st);
+    // validity of this lane's key (lane % 32) in the tile that is in flight; fetched with the tile so
+    // that its latency hides behind the previous tile's arithmetic
+    auto key_valid = [&](int j) {
+        const int jl = j + (lane & 31);
+        return jl < p.Mv ? (!vb || vb[jl]) : false;
+    };
+    bool v_nxt = false;
+    if (j0 < c1) {
+        Tile::gload(kb, tok_stride, j0, p.L, lane, st);
+        v_nxt = key_valid(j0);
+    }
 
     // text-query fragments of this head: through the same LDS tile, one 32-row block at a time
     bf16x8 qf[NB][KS];
@@ -145,12 +155,23 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         bf16x8 kf[KS];
         Tile::frags(tile, lane, kf);
         wave_lds_sync();
-        if (j0 + 32 * 4 < c1) Tile::gload(kb, tok_stride, j0 + 32 * 4, p.L, lane, st);   // prefetch
+        const bool v_ok = v_nxt;
+        if (j0 + 32 * 4 < c1) {                                                 // prefetch
+            Tile::gload(kb, tok_stride, j0 + 32 * 4, p.L, lane, st);
+            v_nxt = key_valid(j0 + 32 * 4);
+        }
         // validity of the 32 keys of this tile as a bit mask (vision keys only)
-        const int jl = j0 + (lane & 31);
-        const bool v_ok = jl < p.Mv ? (!vb || vb[jl]) : false;
         const uint32_t vmask = (uint32_t)__ballot(v_ok);
-        const bool all_visible = (j0 + 32 <= p.Mv) && vmask == 0xFFFFFFFFu;   // wave-uniform
+        // three wave-uniform cases: a vision tile without holes, a vision tile with dropped keys,
+        // and a tile that reaches into the text keys (causal mask, per text row)
+        const bool vision_tile = j0 + 32 <= p.Mv;
+        const bool all_visible = vision_tile && vmask == 0xFFFFFFFFu;
+        bool key_ok[16];                             // vision tile: is the key of accumulator register r valid
+        {
+            const uint32_t mine = vmask >> (4 * (lane >> 5));   // tile_row(r, lane) = 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+            for (int r = 0; r < 16; ++r) key_ok[r] = (mine >> (8 * (r >> 2) + (r & 3))) & 1u;
+        }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             f32x16 acc;
@@ -164,6 +185,12 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
             if (all_visible) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) { t[r] = acc[r] * scale_log2e; bm = fmaxf(bm, t[r]); }
+            } else if (vision_tile) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    t[r] = key_ok[r] ? acc[r] * scale_log2e : -INFINITY;
+                    bm = fmaxf(bm, t[r]);
+                }
             } else {
                 const int i = i_base + 32 * nb + (lane & 31);
 #pragma unroll
