@@ -29,6 +29,21 @@ __device__ __forceinline__ int member_token(const EncodeDims& p, int w, int m) {
     const int dx = m % p.kw, dy = (m / p.kw) % p.kh, dt = m / (p.kw * p.kh);
     return ((wt * p.kt + dt) * p.Hg + (wy * p.kh + dy)) * p.Wg + (wx * p.kw + dx);
 }
+// member_token(p, w, m) = window_base(p, w) + member_offset(p, m)
+__device__ __forceinline__ int window_base(const EncodeDims& p, int w) {
+    const int wx = w % p.nwx, wy = (w / p.nwx) % p.nwy, wt = w / (p.nwx * p.nwy);
+    return (wt * p.kt * p.Hg + wy * p.kh) * p.Wg + wx * p.kw;
+}
+__device__ __forceinline__ int member_offset(const EncodeDims& p, int m) {
+    const int dx = m % p.kw, dy = (m / p.kw) % p.kh, dt = m / (p.kw * p.kh);
+    return (dt * p.Hg + dy) * p.Wg + dx;
+}
+// A wave that works on one window: lane m < ws computes member m's token (one division sequence
+// for all members instead of one per member); read back with wave_member().
+__device__ __forceinline__ int lane_member_token(const EncodeDims& p, int w, int lane) {
+    return lane < p.ws ? member_token(p, w, lane) : 0;
+}
+__device__ __forceinline__ int wave_member(int per_lane, int m) { return __builtin_amdgcn_readlane(per_lane, m); }
 
 __device__ __forceinline__ int window_of_token(const EncodeDims& p, int tok) {
     const int x = tok % p.Wg, y = (tok / p.Wg) % p.Hg, t = tok / (p.Wg * p.Hg);
@@ -131,14 +146,15 @@ __device__ __forceinline__ void window_sim_item(
 
     const char* rows[WSM];
     bool ok[WSM];
+    const int tok_l = lane_member_token(p, w, lane);
+    const int ok_l = lane < p.ws && (!valid || valid[(size_t)b * p.M + tok_l]);
 #pragma unroll
     for (int m = 0; m < WSM; ++m) {
         ok[m] = false;
         rows[m] = nullptr;
         if (m < p.ws) {
-            const int tok = member_token(p, w, m);
-            ok[m] = !valid || valid[(size_t)b * p.M + tok];
-            rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + tok) * p.D * esz;
+            ok[m] = wave_member(ok_l, m) != 0;
+            rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + wave_member(tok_l, m)) * p.D * esz;
         }
     }
     float G[WSM * (WSM + 1) / 2];
@@ -353,8 +369,10 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
     __shared__ int s_hist[256];
     __shared__ int s_red[16];
+    __shared__ int s_moff[kMaxWindow];               // member_offset(m): integer divisions done once per block
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
     const int M = p.M, W = p.W;
+    if (tid < p.ws) s_moff[tid] = member_offset(p, tid);    // read after later barriers
     float* s_tmass = reinterpret_cast<float*>(s_dyn);
     uint8_t* s_key = s_dyn + 4 * (size_t)M;
     uint8_t* s_state = s_key + M;                    // 0: not in a merged window, 1: first valid member, 2: merged away
@@ -477,8 +495,9 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         int n = 0, first = -1;
         bool has_key = false;
         float total = 0.f;
+        const int base = window_base(p, w);
         for (int m = 0; m < p.ws; ++m) {
-            const int tok = member_token(p, w, m);
+            const int tok = base + s_moff[m];
             if (vb && !vb[tok]) continue;
             ++n;
             if (first < 0) first = tok;
@@ -488,7 +507,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         const bool mg = n >= 2 && !has_key && simv[t] > tau;
         if (mg) {
             for (int m = 0; m < p.ws; ++m) {
-                const int tok = member_token(p, w, m);
+                const int tok = base + s_moff[m];
                 if (vb && !vb[tok]) continue;
                 s_state[tok] = tok == first ? 1 : 2;
             }
@@ -550,38 +569,67 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
     const float* mb = mass_in ? mass_in + (size_t)b * p.M : nullptr;
     const int32_t* dst_b = dstpos + (size_t)b * p.M;
 
-    if (!wmerged[(size_t)b * p.W + w]) {
-        for (int m = 0; m < p.ws; ++m) {
-            const int tok = member_token(p, w, m);
-            if (vb && !vb[tok]) continue;
-            const int pos = dst_b[tok];
-            const u32x4* src = reinterpret_cast<const u32x4*>(xb + (size_t)tok * rowb);
-            u32x4* dst = reinterpret_cast<u32x4*>(ob + (size_t)pos * rowb);
-            for (int c = lane; c < (int)(rowb / 16); c += kWave) dst[c] = src[c];
+    // lane m < ws: token, validity, destination row and mass of member m, all requested at once
+    const int is_merged = wmerged[(size_t)b * p.W + w];
+    const int tok_l = lane_member_token(p, w, lane);
+    const int ok_l = lane < p.ws && (!vb || vb[tok_l]);
+    const int pos_l = ok_l ? dst_b[tok_l] : -1;
+    const float mass_l = ok_l ? (mb ? mb[tok_l] : 1.0f) : 0.f;
+    const int nchunk = (int)(rowb / 16);
+
+    if (!is_merged) {
+        // plain copies, up to four rows in flight
+        for (int m0 = 0; m0 < p.ws; m0 += 4) {
+            const u32x4* src[4];
+            u32x4* dst[4];
+            bool okm[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int m = min(m0 + u, p.ws - 1);
+                okm[u] = m0 + u < p.ws && wave_member(ok_l, m) != 0;
+                src[u] = reinterpret_cast<const u32x4*>(xb + (size_t)wave_member(tok_l, m) * rowb);
+                dst[u] = reinterpret_cast<u32x4*>(ob + (size_t)max(wave_member(pos_l, m), 0) * rowb);
+            }
+            for (int c = lane; c < nchunk; c += kWave) {
+                u32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (okm[u]) v[u] = src[u][c];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (okm[u]) dst[u][c] = v[u];
+            }
         }
         return;
     }
-    int first = -1;
+    // mass-weighted mean of the valid members (members in ascending order), written at the first one
+    const uint64_t okmask = __ballot(ok_l != 0);
+    if (okmask == 0ull) return;                      // cannot happen: a merged window has >= 2 valid members
+    const int first_m = __builtin_ctzll(okmask);
     float msum = 0.f;
-    for (int m = 0; m < p.ws; ++m) {
-        const int tok = member_token(p, w, m);
-        if (vb && !vb[tok]) continue;
-        if (first < 0) first = tok;
-        msum += mb ? mb[tok] : 1.0f;
-    }
-    char* orow = ob + (size_t)dst_b[first] * rowb;
+    for (int m = 0; m < p.ws; ++m)
+        if ((okmask >> m) & 1ull) msum += __builtin_bit_cast(float, wave_member(__builtin_bit_cast(int, mass_l), m));
+    char* orow = ob + (size_t)wave_member(pos_l, first_m) * rowb;
     for (int c = lane * VEC; c < p.D; c += kWave * VEC) {
         float acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-        for (int m = 0; m < p.ws; ++m) {
-            const int tok = member_token(p, w, m);
-            if (vb && !vb[tok]) continue;
-            const float mm = mb ? mb[tok] : 1.0f;
-            float v[VEC];
-            Vec<BF>::load(xb + (size_t)tok * rowb, c, v);
+        for (int m0 = 0; m0 < p.ws; m0 += 4) {
+            float v[4][VEC], mm[4];
+            bool okm[4];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = fmaf(mm, v[e], acc[e]);
+            for (int u = 0; u < 4; ++u) {
+                const int m = min(m0 + u, p.ws - 1);
+                okm[u] = m0 + u < p.ws && ((okmask >> m) & 1ull);
+                mm[u] = __builtin_bit_cast(float, wave_member(__builtin_bit_cast(int, mass_l), m));
+                if (okm[u]) Vec<BF>::load(xb + (size_t)wave_member(tok_l, m) * rowb, c, v[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (!okm[u]) continue;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] = fmaf(mm[u], v[u][e], acc[e]);
+            }
         }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = acc[e] / msum;

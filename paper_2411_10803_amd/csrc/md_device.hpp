@@ -219,34 +219,40 @@ __device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int 
 }
 
 // Same selection with the keys held in registers (IPT per thread, 0 = absent; real keys are never 0
-// as long as the tie value is below 2^31 - 1): no memory traffic inside the passes.
+// as long as the tie value is below 2^31 - 1): no memory traffic inside the passes.  The wave that
+// scans the histogram also clears it, so a pass costs two barriers.
 template <int IPT>
 __device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&key)[IPT], int k, int* hist) {
-    uint64_t prefix = 0;
-    int shift = 64;
     __shared__ int s_digit, s_k, s_done;
-    int kk = k;
     if (k <= 0) return SelectBound{~0ull, 0};               // nothing selected
-    for (int pass = 0; pass < 8; ++pass) {
-        const int sh = 56 - 8 * pass;
-        __syncthreads();
-        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
-        __syncthreads();
+    const int lane = lane_id();
+    __syncthreads();                                        // earlier readers of the shared words are done
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+    int sh = 56, shift = 64;
+    uint64_t prefix = 0ull;
+    int kk = k;
+    bool first = true;
+    for (;;) {
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
             const uint64_t kv = key[t];
-            if (kv != 0 && (pass == 0 || (kv >> shift) == prefix)) atomicAdd(&hist[(kv >> sh) & 0xFF], 1);
+            if (kv != 0 && (first || (kv >> shift) == prefix)) atomicAdd(&hist[(kv >> sh) & 0xFF], 1);
         }
         __syncthreads();
         if (threadIdx.x < kWave) {
-            const int lane = threadIdx.x;
+            // digits 255..0 handled 4 per lane, high digits in low lanes
             int c[4], s = 0;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) { c[t] = hist[255 - (lane * 4 + t)]; s += c[t]; }
+            for (int t = 0; t < 4; ++t) {
+                c[t] = hist[255 - (lane * 4 + t)];
+                hist[255 - (lane * 4 + t)] = 0;
+                s += c[t];
+            }
             const int incl = wave_incl_scan_i(s);
-            int run = incl - s;
+            int run = incl - s;                             // items in strictly higher digits
             const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
-            if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }
+            if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }   // fewer than k items
             if (total >= kk) {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -260,11 +266,15 @@ __device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&k
             }
         }
         __syncthreads();
-        if (s_done == 2) return SelectBound{0ull, 63};
-        prefix = (prefix << 8) | (uint64_t)s_digit;
+        const int done = s_done;
+        if (done == 2) return SelectBound{0ull, 63};        // select everything (keys < 2^63)
+        const int width = shift - sh;                       // 8, less when the last digit overlaps its predecessor
+        prefix = (prefix << width) | ((uint64_t)s_digit & ((1ull << width) - 1ull));
         shift = sh;
         kk = s_k;
-        if (s_done == 1) break;
+        first = false;
+        if (done == 1 || sh == 0) break;
+        sh = max(sh - 8, 0);
     }
     return SelectBound{prefix, shift};
 }
