@@ -82,49 +82,77 @@ template <> struct Vec<true> {
 
 // ---------------------------------------------------------------------------------------------
 // Eq. 6 numerator: logit[b][h][j] = q_cls[b][h] . k_cls[b][j][h] / sqrt(dc), j = 0..M.
-// One wave per key row.  A head covers vph = dc/VEC consecutive 16-byte vectors (a power of two),
-// so the per-head sums are segmented butterflies over vph lanes (or whole-wave sums if vph >= 64).
+// One wave per kClsRows consecutive key rows of a sample (their loads are in flight together).  A
+// head covers vph = dc/VEC consecutive 16-byte vectors (a power of two), so the per-head sums are
+// segmented butterflies over vph lanes (or whole-wave sums if vph >= 64).
+constexpr int kClsRows = 4;
+__host__ __device__ __forceinline__ int cls_groups(int M) { return (M + 1 + kClsRows - 1) / kClsRows; }
+
 template <bool BF>
-__device__ __forceinline__ void cls_logits_row(
+__device__ __forceinline__ void cls_logits_rows(
     long item, const void* __restrict__ q_cls, const void* __restrict__ k_cls, const uint8_t* __restrict__ valid,
     const EncodeDims& p, float* __restrict__ logits)
 {
     constexpr int VEC = Vec<BF>::N;
+    constexpr int R = kClsRows;
     const int lane = lane_id();
-    const long rows = (long)p.B * (p.M + 1);
-    if (item >= rows) return;
-    const int b = (int)(item / (p.M + 1)), j = (int)(item % (p.M + 1));
-    if (j > 0 && valid && !valid[(size_t)b * p.M + (j - 1)]) return;     // padding: never read
+    const int gps = cls_groups(p.M);
+    if (item >= (long)p.B * gps) return;
+    const int b = (int)(item / gps), j0 = (int)(item % gps) * R;
+    bool act[R];                                     // wave-uniform; padding rows are never read
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int j = j0 + r;
+        act[r] = j <= p.M && (j == 0 || !valid || valid[(size_t)b * p.M + (j - 1)]);
+    }
 
     const size_t esz = BF ? 2 : 4;
     const char* qrow = static_cast<const char*>(q_cls) + (size_t)b * p.D * esz;
-    const char* krow = static_cast<const char*>(k_cls) + ((size_t)b * (p.M + 1) + j) * p.D * esz;
+    const char* krow = static_cast<const char*>(k_cls) + ((size_t)b * (p.M + 1) + j0) * p.D * esz;
+    const size_t rowb = (size_t)p.D * esz;
     const int nvec = p.D / VEC, vph = p.dc / VEC;
     const float scale = 1.0f / sqrtf((float)p.dc);
-    float* out = logits + (size_t)b * p.Hc * (p.M + 1) + j;
+    float* out = logits + (size_t)b * p.Hc * (p.M + 1) + j0;
 
-    float acc = 0.f;
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = 0.f;
     const int iters = (nvec + kWave - 1) / kWave;
     for (int it = 0; it < iters; ++it) {
         const int idx = it * kWave + lane;
-        float part = 0.f;
-        if (idx < nvec) {
-            float qv[VEC], kv[VEC];
-            Vec<BF>::load(qrow, idx * VEC, qv);
-            Vec<BF>::load(krow, idx * VEC, kv);
+        float part[R];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) part = fmaf(qv[e], kv[e], part);
+        for (int r = 0; r < R; ++r) part[r] = 0.f;
+        if (idx < nvec) {
+            float qv[VEC], kv[R][VEC];
+            Vec<BF>::load(qrow, idx * VEC, qv);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (act[r]) Vec<BF>::load(krow + r * rowb, idx * VEC, kv[r]);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (!act[r]) continue;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) part[r] = fmaf(qv[e], kv[r][e], part[r]);
+            }
         }
         if (vph < kWave) {
-            part = group_sum_rt(part, vph);
-            if (idx < nvec && (lane & (vph - 1)) == 0) out[(size_t)(idx / vph) * (p.M + 1)] = part * scale;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (!act[r]) continue;
+                const float tot = group_sum_rt(part[r], vph);
+                if (idx < nvec && (lane & (vph - 1)) == 0) out[(size_t)(idx / vph) * (p.M + 1) + r] = tot * scale;
+            }
         } else {
-            acc += part;
             const int per_head = vph / kWave;                 // iterations per head
-            if ((it + 1) % per_head == 0) {
-                const float tot = wave_sum(acc);
-                if (lane == 0) out[(size_t)(it / per_head) * (p.M + 1)] = tot * scale;
-                acc = 0.f;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                acc[r] += part[r];
+                if ((it + 1) % per_head == 0) {
+                    const float tot = wave_sum(acc[r]);
+                    if (act[r] && lane == 0) out[(size_t)(it / per_head) * (p.M + 1) + r] = tot * scale;
+                    acc[r] = 0.f;
+                }
             }
         }
     }
@@ -211,7 +239,7 @@ __device__ __forceinline__ void window_sim_item(
 }
 
 // One launch for both bandwidth-bound score passes: waves [0, B*W) take a window each (Eq. 5), the
-// following B*(1+M) waves a key row each (Eq. 6 logits; none when no key set is asked for).
+// following waves a few key rows each (Eq. 6 logits; none when no key set is asked for).
 template <int WSM, bool XBF, bool QKBF>
 __global__ __launch_bounds__(256) void encode_scores_kernel(
     const void* __restrict__ x, const void* __restrict__ q_cls, const void* __restrict__ k_cls,
@@ -220,7 +248,7 @@ __global__ __launch_bounds__(256) void encode_scores_kernel(
     const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
     const long n_win = (long)p.B * p.W;
     if (item < n_win) window_sim_item<WSM, XBF>(item, x, valid, p, sim);
-    else if (with_cls) cls_logits_row<QKBF>(item - n_win, q_cls, k_cls, valid, p, logits);
+    else if (with_cls) cls_logits_rows<QKBF>(item - n_win, q_cls, k_cls, valid, p, logits);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -731,7 +759,7 @@ extern "C" int mustdrop_encode_merge(
     p.nwx = Wg / kw; p.nwy = Hg / kh; p.nwt = T / kt;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const long items = (long)B * W + (key_budget > 0 ? (long)B * (M + 1) : 0);
+    const long items = (long)B * W + (key_budget > 0 ? (long)B * cls_groups(M) : 0);
     dim3 sgrid((unsigned)((items + 3) / 4));
     const bool xbf = x_dtype == MD_BF16, qkbf = qk_dtype == MD_BF16;
     const int with_cls = key_budget > 0;
