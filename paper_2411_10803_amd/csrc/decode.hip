@@ -532,12 +532,20 @@ __global__ __launch_bounds__(256) void decode_move_kernel(
     const int b = blockIdx.y;
     const int nm = n_move[b];
     const int rv = p.H * p.d / 8;
+    // source rows (beyond the new length) and destination rows (holes below it) never coincide, but
+    // the compiler cannot know: the vectors of a round are read into registers before any is written
     for (int t = blockIdx.x; t < nm; t += gridDim.x) {
         const long src = ((long)b * p.Lcap + movers[(long)b * p.Lcap + t]) * rv;
         const long dst = ((long)b * p.Lcap + holes[(long)b * p.Lcap + t]) * rv;
-        for (int c = threadIdx.x; c < rv; c += blockDim.x) {
-            k_cache[dst + c] = k_cache[src + c];
-            v_cache[dst + c] = v_cache[src + c];
+        for (int c = threadIdx.x; c < rv; c += 2 * blockDim.x) {
+            const int c2 = c + blockDim.x;
+            const bool two = c2 < rv;
+            const u32x4 k0 = k_cache[src + c], v0 = v_cache[src + c];
+            u32x4 k1 = k0, v1 = v0;
+            if (two) { k1 = k_cache[src + c2]; v1 = v_cache[src + c2]; }
+            k_cache[dst + c] = k0;
+            v_cache[dst + c] = v0;
+            if (two) { k_cache[dst + c2] = k1; v_cache[dst + c2] = v1; }
         }
     }
 }

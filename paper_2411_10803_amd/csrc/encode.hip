@@ -625,7 +625,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
                     if (okm[u]) v[u] = src[u][c];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (okm[u]) dst[u][c] = v[u];
+                    if (okm[u]) __builtin_nontemporal_store(v[u], dst[u] + c);
             }
         }
         return;

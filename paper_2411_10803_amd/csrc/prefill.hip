@@ -617,7 +617,8 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
     u32x4* hd = hidden_out + ((long)b * rows_cap + o) * hv;
     u32x4* kd = k_out + ((long)b * rows_cap + o) * kv;
     u32x4* vd = v_out + ((long)b * rows_cap + o) * kv;
-    // every row is read once and written once: streaming loads and stores, four vectors in flight
+    // every source row is read once (streaming loads; the copies are read again by the next stage),
+    // four vectors in flight
     auto copy2 = [&](const u32x4* __restrict__ s0, u32x4* __restrict__ d0, const u32x4* __restrict__ s1,
                      u32x4* __restrict__ d1, int n) {
         const int step = 2 * blockDim.x;
@@ -627,9 +628,9 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
             const u32x4 a0 = __builtin_nontemporal_load(s0 + c), a1 = __builtin_nontemporal_load(s1 + c);
             u32x4 b0 = a0, b1 = a1;
             if (two) { b0 = __builtin_nontemporal_load(s0 + c2); b1 = __builtin_nontemporal_load(s1 + c2); }
-            __builtin_nontemporal_store(a0, d0 + c);
-            __builtin_nontemporal_store(a1, d1 + c);
-            if (two) { __builtin_nontemporal_store(b0, d0 + c2); __builtin_nontemporal_store(b1, d1 + c2); }
+            d0[c] = a0;
+            d1[c] = a1;
+            if (two) { d0[c2] = b0; d1[c2] = b1; }
         }
     };
     copy2(ks, kd, vs, vd, kv);
