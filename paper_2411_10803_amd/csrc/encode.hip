@@ -58,6 +58,11 @@ template <> struct Vec<false> {
         const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c);
         o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
     }
+    // data that is not read again: streaming load
+    __device__ static __forceinline__ void load_once(const void* row, int c, float (&o)[4]) {
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c));
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
     __device__ static __forceinline__ void store(void* row, int c, const float (&o)[4]) {
         f32x4 v; v.x = o[0]; v.y = o[1]; v.z = o[2]; v.w = o[3];
         *reinterpret_cast<f32x4*>(static_cast<float*>(row) + c) = v;
@@ -65,10 +70,15 @@ template <> struct Vec<false> {
 };
 template <> struct Vec<true> {
     static constexpr int N = 8;
-    __device__ static __forceinline__ void load(const void* row, int c, float (&o)[8]) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c);
+    __device__ static __forceinline__ void widen(const u32x4 v, float (&o)[8]) {
         o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
         o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+    }
+    __device__ static __forceinline__ void load(const void* row, int c, float (&o)[8]) {
+        widen(*reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c), o);
+    }
+    __device__ static __forceinline__ void load_once(const void* row, int c, float (&o)[8]) {
+        widen(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c)), o);
     }
     __device__ static __forceinline__ void store(void* row, int c, const float (&o)[8]) {
         u32x4 v;
@@ -622,7 +632,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
                 u32x4 v[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (okm[u]) v[u] = src[u][c];
+                    if (okm[u]) v[u] = __builtin_nontemporal_load(src[u] + c);
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     if (okm[u]) __builtin_nontemporal_store(v[u], dst[u] + c);
@@ -650,7 +660,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
                 const int m = min(m0 + u, p.ws - 1);
                 okm[u] = m0 + u < p.ws && ((okmask >> m) & 1ull);
                 mm[u] = __builtin_bit_cast(float, wave_member(__builtin_bit_cast(int, mass_l), m));
-                if (okm[u]) Vec<BF>::load(xb + (size_t)wave_member(tok_l, m) * rowb, c, v[u]);
+                if (okm[u]) Vec<BF>::load_once(xb + (size_t)wave_member(tok_l, m) * rowb, c, v[u]);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
