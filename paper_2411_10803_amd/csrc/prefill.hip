@@ -128,12 +128,15 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     }
 
     // text-query fragments of this head: through the same LDS tile, one 32-row block at a time
+    // (all loads are issued before the first LDS pass: the fences below would otherwise serialise them)
     bf16x8 qf[NB][KS];
+    u32x4 sq[NB][KS];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+        Tile::gload(qb, tok_stride, i_base + 32 * nb, tl, lane, sq[nb]);  // rows >= txt_len read as zero
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        u32x4 sq[KS];
-        Tile::gload(qb, tok_stride, i_base + 32 * nb, tl, lane, sq);      // rows >= txt_len read as zero
-        Tile::to_lds(tile, lane, sq);
+        Tile::to_lds(tile, lane, sq[nb]);
         wave_lds_sync();
         Tile::frags(tile, lane, qf[nb]);
         wave_lds_sync();
