@@ -59,6 +59,25 @@ struct OperandTile {
             else st[t] = u32x4{0u, 0u, 0u, 0u};
         }
     }
+    // The same for a tile whose 32 rows all exist.  tile_base: first row of the tile (wave-uniform),
+    // lane_off: from lane_offset(); the addresses are a scalar base plus a tile-invariant lane offset,
+    // so a load costs no vector arithmetic.
+    __device__ static __forceinline__ uint32_t lane_offset(long row_stride, int lane) {
+        return (uint32_t)(((lane / CH) * row_stride + (lane % CH) * 8) * 2);
+    }
+    __device__ static __forceinline__ void gload_full(const uint16_t* tile_base, long row_stride, uint32_t lane_off,
+                                                      u32x4 (&st)[KS]) {
+#pragma unroll
+        for (int t = 0; t < KS; ++t)
+            st[t] = *reinterpret_cast<const u32x4*>(
+                reinterpret_cast<const char*>(tile_base + (long)t * ROWS_PER_LOAD * row_stride) + lane_off);
+    }
+    // either of the two, by a wave-uniform test
+    __device__ static __forceinline__ void gload_any(const uint16_t* base, long row_stride, int row0, int nrows, int lane,
+                                                     uint32_t lane_off, u32x4 (&st)[KS]) {
+        if (row0 + 32 <= nrows) gload_full(base + (long)row0 * row_stride, row_stride, lane_off, st);
+        else gload(base, row_stride, row0, nrows, lane, st);
+    }
     __device__ static __forceinline__ void to_lds(char* tile, int lane, const u32x4 (&st)[KS]) {
         const int chunk = lane % CH, sub = lane / CH;
 #pragma unroll
@@ -117,13 +136,16 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     u32x4 st[KS];
     // validity of this lane's key (lane % 32) in the tile that is in flight; fetched with the tile so
     // that its latency hides behind the previous tile's arithmetic
-    auto key_valid = [&](int j) {
+    // (kept as the loaded byte until the next iteration: turning it into a lane mask right away would
+    // make the wave wait for the load, and with it for the tile that was requested just before)
+    auto key_valid = [&](int j) -> uint32_t {
         const int jl = j + (lane & 31);
-        return jl < p.Mv ? (!vb || vb[jl]) : false;
+        return vb ? (uint32_t)vb[min(jl, p.Mv - 1)] : 1u;
     };
-    bool v_nxt = false;
+    uint32_t v_nxt = 0;
+    const uint32_t lane_off = Tile::lane_offset(tok_stride, lane);
     if (j0 < c1) {
-        Tile::gload(kb, tok_stride, j0, p.L, lane, st);
+        Tile::gload_any(kb, tok_stride, j0, p.L, lane, lane_off, st);
         v_nxt = key_valid(j0);
     }
 
@@ -158,9 +180,9 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         bf16x8 kf[KS];
         Tile::frags(tile, lane, kf);
         wave_lds_sync();
-        const bool v_ok = v_nxt;
+        const bool v_ok = v_nxt != 0 && j0 + (lane & 31) < p.Mv;
         if (j0 + 32 * 4 < c1) {                                                 // prefetch
-            Tile::gload(kb, tok_stride, j0 + 32 * 4, p.L, lane, st);
+            Tile::gload_any(kb, tok_stride, j0 + 32 * 4, p.L, lane, lane_off, st);
             v_nxt = key_valid(j0 + 32 * 4);
         }
         // validity of the 32 keys of this tile as a bit mask (vision keys only)
@@ -169,12 +191,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         // and a tile that reaches into the text keys (causal mask, per text row)
         const bool vision_tile = j0 + 32 <= p.Mv;
         const bool all_visible = vision_tile && vmask == 0xFFFFFFFFu;
-        bool key_ok[16];                             // vision tile: is the key of accumulator register r valid
-        {
-            const uint32_t mine = vmask >> (4 * (lane >> 5));   // tile_row(r, lane) = 8*(r/4) + 4*(lane/32) + r%4
-#pragma unroll
-            for (int r = 0; r < 16; ++r) key_ok[r] = (mine >> (8 * (r >> 2) + (r & 3))) & 1u;
-        }
+        const uint32_t mine = vmask >> (4 * (lane >> 5));   // tile_row(r, lane) = 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             f32x16 acc;
@@ -183,16 +200,16 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nb][ks], acc, 0, 0, 0);
-            float t[16];
+            // invisible entries become -inf; the positive scale is applied after the maximum
             float bm = -INFINITY;
             if (all_visible) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { t[r] = acc[r] * scale_log2e; bm = fmaxf(bm, t[r]); }
+                for (int r = 0; r < 16; ++r) bm = fmaxf(bm, acc[r]);
             } else if (vision_tile) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    t[r] = key_ok[r] ? acc[r] * scale_log2e : -INFINITY;
-                    bm = fmaxf(bm, t[r]);
+                    if (!((mine >> (8 * (r >> 2) + (r & 3))) & 1u)) acc[r] = -INFINITY;
+                    bm = fmaxf(bm, acc[r]);
                 }
             } else {
                 const int i = i_base + 32 * nb + (lane & 31);
@@ -201,15 +218,15 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
                     const int row = tile_row(r, lane);
                     const int j = j0 + row;
                     const bool vis = j < p.Mv ? ((vmask >> row) & 1u) : (j < p.L && (j - p.Mv) <= i);
-                    t[r] = vis ? acc[r] * scale_log2e : -INFINITY;
-                    bm = fmaxf(bm, t[r]);
+                    if (!vis) acc[r] = -INFINITY;
+                    bm = fmaxf(bm, acc[r]);
                 }
             }
-            const float mn = fmaxf(m[nb], bm);
+            const float mn = fmaxf(m[nb], bm * scale_log2e);
             if (mn > -INFINITY) {
                 float s = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s += fast_exp2(t[r] - mn);
+                for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[r], scale_log2e, -mn));
                 z[nb] = z[nb] * fast_exp2(m[nb] - mn) + s;
                 m[nb] = mn;
             }
@@ -738,6 +755,7 @@ extern "C" int mustdrop_prefill_filter(
     if ((long)B * (Mv + N) > (1l << 28)) return fail(MD_ESHAPE, "prefill_filter: too many tokens");
     if (C % 8) return fail(MD_EALIGN, "prefill_filter: a hidden row of C=%d bf16 is not a multiple of 16 bytes", C);
     if (std::isnan(softmax_scale) || std::isnan(gamma) || std::isnan(alpha)) return fail(MD_EINVAL, "prefill_filter: NaN parameter");
+    if (!(softmax_scale > 0.f) || std::isinf(softmax_scale)) return fail(MD_EINVAL, "prefill_filter: softmax_scale must be positive and finite");
     if (mode == MD_FILTER_BUDGET) {
         if (budget < 0) return fail(MD_EINVAL, "prefill_filter: negative budget");
         if (!(gamma > 0.f) || !(alpha > 0.f)) return fail(MD_EINVAL, "prefill_filter: budget mode needs gamma > 0 and alpha > 0");
