@@ -115,6 +115,21 @@ def timed(torch, fn, iters):
     return (time.perf_counter() - t0) * 1e3 / iters
 
 
+# HBM bytes per launch on the benchmark workload, from two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same counters show for a plain
+# 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
+# The runs and the raw figures are in profiles/hbm_traffic_cfg2_llava15_b16.txt.
+MEASURED_HBM_TRAFFIC_BYTES = {
+    "prefill_compact": int((49007.1 * 2.0 + 97728.0) * 1024),
+    "prefill_rowstats": int((45191.7 * 2.0 + 8320.0) * 1024),
+    "prefill_colscore": int((41102.4 * 2.0 + 72.0) * 1024),
+    "encode_scores": int((18672.1 * 2.0 + 855.7) * 1024),
+    "encode_emit": int((9335.5 * 2.0 + 14286.0) * 1024),
+    "decode_logits": int((16837.0 * 2.0 + 765.0) * 1024),
+    "decode_move": int((8077.0 * 2.0 + 16000.0) * 1024),
+}
+
+
 def kernel_bytes(cfg, pipe, counts):
     """Algorithmic bytes per launch of every kernel of the step (what the method itself must move)."""
     B, M, N, H, d, C, D = cfg.B, cfg.M, cfg.N, cfg.H, cfg.d, cfg.C, cfg.D
@@ -309,9 +324,11 @@ def main():
         kernels[name] = {"avg_us": round(us, 2), "calls": r["calls"], "algorithmic_MB": round(kb.get(name, 0) / 1e6, 3),
                          "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     dominant = max(kernels, key=lambda n: kernels[n]["avg_us"])
+    traffic = MEASURED_HBM_TRAFFIC_BYTES.get(dominant) if cfg.name == "cfg2_llava15_b16" else None
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"], "traffic": None,
-                "avg_us": kernels[dominant]["avg_us"]}
+                "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"], "traffic": traffic,
+                "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
+                "algorithmic_bytes": kb.get(dominant, 0), "avg_us": kernels[dominant]["avg_us"]}
 
     tokens = cfg.B * cfg.M
     result = {

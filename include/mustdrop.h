@@ -184,11 +184,12 @@ int mustdrop_decode_append(
 /* ------------------------------------------------------------------------------------------
  * Benchmarking aid (not part of the method): per-kernel timing with HIP events.
  * Between mustdrop_profile_start() and mustdrop_profile_stop() every kernel the library launches
- * is bracketed by an event pair recorded on the launch stream.  _stop waits for the events,
- * destroys them and reports, per distinct kernel name, the summed milliseconds and the number of
- * launches: names is a host array of cap*64 chars, total_ms / calls host arrays of cap entries,
- * *n_out the number of names filled.  Host pointers.  Not thread-safe; do not use while another
- * thread is inside the library. */
+ * carries an event pair that receives the begin and end timestamps of that dispatch on its stream
+ * (what a kernel trace reports; marker events around a launch would add their own few microseconds).
+ * _stop waits for the events, destroys them and reports, per distinct kernel name, the summed
+ * milliseconds and the number of launches: names is a host array of cap*64 chars, total_ms / calls
+ * host arrays of cap entries, *n_out the number of names filled.  Host pointers.  Not thread-safe;
+ * do not use while another thread is inside the library. */
 int mustdrop_profile_start(void);
 int mustdrop_profile_stop(char* names, float* total_ms, int* calls, int cap, int* n_out);
 

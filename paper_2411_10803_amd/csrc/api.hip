@@ -30,15 +30,13 @@ std::vector<ProfRecord> g_prof;
 
 bool profiling() { return g_prof_on; }
 
-void profile_mark_begin(const char* kernel_name, hipStream_t st) {
+void profile_events(const char* kernel_name, hipEvent_t* start, hipEvent_t* stop) {
     ProfRecord r{kernel_name, nullptr, nullptr};
-    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-    (void)hipEventRecord(r.start, st);
+    if (hipEventCreate(&r.start) != hipSuccess) return;
+    if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
     g_prof.push_back(r);
-}
-
-void profile_mark_end(hipStream_t st) {
-    if (!g_prof.empty()) (void)hipEventRecord(g_prof.back().stop, st);
+    *start = r.start;
+    *stop = r.stop;
 }
 
 }  // namespace md

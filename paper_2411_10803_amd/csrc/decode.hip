@@ -659,10 +659,10 @@ extern "C" int mustdrop_decode_evict(
         if (blocks_x < 1) blocks_x = 1;
         dim3 g1(blocks_x, B);
         switch (nit) {
-            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
-            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
-            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
-            default: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, w.logits, w.stat_partial))); break;
+            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 1>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
+            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 2>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
+            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 4>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
+            default: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 8>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
         }
         n_part = blocks_x;
     } else {
@@ -670,13 +670,13 @@ extern "C" int mustdrop_decode_evict(
         tpb = tpb < 4 ? 4 : (tpb > 32 ? 32 : tpb);
         dim3 g1((Lcap + tpb - 1) / tpb, B);
         switch (d / 8) {
-            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-            case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-            case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
-            default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64><<<g1, 256, 0, st>>>(qp, kp, len, p, softmax_scale, tpb, w.logits))); break;
+            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
         }
     }
     const bool fast_h = H == 4 || H == 8 || H == 16 || H == 32 || H == 64;
@@ -684,9 +684,9 @@ extern "C" int mustdrop_decode_evict(
         const size_t lds = 2 * sizeof(int) * (size_t)Lcap;
         const int ipt = (Lcap + 1023) / 1024;
 #define MD_SELECT_FAST(I, E)                                                                                       \
-    MD_LAUNCH("decode_select", st, (decode_select_fast_kernel<I, E><<<B, 1024, lds, st>>>(                          \
+    MD_LAUNCH("decode_select", st, (decode_select_fast_kernel<I, E>), B, 1024, lds,                          \
         p, w.logits, w.stat_partial, n_part, decay, budget, acc, ids, protect, len, w.holes, w.movers, w.n_move,   \
-        evicted_ids, evicted_count)))
+        evicted_ids, evicted_count)
 #define MD_SELECT_FAST_H(I)                                                                                        \
     switch (H) {                                                                                                   \
         case 4: MD_SELECT_FAST(I, 1); break;                                                                       \
@@ -703,12 +703,12 @@ extern "C" int mustdrop_decode_evict(
 #undef MD_SELECT_FAST
     } else {
         const size_t lds = sizeof(float) * ((size_t)2 * H + 1024);
-        MD_LAUNCH("decode_select", st, (decode_select_kernel<<<B, 1024, lds, st>>>(
-            p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count)));
+        MD_LAUNCH("decode_select", st, (decode_select_kernel), B, 1024, lds,
+            p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
     }
     dim3 g3(32, B);
-    MD_LAUNCH("decode_move", st, (decode_move_kernel<<<g3, 256, 0, st>>>(
-        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache))));
+    MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
+        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache));
     return check_launch("decode_evict");
 }
 
@@ -727,8 +727,8 @@ extern "C" int mustdrop_decode_append(
         return fail(MD_EALIGN, "decode_append: tensors must be 16-byte aligned");
     DecodeDims p{B, Lcap, H, d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MD_LAUNCH("decode_append", st, (decode_append_kernel<<<B, 256, 0, st>>>(
+    MD_LAUNCH("decode_append", st, (decode_append_kernel), B, 256, 0,
         p, static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
-        static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new)));
+        static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new);
     return check_launch("decode_append");
 }

@@ -696,10 +696,10 @@ EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
 template <int WSM>
 void launch_scores(dim3 grid, hipStream_t st, bool xbf, bool qkbf, const void* x, const void* q_cls, const void* k_cls,
                    const uint8_t* valid, const EncodeDims& p, int with_cls, float* sim, float* logits) {
-    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
-    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
-    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
-    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false><<<grid, 256, 0, st>>>(x, q_cls, k_cls, valid, p, with_cls, sim, logits)));
+    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
 }
 
 }  // namespace
@@ -779,19 +779,19 @@ extern "C" int mustdrop_encode_merge(
     else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
 #define MD_DECIDE_FAST(IPT_)                                                                                  \
-    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_><<<B, 1024, 6 * (size_t)M, st>>>(              \
+    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_>), B, 1024, 6 * (size_t)M,              \
         p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.wmerged, wsp.dstpos,                          \
-        out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)))
+        out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)
     if (M <= 1024) MD_DECIDE_FAST(1);
     else if (M <= 2048) MD_DECIDE_FAST(2);
     else if (M <= 4096) MD_DECIDE_FAST(4);
     else if (M <= 8192) MD_DECIDE_FAST(8);
     else
-        MD_LAUNCH("encode_decide", st, (encode_decide_kernel<<<B, 1024, 0, st>>>(
+        MD_LAUNCH("encode_decide", st, (encode_decide_kernel), B, 1024, 0,
             p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
-            out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)));
+            out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out);
 #undef MD_DECIDE_FAST
-    if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x)));
-    else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false><<<wgrid, 256, 0, st>>>(x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x)));
+    if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true>), wgrid, 256, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
+    else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false>), wgrid, 256, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
     return check_launch("encode_merge");
 }

@@ -1,6 +1,7 @@
 // Host-side helpers of the C ABI: thread-local error text, argument checks, workspace carving.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -48,14 +49,21 @@ inline size_t elt_size(int dtype) { return dtype == MD_BF16 ? 2 : 4; }
 // Optional per-kernel timing (mustdrop_profile_start / _stop): when enabled, every launch is
 // bracketed by a pair of HIP events on the launch stream.  Off by default: two branches per launch.
 bool profiling();
-void profile_mark_begin(const char* kernel_name, hipStream_t st);
-void profile_mark_end(hipStream_t st);
+// A pair of events for the next launch of `kernel_name` (timing session open), or two null handles.
+void profile_events(const char* kernel_name, hipEvent_t* start, hipEvent_t* stop);
 
-#define MD_LAUNCH(name, st, ...)                                   \
-    do {                                                           \
-        if (md::profiling()) md::profile_mark_begin(name, st);     \
-        __VA_ARGS__;                                               \
-        if (md::profiling()) md::profile_mark_end(st);             \
+// Every kernel launch of the library.  In a timing session the launch carries an event pair that
+// receives the dispatch's own begin and end timestamps (the figures a kernel trace shows), not the
+// time at which a marker on the stream is reached.
+#define MD_LAUNCH(name, st, kern, grid, block, shmem, ...)                                         \
+    do {                                                                                           \
+        if (md::profiling()) {                                                                     \
+            hipEvent_t md_e0 = nullptr, md_e1 = nullptr;                                           \
+            md::profile_events(name, &md_e0, &md_e1);                                              \
+            hipExtLaunchKernelGGL(kern, dim3(grid), dim3(block), shmem, st, md_e0, md_e1, 0, __VA_ARGS__); \
+        } else {                                                                                   \
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(block), shmem, st, __VA_ARGS__);              \
+        }                                                                                          \
     } while (0)
 
 }  // namespace md

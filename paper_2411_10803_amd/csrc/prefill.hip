@@ -707,18 +707,18 @@ int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t s
     constexpr int NW = MD_PF_NW;
     const int ntg = (NB + NBW - 1) / NBW;
     dim3 g1(p.nch * ntg, p.H, p.B);
-    MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW, KS><<<g1, 256, 0, st>>>(
+    MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW, KS>), g1, 256, 0,
         static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
-        w.partial, w.cstat, w.qfrag)));
+        w.partial, w.cstat, w.qfrag);
     if (p.nch > 1) {
         const long n = (long)p.B * p.H * p.Npad;
-        MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
-            w.partial, txt_len, p, w.cstat)));
+        MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel), (unsigned)((n + 255) / 256), 256, 0,
+            w.partial, txt_len, p, w.cstat);
     }
     const int nt = (p.Mv + 31) / 32;
     dim3 g2(p.B % 8 == 0 || 8 % p.B != 0 ? nt * p.B : 8 * ((nt + 8 / p.B - 1) / (8 / p.B)));
-    MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB, KS, NW><<<g2, 64 * NW, 0, st>>>(
-        w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, w.V, w.I)));
+    MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB, KS, NW>), g2, 64 * NW, 0,
+        w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, w.V, w.I);
     return MD_OK;
 }
 
@@ -806,21 +806,21 @@ extern "C" int mustdrop_prefill_filter(
     if (rc != MD_OK) return rc;
     int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
 #define MD_PSELECT_FAST(IPT_)                                                                               \
-    MD_LAUNCH("prefill_select", st, (prefill_select_fast_kernel<IPT_><<<B, 1024, 0, st>>>(                 \
+    MD_LAUNCH("prefill_select", st, (prefill_select_fast_kernel<IPT_>), B, 1024, 0,                 \
         p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,                          \
-        src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)))
+        src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)
     if (Mv <= 1024) MD_PSELECT_FAST(1);
     else if (Mv <= 2048) MD_PSELECT_FAST(2);
     else if (Mv <= 4096) MD_PSELECT_FAST(4);
     else if (Mv <= 8192) MD_PSELECT_FAST(8);
     else
-        MD_LAUNCH("prefill_select", st, (prefill_select_kernel<<<B, 1024, 0, st>>>(
+        MD_LAUNCH("prefill_select", st, (prefill_select_kernel), B, 1024, 0,
             p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,
-            w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)));
+            w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv);
 #undef MD_PSELECT_FAST
     dim3 gc(Rcap + N, B);
-    MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel<<<gc, 256, 0, st>>>(p, src_row,
+    MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel), gc, 256, 0, p, src_row,
         static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
-        static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out))));
+        static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out));
     return check_launch("prefill_filter");
 }
