@@ -200,6 +200,49 @@ def decode_loop_cfg5(torch, md, harness, steps):
     }
 
 
+def progressive_prefill(torch, md, harness, cfg, pipe, iters=100):
+    """Sec. 3.4 applied in three successive layers: 576 -> 192 -> 128 -> 64 vision tokens, every call on
+    the compacted rows of the one before, with that call's protect flags as key set."""
+    B, N, H = cfg.B, cfg.N, cfg.H
+    budgets = list(cfg.budgets)
+    q = [pipe.q_txt] + [harness.to_dev(wl.layer_text_queries(cfg, l), True) for l in range(1, len(budgets))]
+    key0 = harness.to_dev(wl.random_key_mask(cfg, cfg.key_budget))
+    outs, wss, Mv = [], [], cfg.M
+    for R in budgets:
+        outs.append(None)
+        wss.append(md.prefill_workspace(B, Mv, N, H, R))
+        Mv = R
+    state = {}
+
+    def call(l):
+        R = budgets[l]
+        if l == 0:
+            k, v, h, Mv, key = pipe.k, pipe.v, pipe.hidden, cfg.M, key0
+        else:
+            o = outs[l - 1]
+            k, v, h, Mv = o["k_out"], o["v_out"], o["hidden_out"], budgets[l - 1]
+            key = state[l]
+        outs[l] = md.mustdrop_prefill_filter(q[l], k, v, h, None, None, key, Mv, pipe.scale, md.FILTER_BUDGET, R,
+                                             1.0 / Mv, 2.0 / (Mv + N), Rcap=R, out=outs[l], workspace=wss[l],
+                                             want_scores=False)
+        if l + 1 < len(budgets):                     # key flags of the next call: the vision part of out_protect
+            state[l + 1] = outs[l]["out_protect"][:, :R].contiguous()
+
+    def chain():
+        for l in range(len(budgets)):
+            call(l)
+
+    for _ in range(3):
+        chain()
+    total = timed(torch, chain, iters)
+    per_call = [timed(torch, lambda l=l: call(l), iters) for l in range(len(budgets))]
+    kept = [int(o["kept_count"].min()) for o in outs]
+    assert kept == budgets, kept
+    return {"workload": cfg.name, "vision_tokens": [cfg.M] + budgets, "us_per_chain": total * 1e3,
+            "us_per_call": [round(x * 1e3, 2) for x in per_call],
+            "vision_tokens_per_s": B * cfg.M / (total * 1e-3)}
+
+
 def cpu_baseline(cfg, pipe, min_seconds=10.0):
     """The oracle, as it stands, on this host: the same chained step on the full batch of 16."""
     import oracle
@@ -268,6 +311,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--no-progressive", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) to scale rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -347,6 +391,8 @@ def main():
     }
     if not args.no_decode_loop:
         result["decode_loop"] = decode_loop_cfg5(torch, md, harness, args.decode_steps)
+    if not args.no_progressive:
+        result["progressive_prefill"] = progressive_prefill(torch, md, harness, cfg, pipe)
     if not args.no_parity:
         result["parity"] = parity_check(cfg, pipe, harness)
     if not args.no_cpu_baseline:

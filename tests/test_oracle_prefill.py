@@ -230,3 +230,30 @@ def test_boundary_cases_of_eq9_and_eq10():
     assert o["kept_count"][0] == 3
     o = run(t, mode=FILTER_THRESHOLD, gamma=1.0, alpha=np.nextafter(np.float32(0.25), np.float32(1)))
     assert o["kept_count"][0] == 0
+
+
+def test_chained_calls_keep_the_key_set_and_shrink_to_the_budgets():
+    """Sec. 3.3 / 3.4: tokens of the key set are retained by every later filtering step.  Three chained
+    oracle calls (budgets 48 -> 20 -> 9) on a small sample: every call keeps exactly its budget, rows are
+    bitwise copies, and the keys of the first call are still present at the end."""
+    cfg = wl.tiny(wl.CONFIGS[2], B=2, Hg=8, Wg=8, N=8, H=2, d=64, C=64)
+    t = wl.prefill_inputs(cfg)
+    key = wl.random_key_mask(cfg, 6)
+    keys0 = [set(np.flatnonzero(key[b]).tolist()) for b in range(cfg.B)]
+    scale = 1.0 / np.sqrt(cfg.d)
+    Mv, vis = cfg.M, None
+    orig = np.tile(np.arange(cfg.M), (cfg.B, 1))
+    for layer, R in enumerate((48, 20, 9)):
+        q = t["q_txt"] if layer == 0 else wl.layer_text_queries(cfg, layer)
+        o = oracle.prefill_filter(q, t["k"], t["v"], t["hidden"], vis, None, key, Mv, scale, FILTER_BUDGET, R,
+                                  1.0 / Mv, 2.0 / (Mv + cfg.N), R)
+        assert np.all(o["kept_count"] == R)
+        for b in range(cfg.B):
+            rows = np.concatenate([o["kept_index"][b], Mv + np.arange(cfg.N)])
+            assert np.array_equal(o["k_out"][b], t["k"][b, rows])
+            assert np.array_equal(o["hidden_out"][b], t["hidden"][b, rows])
+        orig = np.take_along_axis(orig, o["kept_index"], axis=1)
+        t = {"q_txt": q, "k": o["k_out"], "v": o["v_out"], "hidden": o["hidden_out"]}
+        key, vis, Mv = o["out_protect"][:, :R].copy(), None, R
+    for b in range(cfg.B):
+        assert keys0[b] <= set(orig[b].tolist())

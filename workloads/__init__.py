@@ -265,6 +265,15 @@ def prefill_inputs(cfg: Config, samples: Optional[Sequence[int]] = None, literal
     return out
 
 
+def layer_text_queries(cfg: Config, layer: int, samples: Optional[Sequence[int]] = None) -> np.ndarray:
+    """q_txt [b, N, H, d] bf16 of a later LLM layer (layer >= 1) for chained, progressively smaller
+    prefill calls; elements ~ N(0,1), independent of the layer-0 queries of prefill_inputs()."""
+    assert layer >= 1
+    rngs = _sample_rngs(cfg.seed, cfg.B, 20 + layer)
+    idx = list(range(cfg.B)) if samples is None else list(samples)
+    return np.stack([_normal_bf16(rngs[b], (cfg.N, cfg.H, cfg.d)) for b in idx])
+
+
 def random_bf16_payload(rng: np.random.Generator, shape) -> np.ndarray:
     """Cheap finite bf16 bit patterns (|value| < 2) for tensors that are only moved."""
     bits = rng.integers(0, 1 << 16, size=shape, dtype=np.uint16)
