@@ -574,6 +574,10 @@ __global__ __launch_bounds__(256) void decode_append_kernel(
     }
 }
 
+#ifndef MD_DEC_BLOCKS
+#define MD_DEC_BLOCKS 4096   // target number of blocks of the streaming logits kernel
+#endif
+
 struct DecodeWorkspace {
     float* logits; float2* stat_partial; uint8_t* keep; int32_t* holes; int32_t* movers; int32_t* n_move;
     size_t bytes;
@@ -652,7 +656,7 @@ extern "C" int mustdrop_decode_evict(
     int n_part = 0;                                   // > 0: the logits kernel left per-block softmax statistics
     if (d == 128 && (nit == 1 || nit == 2 || nit == 4 || nit == 8)) {
         // streaming shape: about 16 waves per CU in flight, each striding over its sample's entries
-        int blocks_x = (4096 + B - 1) / B;
+        int blocks_x = (MD_DEC_BLOCKS + B - 1) / B;
         const int max_x = (Lcap + 3) / 4;
         if (blocks_x > max_x) blocks_x = max_x;
         if (blocks_x > kMaxStatParts) blocks_x = kMaxStatParts;
