@@ -159,7 +159,8 @@ int mustdrop_prefill_filter(
  *   evicted_ids [B, Lcap] or NULL: ids of the evicted entries in ascending (pre-compaction) slot order
  *   evicted_count [B] or NULL
  *
- * Limits: d a power of two in [8, 512]; H divides 1024.
+ * Limits: d a power of two in [8, 512]; H <= 1024 (rows of 1, 2, 4 or 8 KiB with d = 128 and
+ * H in {4, 8, 16, 32, 64} take the streaming kernels, other shapes the general ones).
  */
 size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H);
 

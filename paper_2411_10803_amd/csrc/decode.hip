@@ -435,7 +435,7 @@ __global__ __launch_bounds__(1024) void decode_select_kernel(
         return;
     }
     // per-head softmax statistics over the live entries: thread = (part, head)
-    const int parts = blockDim.x / H;                // host guarantees H <= blockDim.x and H | blockDim.x
+    const int parts = blockDim.x / H;                // host guarantees H <= blockDim.x; threads beyond parts*H idle here
     const int h = tid % H, part = tid / H;
     {
         float mx = -INFINITY;
@@ -600,7 +600,7 @@ int check_decode_dims(const char* who, int B, int Lcap, int H, int d) {
     if (B <= 0 || Lcap <= 0 || H <= 0 || d <= 0) return fail(MD_EINVAL, "%s: B, Lcap, H, d must be positive", who);
     if (d != 8 && d != 16 && d != 32 && d != 64 && d != 128 && d != 256 && d != 512)
         return fail(MD_ESHAPE, "%s: head dim %d must be a power of two in [8, 512]", who, d);
-    if (H > 1024 || (1024 % H) != 0) return fail(MD_ESHAPE, "%s: H=%d must divide 1024", who, H);
+    if (H > 1024) return fail(MD_ESHAPE, "%s: H=%d exceeds the limit of 1024 heads", who, H);
     if ((long)B * Lcap > (1l << 28)) return fail(MD_ESHAPE, "%s: cache too large", who);
     return MD_OK;
 }

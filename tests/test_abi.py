@@ -113,7 +113,7 @@ def decode(lib, **kw):
 def test_decode_argument_errors(lib):
     assert decode(lib, q=None) == 1
     assert decode(lib, d=96) == 2
-    assert decode(lib, H=48) == 2
+    assert decode(lib, H=2048) == 2
     assert decode(lib, budget=-5) == 1
     assert decode(lib, v=P(0x10000000)) == 4
     assert decode(lib, wsb=0) == 5

@@ -39,7 +39,8 @@ def test_prefill_more_than_8192_vision_tokens():
         assert g["kept_count"][0] == R
 
 
-@pytest.mark.parametrize("H,d,L0", [(2, 64, 300), (32, 64, 500), (8, 256, 200), (1, 128, 9000), (32, 128, 9000)])
+@pytest.mark.parametrize("H,d,L0", [(2, 64, 300), (32, 64, 500), (8, 256, 200), (1, 128, 9000), (32, 128, 9000),
+                                    (5, 64, 700), (40, 128, 600), (28, 128, 1300)])
 def test_decode_general_kernels(H, d, L0):
     from paper_2411_10803_amd import harness
     cfg = wl.tiny(wl.CONFIGS[5], B=2, L0=L0, steps=1, decode_budget=L0 // 3, n_protect=L0 // 10, H=H, d=d)
