@@ -126,8 +126,9 @@ int mustdrop_encode_merge(
  *   out_protect[B, Rcap+N] u8 or NULL: 1 for key tokens and text rows (the decode stage's protect flags)
  *   score_global, score_indiv [B, Mv] f32 or NULL: V_j and I_j (0 for invalid tokens)
  *
- * Limits: d in {64, 128}; N <= 128; H <= 128; softmax_scale positive and finite; C*2 and H*d*2
- * multiples of 16 bytes.
+ * Limits: d in {64, 128}; N <= 1024 (tuned for N <= 128: a longer prompt re-reads K once per 64
+ * text rows in the first sweep and once per 128 in the second); H <= 128; softmax_scale positive
+ * and finite; C*2 and H*d*2 multiples of 16 bytes.
  */
 size_t mustdrop_prefill_filter_workspace_bytes(int B, int Mv, int N, int H, int Rcap);
 

@@ -286,13 +286,14 @@ __global__ __launch_bounds__(256) void prefill_cstat_kernel(
 // K tiles go global -> registers (prefetched one head ahead) -> wave-private LDS -> fragments;
 // text-query fragments come from qfrag with coalesced loads.  The row statistics are folded into one
 // constant per (head, text row): p = exp2(s*scale*log2e + c), c = -m - log2(Z*H), so a probability
-// costs one FMA and one exp2.  NB = number of 32-row text blocks (all of them: the column sum and
-// max run over every text row).
+// costs one FMA and one exp2.  NB <= 4 = number of 32-row text blocks of this launch, starting at
+// block nb0: prompts of more than 128 rows take one launch per 128 rows, each writing its own
+// partial column sums and maxima, merged by prefill_merge_groups_kernel.
 template <int NB, int KS, int NW>
 __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
     const bf16x8* __restrict__ qfrag, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len,
-    const float* __restrict__ cstat, PrefillDims p, float scale_log2e,
+    const float* __restrict__ cstat, PrefillDims p, float scale_log2e, int nb0,
     float* __restrict__ Vout, float* __restrict__ Iout)
 {
     using Tile = OperandTile<KS>;
@@ -339,8 +340,8 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
 
     constexpr int TP = (NB + 1) / 2;                 // text blocks are processed in pairs (64 registers of fragments)
     for (int h = wv; h < p.H; h += NW) {
-        const bf16x8* qh = qfrag + ((long)b * p.H + h) * NB * KS * kWave + lane;
-        const float* ch = cstat + ((long)b * p.H + h) * p.Npad + (lane & 31);
+        const bf16x8* qh = qfrag + (((long)b * p.H + h) * (p.Npad / 32) + nb0) * KS * kWave + lane;
+        const float* ch = cstat + ((long)b * p.H + h) * p.Npad + 32 * nb0 + (lane & 31);
         bf16x8 qf[2][KS];
         float c[2];
         auto load_pair = [&](int tp) {
@@ -407,7 +408,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
         __syncthreads();
         constexpr int per = (32 * HALF + PARTS - 1) / PARTS;
         for (int ii = part * per; ii < min((part + 1) * per, 32 * HALF); ++ii) {
-            if (half * 32 + ii >= tl) break;
+            if ((nb0 + half) * 32 + ii >= tl) break;
             float a = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w)
@@ -662,6 +663,17 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
     }
 }
 
+// Prompts of more than 128 text rows: V = sum, I = max over the launches' partial results (group 0 holds the result).
+__global__ __launch_bounds__(256) void prefill_merge_groups_kernel(long n, int groups, float* __restrict__ V, float* __restrict__ I)
+{
+    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    float v = V[e], m = I[e];
+    for (int g = 1; g < groups; ++g) { v += V[g * n + e]; m = fmaxf(m, I[g * n + e]); }
+    V[e] = v;
+    I[e] = m;
+}
+
 struct PrefillWorkspace {
     float2* partial; float* cstat; bf16x8* qfrag; float* V; float* I; float* score; int32_t* src_row;
     size_t bytes;
@@ -692,33 +704,57 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
     w.partial = c.take<float2>((size_t)B * H * 64 * Npad);
     w.cstat = c.take<float>((size_t)B * H * Npad);
     w.qfrag = c.take<bf16x8>((size_t)B * H * Npad * 16);      // [B][H][NB][KS][64] fragments, d <= 128
-    w.V = c.take<float>((size_t)B * Mv);
-    w.I = c.take<float>((size_t)B * Mv);
+    const int groups = (Npad / 32 + 3) / 4;                    // column-score launches (128 text rows each)
+    w.V = c.take<float>((size_t)groups * B * Mv);
+    w.I = c.take<float>((size_t)groups * B * Mv);
     w.score = c.take<float>((size_t)B * Mv);
     w.src_row = c.take<int32_t>((size_t)B * (Rcap + N));
     w.bytes = c.off;
     return w;
 }
 
-template <int NBW, int NB, int KS>
+template <int KS>
 int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t st, const void* q_txt, const void* k,
                   const uint8_t* vis_valid, const int32_t* txt_len, float scale_log2e) {
-    // NBW: 32-row text blocks per block of sweep 1 (<= 2); NB: all text blocks (sweep 2)
     constexpr int NW = MD_PF_NW;
-    const int ntg = (NB + NBW - 1) / NBW;
+    const int nbt = p.Npad / 32;                     // 32-row text blocks in all
+    // sweep 1: a block covers two text blocks (one if there is only one)
+    const int ntg = nbt == 1 ? 1 : (nbt + 1) / 2;
     dim3 g1(p.nch * ntg, p.H, p.B);
-    MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW, KS>), g1, 256, 0,
-        static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
-        w.partial, w.cstat, w.qfrag);
+    if (nbt == 1)
+        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<1, KS>), g1, 256, 0,
+            static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
+            w.partial, w.cstat, w.qfrag);
+    else
+        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<2, KS>), g1, 256, 0,
+            static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
+            w.partial, w.cstat, w.qfrag);
     if (p.nch > 1) {
         const long n = (long)p.B * p.H * p.Npad;
         MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel), (unsigned)((n + 255) / 256), 256, 0,
             w.partial, txt_len, p, w.cstat);
     }
+    // sweep 2: one launch per 128 text rows
     const int nt = (p.Mv + 31) / 32;
     dim3 g2(p.B % 8 == 0 || 8 % p.B != 0 ? nt * p.B : 8 * ((nt + 8 / p.B - 1) / (8 / p.B)));
-    MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB, KS, NW>), g2, 64 * NW, 0,
-        w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, w.V, w.I);
+    const long nv = (long)p.B * p.Mv;
+    const int groups = (nbt + 3) / 4;
+    for (int g = 0; g < groups; ++g) {
+        const int nb0 = 4 * g, nbg = nbt - nb0 < 4 ? nbt - nb0 : 4;
+        float* Vg = w.V + g * nv;
+        float* Ig = w.I + g * nv;
+#define MD_COLSCORE(NB_)                                                                                       \
+        MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB_, KS, NW>), g2, 64 * NW, 0,                  \
+            w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, nb0, Vg, Ig)
+        if (nbg == 1) MD_COLSCORE(1);
+        else if (nbg == 2) MD_COLSCORE(2);
+        else if (nbg == 3) MD_COLSCORE(3);
+        else MD_COLSCORE(4);
+#undef MD_COLSCORE
+    }
+    if (groups > 1)
+        MD_LAUNCH("prefill_merge_groups", st, (prefill_merge_groups_kernel), (unsigned)((nv + 255) / 256), 256, 0,
+            nv, groups, w.V, w.I);
     return MD_OK;
 }
 
@@ -750,7 +786,7 @@ extern "C" int mustdrop_prefill_filter(
     if (!q_txt || !k || !v || !hidden || !hidden_out || !k_out || !v_out || !kept_index || !kept_count)
         return fail(MD_EINVAL, "prefill_filter: q_txt, k, v, hidden, the *_out tensors, kept_index and kept_count are required");
     if (d != 64 && d != 128) return fail(MD_ESHAPE, "prefill_filter: head dim %d not supported (64 or 128)", d);
-    if (N > 128) return fail(MD_ESHAPE, "prefill_filter: N=%d text tokens exceeds the limit of 128", N);
+    if (N > 1024) return fail(MD_ESHAPE, "prefill_filter: N=%d text tokens exceeds the limit of 1024", N);
     if (H > 128) return fail(MD_ESHAPE, "prefill_filter: H=%d heads exceeds the limit of 128", H);
     if ((long)B * (Mv + N) > (1l << 28)) return fail(MD_ESHAPE, "prefill_filter: too many tokens");
     if (C % 8) return fail(MD_EALIGN, "prefill_filter: a hidden row of C=%d bf16 is not a multiple of 16 bytes", C);
@@ -790,19 +826,8 @@ extern "C" int mustdrop_prefill_filter(
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float sl2 = softmax_scale * kLog2e;
 
-    int rc = MD_OK;
-    const int NB = p.Npad / 32;
-    if (d == 128) {
-        if (NB == 1) rc = launch_scores<1, 1, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 2) rc = launch_scores<2, 2, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 3) rc = launch_scores<2, 3, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else rc = launch_scores<2, 4, 8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-    } else {
-        if (NB == 1) rc = launch_scores<1, 1, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 2) rc = launch_scores<2, 2, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else if (NB == 3) rc = launch_scores<2, 3, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-        else rc = launch_scores<2, 4, 4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
-    }
+    int rc = d == 128 ? launch_scores<8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2)
+                      : launch_scores<4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
     if (rc != MD_OK) return rc;
     int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
 #define MD_PSELECT_FAST(IPT_)                                                                               \

@@ -92,7 +92,7 @@ def test_prefill_argument_errors(lib):
     assert prefill(lib, k=None) == 1
     assert prefill(lib, mode=3) == 6
     assert prefill(lib, d=96) == 2
-    assert prefill(lib, N=129) == 2
+    assert prefill(lib, N=1025) == 2
     assert prefill(lib, C=4100) == 3
     assert prefill(lib, budget=-1) == 1
     assert prefill(lib, gamma=0.0) == 1 and b"gamma" in lib.mustdrop_last_error()

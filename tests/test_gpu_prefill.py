@@ -77,6 +77,19 @@ def test_ragged_padding_and_odd_shapes():
     assert np.array_equal(g["kept_count"], vis_valid.sum(1))
 
 
+def test_long_prompts_more_than_128_text_rows():
+    # the column scores of a long prompt come from several launches (128 text rows each) that are merged
+    cfg = wl.tiny(wl.CONFIGS[2], B=2, Hg=9, Wg=13, N=300, H=4, d=128, C=64)
+    t = wl.prefill_inputs(cfg)
+    txt_len = np.array([300, 131], dtype=np.int32)
+    is_key = wl.random_key_mask(cfg, 7)
+    for R in (20, 60):
+        run(t, cfg.M, R, txt_len=txt_len, is_key=is_key)
+    run(t, cfg.M, 0, mode=FILTER_THRESHOLD, txt_len=txt_len, is_key=is_key, gamma=1.0 / cfg.M, alpha=1.5 / cfg.M)
+    cfg = wl.tiny(wl.CONFIGS[2], B=1, Hg=6, Wg=6, N=1024, H=2, d=64, C=64)
+    run(wl.prefill_inputs(cfg), cfg.M, 12)
+
+
 def test_threshold_mode_and_special_cases():
     cfg = wl.tiny(wl.CONFIGS[2], B=2, Hg=8, Wg=12, N=32, H=4, d=128, C=512)
     Mv = cfg.M
