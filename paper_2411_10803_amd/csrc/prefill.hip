@@ -152,21 +152,26 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     // text-query fragments of this head: through the same LDS tile, one 32-row block at a time
     // (all loads are issued before the first LDS pass: the fences below would otherwise serialise them)
     bf16x8 qf[NB][KS];
-    u32x4 sq[NB][KS];
+    constexpr int NST = NB < 2 ? NB : 2;             // text blocks staged at a time (32 registers each)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-        Tile::gload(qb, tok_stride, i_base + 32 * nb, tl, lane, sq[nb]);  // rows >= txt_len read as zero
+    for (int nb0 = 0; nb0 < NB; nb0 += NST) {
+        u32x4 sq[NST][KS];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        Tile::to_lds(tile, lane, sq[nb]);
-        wave_lds_sync();
-        Tile::frags(tile, lane, qf[nb]);
-        wave_lds_sync();
-        const int nbg = tg * NB + nb;                // 32-row block index within the padded text axis
-        if (ch == 0 && wv == 0 && nbg < p.Npad / 32) {
+        for (int e = 0; e < NST; ++e)
+            Tile::gload(qb, tok_stride, i_base + 32 * (nb0 + e), tl, lane, sq[e]);   // rows >= txt_len read as zero
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[nb][ks];
+        for (int e = 0; e < NST; ++e) {
+            const int nb = nb0 + e;
+            Tile::to_lds(tile, lane, sq[e]);
+            wave_lds_sync();
+            Tile::frags(tile, lane, qf[nb]);
+            wave_lds_sync();
+            const int nbg = tg * NB + nb;            // 32-row block index within the padded text axis
+            if (ch == 0 && wv == 0 && nbg < p.Npad / 32) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[nb][ks];
+            }
         }
     }
 
