@@ -16,6 +16,10 @@ namespace {
 
 constexpr float kLog2eE = 1.4426950408889634f;
 constexpr int kMaxWindow = 16;
+#ifndef MD_ENC_WAVES
+#define MD_ENC_WAVES 4
+#endif
+constexpr int kEncWaves = MD_ENC_WAVES;          // waves (= work items) per block of the wave-per-item kernels
 constexpr int kMaxClsHeads = 256;
 
 struct EncodeDims {
@@ -696,10 +700,10 @@ EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
 template <int WSM>
 void launch_scores(dim3 grid, hipStream_t st, bool xbf, bool qkbf, const void* x, const void* q_cls, const void* k_cls,
                    const uint8_t* valid, const EncodeDims& p, int with_cls, float* sim, float* logits) {
-    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
-    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
-    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
-    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false>), grid, 256, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
 }
 
 }  // namespace
@@ -770,14 +774,14 @@ extern "C" int mustdrop_encode_merge(
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     const long items = (long)B * W + (key_budget > 0 ? (long)B * cls_groups(M) : 0);
-    dim3 sgrid((unsigned)((items + 3) / 4));
+    dim3 sgrid((unsigned)((items + kEncWaves - 1) / kEncWaves));
     const bool xbf = x_dtype == MD_BF16, qkbf = qk_dtype == MD_BF16;
     const int with_cls = key_budget > 0;
     if (ws <= 2) launch_scores<2>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     else if (ws <= 4) launch_scores<4>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     else if (ws <= 8) launch_scores<8>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
-    dim3 wgrid((unsigned)(((long)B * W + 3) / 4));
+    dim3 wgrid((unsigned)(((long)B * W + kEncWaves - 1) / kEncWaves));
 #define MD_DECIDE_FAST(IPT_)                                                                                  \
     MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_>), B, 1024, 6 * (size_t)M,              \
         p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.wmerged, wsp.dstpos,                          \
@@ -791,7 +795,7 @@ extern "C" int mustdrop_encode_merge(
             p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
             out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out);
 #undef MD_DECIDE_FAST
-    if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true>), wgrid, 256, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
-    else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false>), wgrid, 256, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
+    if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true>), wgrid, 64 * kEncWaves, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
+    else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false>), wgrid, 64 * kEncWaves, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
     return check_launch("encode_merge");
 }
