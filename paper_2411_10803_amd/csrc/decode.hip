@@ -18,15 +18,6 @@ namespace {
 
 constexpr float kLog2eD = 1.4426950408889634f;
 
-#ifdef MD_TRACE   // debug builds only: phase timestamps of block 0 / thread 0
-}  // namespace
-__device__ unsigned long long g_trace[32];
-namespace {
-#define MD_STAMP(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_trace[i] = wall_clock64(); } while (0)
-#else
-#define MD_STAMP(i) do { } while (0)
-#endif
-
 struct DecodeDims { int B, Lcap, H, d; };
 constexpr int kMaxStatParts = 256;               // blocks per sample of the streaming logits kernel
 
@@ -234,7 +225,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         }
     }
     const int n = min(max(len[b], 0), p.Lcap);
-    MD_STAMP(0);
     if (n == 0) {
         if (tid == 0) { n_move[b] = 0; if (evicted_count) evicted_count[b] = 0; }
         return;
@@ -252,7 +242,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         id[t] = live[t] ? ib[j] : 0;
         prot[t] = live[t] ? pb[j] != 0 : false;
     }
-    MD_STAMP(1);
     // the lanes of a head finish the merge: group maximum, then the group sum of the rescaled sums
     {
         float gm = mn;
@@ -266,7 +255,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         if (sh < H && sq == 0) { s_cm[sh] = gm; s_cz[sh] = __frcp_rn(zs * (float)H); }
     }
     __syncthreads();
-    MD_STAMP(2);
     // a_t[j] = mean_h softmax; acc <- decay*acc + a_t.  A lane always works on the same four heads,
     // so their statistics sit in registers; LPE lanes add up an entry's heads and one of them drops
     // the result in LDS, from where the entry's owner picks it up (same wave: LDS keeps program order).
@@ -300,12 +288,10 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
             a_new[t] = live[t] ? fmaf(decay, a_old[t], s_at[j]) : 0.f;
         }
     }
-    MD_STAMP(3);
     int np = 0;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) np += prot[t];
     np = block_sum_i(np, s_red);
-    MD_STAMP(4);
 
     if (n <= budget) {                               // nothing leaves: only the scores change
 #pragma unroll
@@ -332,7 +318,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         if (mine == victim) s_vslot = mine_slot;     // keys are unique: one writer
         __syncthreads();
         const int vslot = s_vslot, last = n - 1;
-        MD_STAMP(5);
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
             const int j = tid + t * 1024;
@@ -348,7 +333,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
                 ab[j] = a_new[t];
             }
         }
-        MD_STAMP(7);
         if (tid == 0) {
             n_move[b] = vslot != last ? 1 : 0;
             len[b] = new_len;
@@ -362,7 +346,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
 #pragma unroll
     for (int t = 0; t < IPT; ++t)
         keep[t] = live[t] && (prot[t] || (extra > 0 && (key[t] >> sb.shift) >= sb.bound));
-    MD_STAMP(5);
     // hole / mover / evicted lists in ascending slot order: one pass of block scans per round of entries
     int run_h = 0, run_m = 0, run_e = 0;
     int mrank[IPT];
@@ -382,7 +365,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         if (is_ev && evicted_ids) evicted_ids[(long)b * p.Lcap + run_e + pre_e] = id[t];
         run_h += tot_hm & 0xFFFF; run_m += tot_hm >> 16; run_e += tot_e;
     }
-    MD_STAMP(6);
     __syncthreads();
     // write the scores back; a mover's state goes straight to its hole (no overlap: holes < new_len <= movers)
 #pragma unroll
@@ -399,7 +381,6 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
             ab[j] = a_new[t];
         }
     }
-    MD_STAMP(7);
     if (tid == 0) {
         n_move[b] = run_m;
         len[b] = new_len;
@@ -610,11 +591,6 @@ int check_decode_dims(const char* who, int B, int Lcap, int H, int d) {
 
 using namespace md;
 
-#ifdef MD_TRACE
-extern "C" int mustdrop_debug_trace(unsigned long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(md::g_trace), sizeof(unsigned long long) * 32);
-}
-#endif
 
 extern "C" size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H) {
     if (B <= 0 || Lcap <= 0 || H <= 0) return 0;

@@ -4,7 +4,7 @@
 // Launch plan (all on the caller's stream, no host synchronisation):
 //   encode_scores_kernel one launch, two kinds of waves:
 //       window waves     one wave per window: Gram matrix in registers -> S    (HBM: reads x once)
-//       key-row waves    one wave per key row: q_cls . k_j per head            (HBM: reads k_cls once)
+//       key-row waves    one wave per four key rows: q_cls . k_j per head      (HBM: reads k_cls once)
 //   encode_decide_kernel one block per sample: softmax + head mean, radix top-k -> O, merge
 //                        decisions, prefix sum of survivors, small outputs    (tiny)
 //   encode_emit_kernel  one wave per window: row copies / mass-weighted means (re-reads x, writes out_x)
