@@ -243,6 +243,43 @@ def progressive_prefill(torch, md, harness, cfg, pipe, iters=100):
             "vision_tokens_per_s": B * cfg.M / (total * 1e-3)}
 
 
+def static_handoff(torch, md, binding, cfg, layers=32, kept_vision=64, reps=10):
+    """Sec. 3.5 as printed, at the prefill -> decode hand-off: the caches of all layers keep only S_few
+    (here 64 seeded vision entries) and the text; one mustdrop_decode_keep call over 32 layers."""
+    B, M, N, H, d = cfg.B, cfg.M, cfg.N, cfg.H, cfg.d
+    Lcap = M + N
+    k = torch.empty((layers, B, Lcap, H, d), dtype=torch.bfloat16, device="cuda")      # contents are only moved
+    v = torch.empty_like(k)
+    rng = np.random.default_rng([cfg.seed, 31])
+    keep_np = np.zeros((B, Lcap), np.uint8)
+    keep_np[:, M:] = 1
+    for b in range(B):
+        keep_np[b, rng.choice(M, size=kept_vision, replace=False)] = 1
+    keep = torch.from_numpy(keep_np).cuda()
+    ids0 = torch.arange(Lcap, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+    len0 = torch.full((B,), Lcap, dtype=torch.int32, device="cuda")
+    ids, protect, length = ids0.clone(), keep.clone(), len0.clone()
+    ws = md.decode_workspace(B, Lcap, H)
+    new_len = kept_vision + N
+    moved = int((keep_np[:, new_len:] != 0).sum())                     # kept entries beyond the new length
+    md.mustdrop_decode_keep(k, v, keep, None, ids, protect, length, workspace=ws)       # warm-up
+    torch.cuda.synchronize()
+    assert int(length.min()) == new_len and int(length.max()) == new_len
+    binding.profile_start()
+    for _ in range(reps):
+        ids.copy_(ids0); protect.copy_(keep); length.copy_(len0)
+        md.mustdrop_decode_keep(k, v, keep, None, ids, protect, length, workspace=ws)
+    prof = binding.profile_stop()
+    torch.cuda.synchronize()
+    us = {n: r["ms"] * 1e3 / max(r["calls"], 1) for n, r in prof.items()}
+    move_bytes = 2 * moved * layers * 2 * H * d * 2                    # K and V rows, read + written
+    del k, v
+    return {"workload": cfg.name, "layers": layers, "entries": Lcap, "kept": new_len, "rows_moved_per_layer": moved,
+            "plan_us": round(us.get("decode_keep_plan", 0.0), 2), "move_us": round(us.get("decode_move", 0.0), 2),
+            "move_MB": round(move_bytes / 1e6, 1),
+            "move_GBps": round(move_bytes / (us.get("decode_move", 1e9) * 1e-6) / 1e9, 1)}
+
+
 def cpu_baseline(cfg, pipe, min_seconds=10.0):
     """The oracle, as it stands, on this host: the same chained step on the full batch of 16."""
     import oracle
@@ -311,7 +348,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
-    ap.add_argument("--no-progressive", action="store_true")
+    ap.add_argument("--no-progressive", action="store_true", help="skip the chained-prefill and hand-off extras")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) to scale rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -393,6 +430,8 @@ def main():
         result["decode_loop"] = decode_loop_cfg5(torch, md, harness, args.decode_steps)
     if not args.no_progressive:
         result["progressive_prefill"] = progressive_prefill(torch, md, harness, cfg, pipe)
+    if not args.no_progressive:
+        result["static_handoff"] = static_handoff(torch, md, binding, cfg)
     if not args.no_parity:
         result["parity"] = parity_check(cfg, pipe, harness)
     if not args.no_cpu_baseline:

@@ -184,6 +184,29 @@ int mustdrop_decode_append(
     int B, int Lcap, int H, int d, int32_t new_id, int protect_new, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Stage 3, the static policy as printed (Sec. 3.5): from the shallow layers on, the caches store only
+ * the vision tokens of the set S_few (besides the text and what was generated) -- nothing is scored.
+ * keep[b][j] != 0 marks the entries j < len[b] that stay.  The caches of all n_layers layers are
+ * compacted in one call by the hole filling of mustdrop_decode_evict (the kept entries at slots
+ * >= new_len move, in ascending order, into the dropped slots < new_len, in ascending order), so every
+ * layer holds the same entry in the same slot and ids / protect / acc describe all of them.
+ *
+ *   k_cache, v_cache [n_layers, B, Lcap, H, d] bf16, in/out (device)
+ *   keep     [B, Lcap] u8, read only (entries >= len[b] are ignored)
+ *   acc      [B, Lcap] f32 in/out, or NULL;  ids [B, Lcap] i32, protect [B, Lcap] u8, len [B] i32: in/out
+ *   evicted_ids [B, Lcap] or NULL: ids of the dropped entries in ascending slot order;
+ *   evicted_count [B] or NULL
+ *   workspace: mustdrop_decode_evict_workspace_bytes(B, Lcap, H) bytes, 256-byte aligned
+ * Limits and errors as for mustdrop_decode_evict; n_layers in [1, 65535].
+ */
+int mustdrop_decode_keep(
+    void* k_cache, void* v_cache, const uint8_t* keep,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int n_layers, int B, int Lcap, int H, int d,
+    int32_t* evicted_ids, int32_t* evicted_count,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Benchmarking aid (not part of the method): per-kernel timing with HIP events.
  * Between mustdrop_profile_start() and mustdrop_profile_stop() every kernel the library launches
  * carries an event pair that receives the begin and end timestamps of that dispatch on its stream

@@ -136,3 +136,21 @@ def decode_evict(q, k_cache, v_cache, acc, ids, protect, length, softmax_scale, 
     if rc != 0:
         raise ValueError(f"mustdrop_decode_evict_ref: error {rc}")
     return out
+
+
+def decode_keep(k_caches, v_caches, keep, acc, ids, protect, length):
+    """Sec. 3.5, the static policy: only the entries flagged in ``keep`` stay in the caches of all layers.
+    State arrays are updated IN PLACE.  k_caches, v_caches [n_layers,B,Lcap,H,d] (bf16 bits); keep u8, ids i32,
+    protect u8 [B,Lcap]; acc f32 [B,Lcap] or None; length i32 [B]."""
+    n_layers, B, Lcap, H, d = k_caches.shape
+    out = {
+        "evicted_ids": np.full((B, Lcap), -1, dtype=np.int32),
+        "evicted_count": np.zeros((B,), dtype=np.int32),
+    }
+    rc = lib().mustdrop_decode_keep_ref(
+        _p(k_caches), _p(v_caches), _p(keep), _p(acc), _p(ids), _p(protect), _p(length),
+        C.c_int(n_layers), C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d),
+        _p(out["evicted_ids"]), _p(out["evicted_count"]))
+    if rc != 0:
+        raise ValueError(f"mustdrop_decode_keep_ref: error {rc}")
+    return out

@@ -464,3 +464,58 @@ int mustdrop_decode_evict_ref(
     free(a_t); free(lg); free(keep); free(order);
     return REF_OK;
 }
+
+/* =========================================================================
+ * Stage 3, the static policy as printed (Sec. 3.5): from the shallow layers on,
+ * the caches store only the vision tokens of the set S_few (and what is not a
+ * vision token).  keep[b][j] != 0 marks the entries j < len[b] that stay; the
+ * caches of all n_layers layers, [n_layers][B][Lcap][H][d], are compacted by
+ * the hole filling of the per-step policy above, so every layer keeps the same
+ * entry in the same slot.
+ * ========================================================================= */
+int mustdrop_decode_keep_ref(
+    uint16_t* k_cache, uint16_t* v_cache, const uint8_t* keep_in,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int n_layers, int B, int Lcap, int H, int d,
+    int32_t* evicted_ids, int32_t* evicted_count)
+{
+    if (n_layers <= 0 || B <= 0 || Lcap <= 0 || H <= 0 || d <= 0 || !keep_in) return REF_EINVAL;
+    const size_t row = (size_t)H * d;
+    const size_t layer = (size_t)B * Lcap * row;
+    uint8_t* keep = (uint8_t*)malloc((size_t)Lcap);
+    for (int b = 0; b < B; ++b) {
+        const int n = len[b];
+        if (n < 0 || n > Lcap) { free(keep); return REF_EINVAL; }
+        float* ab = acc ? acc + (size_t)b * Lcap : NULL;
+        int32_t* ib = ids + (size_t)b * Lcap;
+        uint8_t* pb = protect + (size_t)b * Lcap;
+        int new_len = 0, n_ev = 0;
+        for (int j = 0; j < n; ++j) {
+            keep[j] = keep_in[(size_t)b * Lcap + j] != 0;
+            new_len += keep[j];
+        }
+        for (int j = 0; j < n; ++j)
+            if (!keep[j]) {
+                if (evicted_ids) evicted_ids[(size_t)b * Lcap + n_ev] = ib[j];
+                ++n_ev;
+            }
+        int hole = 0;
+        for (int src = new_len; src < n; ++src) {
+            if (!keep[src]) continue;
+            while (keep[hole]) ++hole;
+            for (int l = 0; l < n_layers; ++l) {
+                uint16_t* kb = k_cache + l * layer + (size_t)b * Lcap * row;
+                uint16_t* vb = v_cache + l * layer + (size_t)b * Lcap * row;
+                memcpy(kb + (size_t)hole * row, kb + (size_t)src * row, row * 2);
+                memcpy(vb + (size_t)hole * row, vb + (size_t)src * row, row * 2);
+            }
+            if (ab) ab[hole] = ab[src];
+            ib[hole] = ib[src]; pb[hole] = pb[src];
+            keep[hole] = 1;
+        }
+        len[b] = new_len;
+        if (evicted_count) evicted_count[b] = n_ev;
+    }
+    free(keep);
+    return REF_OK;
+}

@@ -17,7 +17,7 @@ EXPORTS = [
     "mustdrop_last_error", "mustdrop_version",
     "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge",
     "mustdrop_prefill_filter_workspace_bytes", "mustdrop_prefill_filter",
-    "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append",
+    "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append", "mustdrop_decode_keep",
     "mustdrop_profile_start", "mustdrop_profile_stop",
 ]
 
@@ -45,7 +45,8 @@ def library() -> C.CDLL:
         for n in ("mustdrop_encode_merge_workspace_bytes", "mustdrop_prefill_filter_workspace_bytes",
                   "mustdrop_decode_evict_workspace_bytes"):
             getattr(lib, n).restype = C.c_size_t
-        for n in ("mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append"):
+        for n in ("mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
+                  "mustdrop_decode_keep"):
             getattr(lib, n).restype = C.c_int
         _lib = lib
     return _lib
@@ -200,6 +201,21 @@ def mustdrop_decode_append(k_new, v_new, k_cache, v_cache, acc, ids, protect, le
         _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
         C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d), C.c_int(int(new_id)), C.c_int(int(protect_new)),
         _stream(stream)))
+
+
+def mustdrop_decode_keep(k_caches, v_caches, keep, acc, ids, protect, length, evicted_ids=None, evicted_count=None,
+                         workspace=None, stream=None):
+    """Sec. 3.5, the static policy: only the entries flagged in ``keep`` stay, in the caches of all layers
+    (k_caches, v_caches [n_layers,B,Lcap,H,d]); the state is updated in place.  Returns the workspace used."""
+    n_layers, B, Lcap, H, d = k_caches.shape
+    if workspace is None:
+        workspace = decode_workspace(B, Lcap, H, k_caches.device)
+    _check(library().mustdrop_decode_keep(
+        _ptr(k_caches), _ptr(v_caches), _ptr(keep), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
+        C.c_int(n_layers), C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d),
+        _ptr(evicted_ids), _ptr(evicted_count),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return workspace
 
 
 def profile_start():

@@ -505,14 +505,71 @@ __global__ __launch_bounds__(1024) void decode_select_kernel(
     }
 }
 
-// Row moves: block (g, b) copies movers[t] -> holes[t] for t = g, g + gridDim.x, ...
+// The static policy (Sec. 3.5): the entries to keep are given, nothing is scored.  One block per
+// sample turns the keep flags into the same hole / mover lists as the selection kernels and moves the
+// small per-entry arrays; the row moves then run over every layer's cache.
+__global__ __launch_bounds__(1024) void decode_keep_plan_kernel(
+    DecodeDims p, const uint8_t* __restrict__ keep, float* __restrict__ acc, int32_t* __restrict__ ids,
+    uint8_t* __restrict__ protect, int32_t* __restrict__ len,
+    int32_t* __restrict__ holes, int32_t* __restrict__ movers, int32_t* __restrict__ n_move,
+    int32_t* __restrict__ evicted_ids, int32_t* __restrict__ evicted_count)
+{
+    __shared__ int s_red[16];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n = min(max(len[b], 0), p.Lcap);
+    const uint8_t* kf = keep + (long)b * p.Lcap;
+    float* ab = acc ? acc + (long)b * p.Lcap : nullptr;
+    int32_t* ib = ids + (long)b * p.Lcap;
+    uint8_t* pb = protect + (long)b * p.Lcap;
+    int32_t* hb = holes + (long)b * p.Lcap;
+    int32_t* mvb = movers + (long)b * p.Lcap;
+
+    int nk = 0;
+    for (int j = tid; j < n; j += blockDim.x) nk += kf[j] != 0;
+    const int new_len = block_sum_i(nk, s_red);
+    // hole / mover / evicted lists (ascending slot order by construction of the scan)
+    int run_h = 0, run_m = 0, run_e = 0;
+    for (int base = 0; base < n; base += blockDim.x) {
+        const int j = base + tid;
+        const bool kp = j < n && kf[j] != 0;
+        const bool is_hole = j < new_len && !kp;
+        const bool is_mover = j >= new_len && j < n && kp;
+        const bool is_ev = j < n && !kp;
+        int th, tm, te;
+        const int rh = block_rank(is_hole, s_red, th);
+        const int rm = block_rank(is_mover, s_red, tm);
+        const int re = block_rank(is_ev, s_red, te);
+        if (is_hole) hb[run_h + rh] = j;
+        if (is_mover) mvb[run_m + rm] = j;
+        if (is_ev && evicted_ids) evicted_ids[(long)b * p.Lcap + run_e + re] = ib[j];
+        run_h += th; run_m += tm; run_e += te;
+    }
+    __syncthreads();
+    // move the small per-entry arrays (sources >= new_len, destinations < new_len: no overlap)
+    for (int t = tid; t < run_m; t += blockDim.x) {
+        const int src = mvb[t], dst = hb[t];
+        if (ab) ab[dst] = ab[src];
+        ib[dst] = ib[src];
+        pb[dst] = pb[src];
+    }
+    if (tid == 0) {
+        n_move[b] = run_m;
+        len[b] = new_len;
+        if (evicted_count) evicted_count[b] = run_e;
+    }
+}
+
+// Row moves: block (g, b, layer) copies movers[t] -> holes[t] for t = g, g + gridDim.x, ... in the
+// cache of its layer (layer_stride 16-byte vectors apart; one layer for the per-step policy).
 __global__ __launch_bounds__(256) void decode_move_kernel(
     DecodeDims p, const int32_t* __restrict__ holes, const int32_t* __restrict__ movers,
-    const int32_t* __restrict__ n_move, u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache)
+    const int32_t* __restrict__ n_move, u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, long layer_stride)
 {
     const int b = blockIdx.y;
     const int nm = n_move[b];
     const int rv = p.H * p.d / 8;
+    k_cache += blockIdx.z * layer_stride;
+    v_cache += blockIdx.z * layer_stride;
     // source rows (beyond the new length) and destination rows (holes below it) never coincide, but
     // the compiler cannot know: the vectors of a round are read into registers before any is written
     for (int t = blockIdx.x; t < nm; t += gridDim.x) {
@@ -688,8 +745,41 @@ extern "C" int mustdrop_decode_evict(
     }
     dim3 g3(32, B);
     MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
-        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache));
+        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), 0l);
     return check_launch("decode_evict");
+}
+
+extern "C" int mustdrop_decode_keep(
+    void* k_cache, void* v_cache, const uint8_t* keep,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int n_layers, int B, int Lcap, int H, int d,
+    int32_t* evicted_ids, int32_t* evicted_count,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    clear_error();
+    int rc = check_decode_dims("decode_keep", B, Lcap, H, d);
+    if (rc != MD_OK) return rc;
+    if (n_layers <= 0 || n_layers > 65535) return fail(MD_EINVAL, "decode_keep: n_layers=%d out of range", n_layers);
+    if (!k_cache || !v_cache || !keep || !ids || !protect || !len)
+        return fail(MD_EINVAL, "decode_keep: null pointer among the required arguments");
+    if ((H * d * 2) % 16) return fail(MD_EALIGN, "decode_keep: a row of H*d=%d bf16 is not a multiple of 16 bytes", H * d);
+    if (!aligned16(k_cache) || !aligned16(v_cache)) return fail(MD_EALIGN, "decode_keep: caches must be 16-byte aligned");
+    const size_t cache_bytes = (size_t)n_layers * B * Lcap * H * d * 2;
+    if (overlaps(k_cache, cache_bytes, v_cache, cache_bytes)) return fail(MD_EALIAS, "decode_keep: k_cache overlaps v_cache");
+    const DecodeWorkspace w = carve_decode(workspace, B, Lcap, H);
+    if (!workspace || workspace_bytes < w.bytes)
+        return fail(MD_EWORKSPACE, "decode_keep: workspace of %zu bytes needed, %zu given", w.bytes, workspace ? workspace_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(MD_EALIGN, "decode_keep: workspace must be 256-byte aligned");
+
+    DecodeDims p{B, Lcap, H, d};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MD_LAUNCH("decode_keep_plan", st, (decode_keep_plan_kernel), B, 1024, 0,
+        p, keep, acc, ids, protect, len, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
+    dim3 g3(32, B, n_layers);
+    MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
+        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
+        (long)B * Lcap * (H * d / 8));
+    return check_launch("decode_keep");
 }
 
 extern "C" int mustdrop_decode_append(

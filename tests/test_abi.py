@@ -122,3 +122,19 @@ def test_decode_argument_errors(lib):
     assert rc == 1
     rc = lib.mustdrop_decode_append(X, X, X, X, X, X, X, X, 2, 64, 32, 128, -1, 1, None)
     assert rc == 1
+
+
+def test_decode_keep_argument_errors(lib):
+    def keep(**kw):
+        a = dict(k=P(0x10000000), v=P(0x80000000), keep=X, layers=4, B=2, Lcap=640, H=32, d=128, ws=P(0x100000000),
+                 wsb=1 << 30)
+        a.update(kw)
+        return lib.mustdrop_decode_keep(a["k"], a["v"], a["keep"], None, X, X, X, a["layers"], a["B"], a["Lcap"], a["H"],
+                                        a["d"], None, None, a["ws"], C.c_size_t(a["wsb"]), None)
+    assert keep(keep=None) == 1
+    assert keep(layers=0) == 1
+    assert keep(d=96) == 2
+    assert keep(v=P(0x10000000)) == 4
+    assert keep(v=P(0x10000000 + 3 * 2 * 640 * 32 * 128 * 2)) == 4     # overlaps the fourth layer of k
+    assert keep(wsb=0) == 5
+    assert keep(k=P(0x10000008)) == 3

@@ -124,3 +124,43 @@ def test_determinism():
     for r in runs[1:]:
         for name in ("k", "v", "acc", "ids", "protect", "len", "evicted_ids"):
             assert np.array_equal(runs[0][name], r[name]), name
+
+
+@pytest.mark.parametrize("n_layers,B,Lcap,H,d,seed", [(4, 3, 700, 32, 128, 1), (2, 2, 2500, 5, 64, 2), (1, 1, 9, 1, 8, 3)])
+def test_static_policy_over_layers(n_layers, B, Lcap, H, d, seed):
+    """Sec. 3.5 as printed: keep the flagged entries in the caches of all layers (no scoring).  Integer and
+    byte work only: everything must match the oracle bit for bit."""
+    import torch
+    import paper_2411_10803_amd as md
+    from paper_2411_10803_amd import harness
+    rng = np.random.default_rng(seed)
+    k = rng.integers(0, 1 << 16, size=(n_layers, B, Lcap, H, d), dtype=np.uint16) & np.uint16(0xBFFF)
+    v = rng.integers(0, 1 << 16, size=(n_layers, B, Lcap, H, d), dtype=np.uint16) & np.uint16(0xBFFF)
+    acc = rng.random((B, Lcap)).astype(np.float32)
+    ids = np.stack([rng.permutation(4 * Lcap)[:Lcap] for _ in range(B)]).astype(np.int32)
+    protect = (rng.random((B, Lcap)) < 0.3).astype(np.uint8)
+    lens = rng.integers(0, Lcap + 1, size=B).astype(np.int32)
+    lens[0] = Lcap
+    keep = (rng.random((B, Lcap)) < rng.random((B, 1))).astype(np.uint8)
+    for with_acc in (True, False):
+        ko, vo, ao, io, po, lo = k.copy(), v.copy(), acc.copy(), ids.copy(), protect.copy(), lens.copy()
+        o = oracle.decode_keep(ko, vo, keep, ao if with_acc else None, io, po, lo)
+        kd, vd = harness.to_dev(k, True), harness.to_dev(v, True)
+        ad, idd, pd, ld = (harness.to_dev(a) for a in (acc, ids, protect, lens))
+        ev = torch.full((B, Lcap), -1, dtype=torch.int32, device="cuda")
+        evc = torch.zeros((B,), dtype=torch.int32, device="cuda")
+        md.mustdrop_decode_keep(kd, vd, harness.to_dev(keep), ad if with_acc else None, idd, pd, ld, ev, evc)
+        torch.cuda.synchronize()
+        assert np.array_equal(harness.to_host(ld), lo)
+        assert np.array_equal(harness.to_host(evc), o["evicted_count"])
+        kg, vg = harness.to_host(kd), harness.to_host(vd)
+        for b in range(B):
+            n, ne = int(lo[b]), int(o["evicted_count"][b])
+            for l in range(n_layers):
+                assert np.array_equal(kg[l, b, :n], ko[l, b, :n]) and np.array_equal(vg[l, b, :n], vo[l, b, :n])
+                assert np.array_equal(kg[l, b, lens[b]:], k[l, b, lens[b]:])          # beyond the old length: untouched
+            assert np.array_equal(harness.to_host(idd)[b, :n], io[b, :n])
+            assert np.array_equal(harness.to_host(pd)[b, :n], po[b, :n])
+            if with_acc:
+                assert np.array_equal(harness.to_host(ad)[b, :n], ao[b, :n])
+            assert np.array_equal(harness.to_host(ev)[b, :ne], o["evicted_ids"][b, :ne])

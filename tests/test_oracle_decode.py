@@ -151,3 +151,68 @@ def test_length_rule():
         s = state(seed=6, L=L, n_protect=n_protect)
         step(s, budget=budget)
         assert np.all(s["len"] == min(L, max(budget, n_protect)))
+
+
+def _random_state(rng, n_layers, B, Lcap, H, d, lens):
+    k = rng.integers(0, 1 << 16, size=(n_layers, B, Lcap, H, d), dtype=np.uint16) & np.uint16(0xBFFF)
+    v = rng.integers(0, 1 << 16, size=(n_layers, B, Lcap, H, d), dtype=np.uint16) & np.uint16(0xBFFF)
+    acc = rng.random((B, Lcap)).astype(np.float32)
+    ids = np.stack([rng.permutation(10 * Lcap)[:Lcap] for _ in range(B)]).astype(np.int32)
+    protect = (rng.random((B, Lcap)) < 0.3).astype(np.uint8)
+    return k, v, acc, ids, protect, np.array(lens, dtype=np.int32)
+
+
+def test_static_policy_over_layers_brute_force_and_invariants():
+    """Sec. 3.5 as printed: only the flagged entries stay, in every layer's cache.  Checked against a direct
+    Python construction of the hole-filling layout and against the invariants that define it."""
+    rng = np.random.default_rng(11)
+    n_layers, B, Lcap, H, d = 3, 4, 23, 2, 8
+    k, v, acc, ids, protect, lens = _random_state(rng, n_layers, B, Lcap, H, d, [23, 17, 1, 0])
+    keep = (rng.random((B, Lcap)) < 0.4).astype(np.uint8)
+    keep[2, 0] = 0                                   # a sample that loses everything
+    k0, v0, acc0, ids0, prot0 = k.copy(), v.copy(), acc.copy(), ids.copy(), protect.copy()
+    out = oracle.decode_keep(k, v, keep, acc, ids, protect, lens)
+    for b, n in enumerate([23, 17, 1, 0]):
+        kept = [j for j in range(n) if keep[b, j]]
+        dropped = [j for j in range(n) if not keep[b, j]]
+        new_len = len(kept)
+        assert lens[b] == new_len
+        # slot -> source: kept entries below new_len stay; holes take the kept entries beyond, both ascending
+        holes = [j for j in dropped if j < new_len]
+        movers = [j for j in kept if j >= new_len]
+        assert len(holes) == len(movers)
+        src = list(range(new_len))
+        for h_, m_ in zip(holes, movers):
+            src[h_] = m_
+        assert sorted(src) == kept                   # the live set is exactly the kept set
+        for l in range(n_layers):
+            assert np.array_equal(k[l, b, :new_len], k0[l, b, src])
+            assert np.array_equal(v[l, b, :new_len], v0[l, b, src])
+            assert np.array_equal(k[l, b, n:], k0[l, b, n:])             # beyond the old length: untouched
+        assert np.array_equal(ids[b, :new_len], ids0[b, src])
+        assert np.array_equal(protect[b, :new_len], prot0[b, src])
+        assert np.array_equal(acc[b, :new_len], acc0[b, src])
+        assert out["evicted_count"][b] == len(dropped)
+        assert out["evicted_ids"][b, :len(dropped)].tolist() == ids0[b, dropped].tolist()
+
+
+def test_static_policy_equals_the_per_step_policy_with_the_kept_set_protected():
+    """The printed policy is the special case of the scored one in which the kept set is the protected set
+    and the budget is its size: both oracle functions must then leave the same cache (one layer)."""
+    rng = np.random.default_rng(12)
+    B, Lcap, H, d = 3, 40, 2, 16
+    k, v, acc, ids, _, lens = _random_state(rng, 1, B, Lcap, H, d, [40, 33, 12])
+    keep = (rng.random((B, Lcap)) < 0.5).astype(np.uint8)
+    q = wl.f32_to_bf16_bits(rng.standard_normal((B, H, d)).astype(np.float32))
+    budget = 3                                       # below every sample's kept count: only the protected stay
+    assert min(int(keep[b, :lens[b]].sum()) for b in range(B)) >= budget
+    s1 = {"k": k[0].copy(), "v": v[0].copy(), "acc": acc.copy(), "ids": ids.copy(), "protect": keep.copy(), "len": lens.copy()}
+    oracle.decode_evict(q, s1["k"], s1["v"], s1["acc"], s1["ids"], s1["protect"], s1["len"], 0.25, 1.0, budget)
+    k2, v2, ids2, prot2, len2 = k.copy(), v.copy(), ids.copy(), keep.copy(), lens.copy()
+    oracle.decode_keep(k2, v2, keep, None, ids2, prot2, len2)
+    assert np.array_equal(s1["len"], len2)
+    for b in range(B):
+        n = len2[b]
+        assert np.array_equal(s1["k"][b, :n], k2[0, b, :n]) and np.array_equal(s1["v"][b, :n], v2[0, b, :n])
+        assert np.array_equal(s1["ids"][b, :n], ids2[b, :n])
+        assert np.all(prot2[b, :n] == 1)
