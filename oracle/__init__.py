@@ -85,6 +85,40 @@ def encode_merge(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid,
     return out
 
 
+def encode_merge_adaptive(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid,
+                          T, Hg, Wg, kt, kh, kw, tau, key_lambda, key_cap) -> Dict[str, np.ndarray]:
+    """Sec. 3.3 with Eq. 7 as printed: O = {a_cls > mu}, mu = mean + key_lambda * std of a_cls over the valid
+    tokens.  key_index holds the first key_cap keys (ascending), key_count the size of O."""
+    B, M, D = x.shape
+    assert M == T * Hg * Wg
+    Hc, dc = q_cls.shape[1], q_cls.shape[2]
+    W = (T // kt) * (Hg // kh) * (Wg // kw)
+    out = {
+        "out_x": np.zeros((B, M, D), dtype=_stored_dtype(x_dtype)),
+        "out_index": np.full((B, M), -1, dtype=np.int32),
+        "out_mass": np.zeros((B, M), dtype=np.float32),
+        "out_is_key": np.zeros((B, M), dtype=np.uint8),
+        "out_valid": np.zeros((B, M), dtype=np.uint8),
+        "out_count": np.zeros((B,), dtype=np.int32),
+        "key_index": np.full((B, max(key_cap, 1)), -1, dtype=np.int32),
+        "key_count": np.zeros((B,), dtype=np.int32),
+        "a_cls": np.zeros((B, M), dtype=np.float64),
+        "window_sim": np.zeros((B, W), dtype=np.float64),
+    }
+    rc = lib().mustdrop_encode_merge_adaptive_ref(
+        _p(x), C.c_int(x_dtype), _p(q_cls), _p(k_cls), C.c_int(qk_dtype), _p(mass_in), _p(valid),
+        C.c_int(B), C.c_int(T), C.c_int(Hg), C.c_int(Wg), C.c_int(D), C.c_int(Hc), C.c_int(dc),
+        C.c_int(kt), C.c_int(kh), C.c_int(kw), C.c_float(tau), C.c_float(key_lambda), C.c_int(key_cap),
+        _p(out["out_x"]), _p(out["out_index"]), _p(out["out_mass"]), _p(out["out_is_key"]),
+        _p(out["out_valid"]), _p(out["out_count"]), _p(out["key_index"]), _p(out["key_count"]),
+        _p(out["a_cls"]), _p(out["window_sim"]))
+    if rc != 0:
+        raise ValueError(f"mustdrop_encode_merge_adaptive_ref: error {rc}")
+    if key_cap == 0:
+        out["key_index"] = np.zeros((B, 0), dtype=np.int32)
+    return out
+
+
 def prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_scale, mode, budget,
                    gamma, alpha, Rcap=None) -> Dict[str, np.ndarray]:
     """Sec. 3.4 (Eq. 8-10) + token drop.  q_txt [B,N,H,d]; k, v [B,L,H,d]; hidden [B,L,C] (bf16 bits)."""

@@ -84,21 +84,27 @@ static int ranked_cmp(const void* a, const void* b) {
  * Stage 1 -- Sec. 3.3: Local Spatial Merging (Eq. 5) and Key Retaining
  * (Eq. 6-7, budget form).
  * ========================================================================= */
-int mustdrop_encode_merge_ref(
+/* key_mode 0: Eq. 7 in its budget form (the key_budget largest a_cls).  key_mode 1: Eq. 7 as printed,
+ * O = { a_cls > mu }, with the adaptive threshold read as mu = mean + key_lambda * std of a_cls over the
+ * valid tokens (population std); key_budget is then the capacity of key_index per sample and
+ * key_count[b] = |O|. */
+static int encode_merge_core(
     const void* x, int x_dtype,
     const void* q_cls, const void* k_cls, int qk_dtype,
     const float* mass_in, const uint8_t* valid,
     int B, int T, int Hg, int Wg, int D, int Hc, int dc,
-    int kt, int kh, int kw, float tau, int key_budget,
+    int kt, int kh, int kw, float tau, int key_mode, int key_budget, float key_lambda,
     void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key,
-    uint8_t* out_valid, int32_t* out_count, int32_t* key_index,
+    uint8_t* out_valid, int32_t* out_count, int32_t* key_index, int32_t* key_count,
     double* a_cls_out, double* window_sim_out)
 {
     if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || D <= 0) return REF_EINVAL;
     if (kt <= 0 || kh <= 0 || kw <= 0 || T % kt || Hg % kh || Wg % kw) return REF_EINVAL;
     const int M = T * Hg * Wg;
-    if (key_budget < 0 || key_budget > M) return REF_EINVAL;
-    if (key_budget > 0 && (!q_cls || !k_cls || Hc <= 0 || dc <= 0)) return REF_EINVAL;
+    if (key_budget < 0 || (key_mode == 0 && key_budget > M)) return REF_EINVAL;
+    const int with_keys = key_mode == 1 || key_budget > 0;
+    if (with_keys && (!q_cls || !k_cls || Hc <= 0 || dc <= 0)) return REF_EINVAL;
+    if (key_mode == 1 && !key_count) return REF_EINVAL;
     const int ws = kt * kh * kw;
     const int nwt = T / kt, nwy = Hg / kh, nwx = Wg / kw;
     const int W = nwt * nwy * nwx;
@@ -120,7 +126,7 @@ int mustdrop_encode_merge_ref(
         /* ---- Key Retaining: a_cls = softmax(q_cls K^T / sqrt(d_k)) per head, head mean (Eq. 6) */
         memset(is_key, 0, (size_t)M);
         for (int j = 0; j < M; ++j) a_cls[j] = 0.0;
-        if (key_budget > 0) {
+        if (with_keys) {
             for (int h = 0; h < Hc; ++h) {
                 /* key 0 is the CLS key itself and always takes part in the softmax */
                 double mx = -INFINITY;
@@ -141,19 +147,35 @@ int mustdrop_encode_merge_ref(
                 for (int j = 1; j <= M; ++j)
                     if (logit[j] != -INFINITY) a_cls[j - 1] += exp(logit[j] - mx) / z / (double)Hc;
             }
-            /* ---- key set O: the key_budget valid tokens with the largest a_cls (Eq. 7, budget form) */
             int nv = 0;
             for (int j = 0; j < M; ++j) {
                 if (vb && !vb[j]) { a_cls[j] = -INFINITY; continue; }
                 order[nv].score = a_cls[j]; order[nv].tie = j; order[nv].slot = j; ++nv;
             }
-            qsort(order, (size_t)nv, sizeof(ranked_t), ranked_cmp);
-            int nk = key_budget < nv ? key_budget : nv;
-            for (int r = 0; r < nk; ++r) is_key[order[r].slot] = 1;
-            int o = 0;
-            for (int j = 0; j < M; ++j) if (is_key[j]) key_index[(size_t)b * key_budget + o++] = j;
+            if (key_mode == 0) {
+                /* ---- key set O: the key_budget valid tokens with the largest a_cls (Eq. 7, budget form) */
+                qsort(order, (size_t)nv, sizeof(ranked_t), ranked_cmp);
+                int nk = key_budget < nv ? key_budget : nv;
+                for (int r = 0; r < nk; ++r) is_key[order[r].slot] = 1;
+            } else {
+                /* ---- key set O = { a_cls > mu } (Eq. 7), mu = mean + lambda * std over the valid tokens */
+                double mean_a = 0.0, var_a = 0.0;
+                for (int r = 0; r < nv; ++r) mean_a += order[r].score;
+                if (nv > 0) mean_a /= (double)nv;
+                for (int r = 0; r < nv; ++r) var_a += (order[r].score - mean_a) * (order[r].score - mean_a);
+                if (nv > 0) var_a /= (double)nv;
+                const double mu = mean_a + (double)key_lambda * sqrt(var_a);
+                for (int r = 0; r < nv; ++r) if (order[r].score > mu) is_key[order[r].slot] = 1;
+            }
+            int o = 0, total = 0;
+            for (int j = 0; j < M; ++j)
+                if (is_key[j]) {
+                    if (o < key_budget) key_index[(size_t)b * key_budget + o++] = j;
+                    ++total;
+                }
             for (; o < key_budget; ++o) key_index[(size_t)b * key_budget + o] = -1;
-        }
+            if (key_count) key_count[b] = total;
+        } else if (key_count) key_count[b] = 0;
         if (a_cls_out) for (int j = 0; j < M; ++j) a_cls_out[(size_t)b * M + j] = a_cls[j];
 
         /* ---- Local Spatial Merging: mean pairwise cosine inside each window (Eq. 5) */
@@ -238,6 +260,37 @@ int mustdrop_encode_merge_ref(
     free(a_cls); free(logit); free(is_key); free(merged_tok); free(rep_of);
     free(order); free(mem); free(mean); free(win_merged);
     return REF_OK;
+}
+
+int mustdrop_encode_merge_ref(
+    const void* x, int x_dtype,
+    const void* q_cls, const void* k_cls, int qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, int key_budget,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key,
+    uint8_t* out_valid, int32_t* out_count, int32_t* key_index,
+    double* a_cls_out, double* window_sim_out)
+{
+    return encode_merge_core(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, B, T, Hg, Wg, D, Hc, dc, kt, kh, kw,
+                             tau, 0, key_budget, 0.0f, out_x, out_index, out_mass, out_is_key, out_valid, out_count,
+                             key_index, NULL, a_cls_out, window_sim_out);
+}
+
+/* Eq. 7 as printed: O = { a_cls > mu }, mu = mean + key_lambda * std (see encode_merge_core). */
+int mustdrop_encode_merge_adaptive_ref(
+    const void* x, int x_dtype,
+    const void* q_cls, const void* k_cls, int qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, float key_lambda, int key_cap,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key,
+    uint8_t* out_valid, int32_t* out_count, int32_t* key_index, int32_t* key_count,
+    double* a_cls_out, double* window_sim_out)
+{
+    return encode_merge_core(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, B, T, Hg, Wg, D, Hc, dc, kt, kh, kw,
+                             tau, 1, key_cap, key_lambda, out_x, out_index, out_mass, out_is_key, out_valid, out_count,
+                             key_index, key_count, a_cls_out, window_sim_out);
 }
 
 /* =========================================================================

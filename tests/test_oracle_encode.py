@@ -370,3 +370,81 @@ def test_generator_bf16_rounding_matches_torch():
     ours = wl.f32_to_bf16_bits(a)
     ref = torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(ours, ref)
+
+
+# ------------------------------------------------------------------ Eq. 7 as printed: O = {a_cls > mu}
+def _adaptive_case():
+    cfg = wl.tiny(wl.CONFIGS[2], B=3, Hg=8, Wg=10, D=64, Hc=4, dc=16)
+    e = wl.encode_inputs(cfg)
+    rng = np.random.default_rng(21)
+    valid = (rng.random((cfg.B, cfg.M)) > 0.2).astype(np.uint8)
+    return cfg, e, valid
+
+
+def _adaptive(cfg, e, valid, lam, cap=None, tau=2.0):
+    return oracle.encode_merge_adaptive(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, valid,
+                                        cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, lam,
+                                        cfg.M if cap is None else cap)
+
+
+def test_adaptive_key_set_is_the_threshold_rule_on_an_independent_a_cls():
+    """O = {a_cls > mean + lambda * std}: the scores recomputed with numpy (einsum + softmax over the 1+M keys,
+    head mean), the threshold applied in numpy."""
+    cfg, e, valid = _adaptive_case()
+    lam = 0.7
+    o = _adaptive(cfg, e, valid, lam)
+    q = wl.to_f64(e["q_cls"], cfg.x_dtype)
+    k = wl.to_f64(e["k_cls"], cfg.x_dtype)
+    for b in range(cfg.B):
+        vb = valid[b].astype(bool)
+        logits = np.einsum("hc,jhc->hj", q[b], k[b]) / np.sqrt(cfg.dc)
+        logits[:, 1:][:, ~vb] = -np.inf
+        p = np.exp(logits - logits.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        a = p[:, 1:].mean(axis=0)
+        mu = a[vb].mean() + np.float64(np.float32(lam)) * a[vb].std()
+        want = np.flatnonzero(vb & (a > mu))
+        assert o["key_count"][b] == want.size and 0 < want.size < vb.sum()
+        assert o["key_index"][b, :want.size].tolist() == want.tolist()
+        assert np.all(o["key_index"][b, want.size:] == -1)
+
+
+def test_adaptive_key_set_limits_monotonicity_and_the_budget_form():
+    cfg, e, valid = _adaptive_case()
+    tau = 0.5                                        # low enough for many windows to merge when no key blocks them
+    none = _adaptive(cfg, e, valid, 1e6, tau=tau)    # threshold above every score: no keys
+    base = oracle.encode_merge(e["x"], cfg.x_dtype, None, None, cfg.x_dtype, None, valid, cfg.T, cfg.Hg, cfg.Wg,
+                               cfg.kt, cfg.kh, cfg.kw, tau, 0)
+    assert np.all(none["key_count"] == 0)
+    for name in ("out_count", "out_index", "out_mass", "out_is_key", "out_x"):
+        assert np.array_equal(none[name], base[name]), name
+    every = _adaptive(cfg, e, valid, -1e6, tau=tau)  # threshold below every score: every valid token is a key
+    assert np.array_equal(every["key_count"], valid.sum(1))
+    assert np.array_equal(every["out_count"], valid.sum(1))          # a window with a key never merges
+    prev = None
+    for lam in (-1.0, 0.0, 0.5, 1.0, 2.0):
+        o = _adaptive(cfg, e, valid, lam, tau=tau)
+        keys = [set(o["key_index"][b, :o["key_count"][b]].tolist()) for b in range(cfg.B)]
+        if prev is not None:
+            assert all(keys[b] <= prev[b] for b in range(cfg.B))     # a higher threshold keeps a subset
+        prev = keys
+        # with |O| = n the printed rule and the budget form (top-n) name the same set, and all else follows
+        for b in range(cfg.B):
+            n = int(o["key_count"][b])
+            eb = {kk: vv[b:b + 1] for kk, vv in e.items() if kk != "ell"}
+            ob = oracle.encode_merge(eb["x"], cfg.x_dtype, eb["q_cls"], eb["k_cls"], cfg.x_dtype, None, valid[b:b + 1],
+                                     cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, n) if n > 0 else None
+            if ob is not None:
+                assert ob["key_index"][0].tolist() == o["key_index"][b, :n].tolist()
+                assert ob["out_count"][0] == o["out_count"][b]
+                assert np.array_equal(ob["out_index"][0], o["out_index"][b])
+
+
+def test_adaptive_key_index_capacity():
+    cfg, e, valid = _adaptive_case()
+    full = _adaptive(cfg, e, valid, 0.0)
+    cap = 3
+    o = _adaptive(cfg, e, valid, 0.0, cap=cap)
+    assert np.array_equal(o["key_count"], full["key_count"]) and np.all(full["key_count"] > cap)
+    assert np.array_equal(o["key_index"], full["key_index"][:, :cap])
+    assert np.array_equal(o["out_index"], full["out_index"])         # the capacity limits the list, not the set
