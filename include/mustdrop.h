@@ -96,6 +96,23 @@ int mustdrop_encode_merge(
     float* a_cls_out, float* window_sim_out,
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* Stage 1 with the key set in the printed form of Eq. 7: O = { j : a_cls[j] > mu }.  The paper only says
+ * that mu is adaptive and depends on a_cls; this library reads it as mu = mean + key_lambda * std of
+ * a_cls over the valid tokens (population standard deviation, fp32).  Everything else is
+ * mustdrop_encode_merge.  key_cap >= 0 is the capacity of key_index per sample ([B, key_cap], may be
+ * NULL if 0): the first key_cap members of O in ascending order, the rest -1; key_count [B] (required)
+ * receives |O|, which may exceed key_cap.  q_cls and k_cls are always required. */
+int mustdrop_encode_merge_adaptive(
+    const void* x, md_dtype x_dtype,
+    const void* q_cls, const void* k_cls, md_dtype qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, float key_lambda, int key_cap,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
+    int32_t* out_count, int32_t* key_index, int32_t* key_count,
+    float* a_cls_out, float* window_sim_out,
+    void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Stage 2 -- prefill, one LLM layer (Sec. 3.4).  Sequence per sample: [vision 0..Mv-1 | text 0..N-1]
  * (Sec. 3.1, prefilling: X = {V_1..V_M, T_1..T_N}), L = Mv + N.

@@ -7,12 +7,13 @@ kernels.  There is no CPU fallback: if the library is missing, calls raise.
 from .binding import (  # noqa: F401
     BF16, F32, FILTER_BUDGET, FILTER_THRESHOLD, MustDropError,
     decode_workspace, encode_workspace, library, library_path, prefill_workspace,
-    mustdrop_decode_append, mustdrop_decode_evict, mustdrop_decode_keep, mustdrop_encode_merge, mustdrop_prefill_filter,
+    mustdrop_decode_append, mustdrop_decode_evict, mustdrop_decode_keep, mustdrop_encode_merge, mustdrop_encode_merge_adaptive,
+    mustdrop_prefill_filter,
 )
 
 __all__ = [
     "BF16", "F32", "FILTER_BUDGET", "FILTER_THRESHOLD", "MustDropError",
     "library", "library_path", "encode_workspace", "prefill_workspace", "decode_workspace",
     "mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
-    "mustdrop_decode_keep",
+    "mustdrop_decode_keep", "mustdrop_encode_merge_adaptive",
 ]

@@ -15,7 +15,7 @@ _lib = None
 
 EXPORTS = [
     "mustdrop_last_error", "mustdrop_version",
-    "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge",
+    "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge", "mustdrop_encode_merge_adaptive",
     "mustdrop_prefill_filter_workspace_bytes", "mustdrop_prefill_filter",
     "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append", "mustdrop_decode_keep",
     "mustdrop_profile_start", "mustdrop_profile_stop",
@@ -45,7 +45,7 @@ def library() -> C.CDLL:
         for n in ("mustdrop_encode_merge_workspace_bytes", "mustdrop_prefill_filter_workspace_bytes",
                   "mustdrop_decode_evict_workspace_bytes"):
             getattr(lib, n).restype = C.c_size_t
-        for n in ("mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
+        for n in ("mustdrop_encode_merge", "mustdrop_encode_merge_adaptive", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
                   "mustdrop_decode_keep"):
             getattr(lib, n).restype = C.c_int
         _lib = lib
@@ -135,6 +135,42 @@ def mustdrop_encode_merge(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, kt, kh, kw
         C.c_int(kt), C.c_int(kh), C.c_int(kw), C.c_float(tau), C.c_int(key_budget),
         _ptr(out["out_x"]), _ptr(out["out_index"]), _ptr(out["out_mass"]), _ptr(out["out_is_key"]),
         _ptr(out["out_valid"]), _ptr(out["out_count"]), _ptr(out["key_index"]),
+        _ptr(out.get("a_cls")), _ptr(out.get("window_sim")),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return out
+
+
+def mustdrop_encode_merge_adaptive(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, kt, kh, kw, tau, key_lambda, key_cap,
+                                   out: Optional[Dict] = None, workspace=None, stream=None, want_scores=True) -> Dict:
+    """Sec. 3.3 with Eq. 7 as printed: keys = {a_cls > mean + key_lambda * std}; key_index holds the first key_cap
+    of them, key_count their number."""
+    import torch
+    B, M, D = x.shape
+    dev = x.device
+    Hc, dc = q_cls.shape[1], q_cls.shape[2]
+    W = M // (kt * kh * kw)
+    if out is None:
+        out = {
+            "out_x": torch.zeros_like(x),
+            "out_index": torch.full((B, M), -1, dtype=torch.int32, device=dev),
+            "out_mass": torch.zeros((B, M), dtype=torch.float32, device=dev),
+            "out_is_key": torch.zeros((B, M), dtype=torch.uint8, device=dev),
+            "out_valid": torch.zeros((B, M), dtype=torch.uint8, device=dev),
+            "out_count": torch.zeros((B,), dtype=torch.int32, device=dev),
+            "key_index": torch.full((B, max(key_cap, 1)), -1, dtype=torch.int32, device=dev),
+            "key_count": torch.zeros((B,), dtype=torch.int32, device=dev),
+            "a_cls": torch.zeros((B, M), dtype=torch.float32, device=dev) if want_scores else None,
+            "window_sim": torch.zeros((B, max(W, 1)), dtype=torch.float32, device=dev) if want_scores else None,
+        }
+    if workspace is None:
+        workspace = encode_workspace(B, T, Hg, Wg, Hc, kt, kh, kw, dev)
+    out["workspace"] = workspace
+    _check(library().mustdrop_encode_merge_adaptive(
+        _ptr(x), C.c_int(_dtype_code(x)), _ptr(q_cls), _ptr(k_cls), C.c_int(_dtype_code(q_cls)), _ptr(mass_in), _ptr(valid),
+        C.c_int(B), C.c_int(T), C.c_int(Hg), C.c_int(Wg), C.c_int(D), C.c_int(Hc), C.c_int(dc),
+        C.c_int(kt), C.c_int(kh), C.c_int(kw), C.c_float(tau), C.c_float(key_lambda), C.c_int(key_cap),
+        _ptr(out["out_x"]), _ptr(out["out_index"]), _ptr(out["out_mass"]), _ptr(out["out_is_key"]),
+        _ptr(out["out_valid"]), _ptr(out["out_count"]), _ptr(out["key_index"]), _ptr(out["key_count"]),
         _ptr(out.get("a_cls")), _ptr(out.get("window_sim")),
         _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
     return out

@@ -270,6 +270,7 @@ __global__ __launch_bounds__(256) void encode_scores_kernel(
 __global__ __launch_bounds__(1024) void encode_decide_kernel(
     EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
     const float* __restrict__ logits, const float* __restrict__ sim, float tau, int key_budget,
+    int key_adaptive, float key_lambda, int32_t* __restrict__ key_count,
     float* __restrict__ acls, uint8_t* __restrict__ iskey, uint8_t* __restrict__ wmerged,
     int32_t* __restrict__ dstpos,
     int32_t* __restrict__ out_index, float* __restrict__ out_mass, uint8_t* __restrict__ out_is_key,
@@ -279,6 +280,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
     __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
     __shared__ int s_hist[256];
     __shared__ int s_red[16];
+    __shared__ float s_redf[16];
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
     const int M = p.M, W = p.W;
     const uint8_t* vb = valid ? valid + (size_t)b * M : nullptr;
@@ -289,7 +291,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
     int32_t* dst_b = dstpos + (size_t)b * M;
 
     // ---- Key Retaining
-    if (key_budget > 0) {
+    if (key_budget > 0 || key_adaptive) {
         const float* lg = logits + (size_t)b * p.Hc * (M + 1);
         for (int h = wv; h < p.Hc; h += nw) {
             const float* l = lg + (size_t)h * (M + 1);
@@ -318,19 +320,38 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
             ok = !vb || vb[i];
             return ok ? rank_key(acls_b[i], i) : 0ull;
         };
-        const SelectBound sb = block_radix_select(keyfn, M, key_budget, s_hist);
-        int running = 0;
+        SelectBound sb{0ull, 63};
+        float mu = 0.f;
+        if (!key_adaptive) {                         // Eq. 7, budget form
+            sb = block_radix_select(keyfn, M, key_budget, s_hist);
+        } else {                                     // Eq. 7 as printed: a_cls > mu, mu = mean + lambda * std
+            float s1 = 0.f;
+            int cnt = 0;
+            for (int j = tid; j < M; j += blockDim.x)
+                if (!vb || vb[j]) { s1 += acls_b[j]; ++cnt; }
+            s1 = block_sum(s1, s_redf);
+            cnt = block_sum_i(cnt, s_red);
+            const float mean = cnt > 0 ? s1 / (float)cnt : 0.f;
+            float s2 = 0.f;
+            for (int j = tid; j < M; j += blockDim.x)
+                if (!vb || vb[j]) { const float dlt = acls_b[j] - mean; s2 = fmaf(dlt, dlt, s2); }
+            s2 = block_sum(s2, s_redf);
+            mu = mean + key_lambda * sqrtf(cnt > 0 ? s2 / (float)cnt : 0.f);
+        }
+        int running = 0;                             // keys so far; key_budget is the capacity of key_index
         for (int base = 0; base < M; base += blockDim.x) {
             const int j = base + tid;
             bool sel = false;
-            if (j < M && (!vb || vb[j])) sel = (rank_key(acls_b[j], j) >> sb.shift) >= sb.bound;
+            if (j < M && (!vb || vb[j]))
+                sel = key_adaptive ? acls_b[j] > mu : (rank_key(acls_b[j], j) >> sb.shift) >= sb.bound;
             if (j < M) iskey_b[j] = sel;
             int total;
             const int r = block_rank(sel, s_red, total);
-            if (sel) key_index[(size_t)b * key_budget + running + r] = j;
+            if (sel && running + r < key_budget) key_index[(size_t)b * key_budget + running + r] = j;
             running += total;
         }
         for (int r = running + tid; r < key_budget; r += blockDim.x) key_index[(size_t)b * key_budget + r] = -1;
+        if (key_count && tid == 0) key_count[b] = running;
     } else {
         for (int j = tid; j < M; j += blockDim.x) {
             iskey_b[j] = 0;
@@ -402,6 +423,7 @@ template <int IPT>
 __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
     const float* __restrict__ logits, const float* __restrict__ sim, float tau, int key_budget,
+    int key_adaptive, float key_lambda, int32_t* __restrict__ key_count,
     uint8_t* __restrict__ wmerged, int32_t* __restrict__ dstpos,
     int32_t* __restrict__ out_index, float* __restrict__ out_mass, uint8_t* __restrict__ out_is_key,
     uint8_t* __restrict__ out_valid, int32_t* __restrict__ out_count, int32_t* __restrict__ key_index,
@@ -411,6 +433,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
     __shared__ int s_hist[256];
     __shared__ int s_red[16];
+    __shared__ float s_redf[16];
     __shared__ int s_moff[kMaxWindow];               // member_offset(m): integer divisions done once per block
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
     const int M = p.M, W = p.W;
@@ -435,7 +458,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
 #pragma unroll
     for (int t = 0; t < IPT; ++t) sel[t] = false;
 
-    if (key_budget > 0) {
+    if (key_budget > 0 || key_adaptive) {
         const float* lg = logits + (size_t)b * p.Hc * (M + 1);
         // one token per thread and few heads: the own token's logits are requested before the
         // denominators are computed, so that the two passes over the logits cost one round trip
@@ -498,20 +521,41 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
             if (j < M && a_cls_out) a_cls_out[(size_t)b * M + j] = a;
             rk[t] = ok[t] ? rank_key(a, j) : 0ull;
         }
-        const SelectBound sb = block_radix_select_reg<IPT>(rk, key_budget, s_hist);
-        int running = 0;
+        if (!key_adaptive) {                         // Eq. 7, budget form: the key_budget largest scores
+            const SelectBound sb = block_radix_select_reg<IPT>(rk, key_budget, s_hist);
+#pragma unroll
+            for (int t = 0; t < IPT; ++t) sel[t] = rk[t] != 0 && (rk[t] >> sb.shift) >= sb.bound;
+        } else {                                     // Eq. 7 as printed: a_cls > mu, mu = mean + lambda * std
+            float s1 = 0.f;
+            int cnt = 0;
+#pragma unroll
+            for (int t = 0; t < IPT; ++t)
+                if (ok[t]) { s1 += __uint_as_float((uint32_t)(rk[t] >> 32)); ++cnt; }
+            s1 = block_sum(s1, s_redf);
+            cnt = block_sum_i(cnt, s_red);
+            const float mean = cnt > 0 ? s1 / (float)cnt : 0.f;
+            float s2 = 0.f;
+#pragma unroll
+            for (int t = 0; t < IPT; ++t)
+                if (ok[t]) { const float dlt = __uint_as_float((uint32_t)(rk[t] >> 32)) - mean; s2 = fmaf(dlt, dlt, s2); }
+            s2 = block_sum(s2, s_redf);
+            const float mu = mean + key_lambda * sqrtf(cnt > 0 ? s2 / (float)cnt : 0.f);
+#pragma unroll
+            for (int t = 0; t < IPT; ++t) sel[t] = ok[t] && __uint_as_float((uint32_t)(rk[t] >> 32)) > mu;
+        }
+        int running = 0;                             // keys so far; key_budget is the capacity of key_index
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
             if (t * 1024 >= M) continue;             // block-uniform
             const int j = tid + t * 1024;
-            sel[t] = rk[t] != 0 && (rk[t] >> sb.shift) >= sb.bound;
             if (j < M) s_key[j] = sel[t];
             int total;
             const int r = block_rank(sel[t], s_red, total);
-            if (sel[t]) key_index[(size_t)b * key_budget + running + r] = j;
+            if (sel[t] && running + r < key_budget) key_index[(size_t)b * key_budget + running + r] = j;
             running += total;
         }
         for (int r = running + tid; r < key_budget; r += blockDim.x) key_index[(size_t)b * key_budget + r] = -1;
+        if (key_count && tid == 0) key_count[b] = running;
     } else {
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
@@ -718,14 +762,18 @@ extern "C" size_t mustdrop_encode_merge_workspace_bytes(int B, int T, int Hg, in
     return carve_encode(nullptr, B, (int)M, (int)(W > 0 ? W : 1), Hc).bytes;
 }
 
-extern "C" int mustdrop_encode_merge(
+namespace md {
+namespace {
+// Both forms of the key set (Eq. 7): key_adaptive == 0: the key_budget largest scores; key_adaptive == 1:
+// a_cls > mean + key_lambda * std, key_budget = capacity of key_index, key_count = size of the set.
+int encode_merge_impl(
     const void* x, md_dtype x_dtype,
     const void* q_cls, const void* k_cls, md_dtype qk_dtype,
     const float* mass_in, const uint8_t* valid,
     int B, int T, int Hg, int Wg, int D, int Hc, int dc,
-    int kt, int kh, int kw, float tau, int key_budget,
+    int kt, int kh, int kw, float tau, int key_adaptive, int key_budget, float key_lambda,
     void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
-    int32_t* out_count, int32_t* key_index,
+    int32_t* out_count, int32_t* key_index, int32_t* key_count,
     float* a_cls_out, float* window_sim_out,
     void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -741,16 +789,21 @@ extern "C" int mustdrop_encode_merge(
     const long M_l = (long)T * Hg * Wg;
     if (M_l > (1l << 24) || (long)B * M_l > (1l << 30)) return fail(MD_ESHAPE, "encode_merge: too many tokens");
     const int M = (int)M_l, ws = (int)ws_l, W = M / ws;
-    if (key_budget < 0 || key_budget > M) return fail(MD_EINVAL, "encode_merge: key_budget %d outside [0, %d]", key_budget, M);
+    if (key_budget < 0 || (!key_adaptive && key_budget > M))
+        return fail(MD_EINVAL, "encode_merge: key_budget %d outside [0, %d]", key_budget, M);
+    if (key_adaptive && (std::isnan(key_lambda) || !key_count))
+        return fail(MD_EINVAL, "encode_merge: the adaptive key rule needs a key_lambda that is a number and key_count");
+    const bool with_keys = key_adaptive || key_budget > 0;
     if (!x || !out_x || !out_index || !out_mass || !out_is_key || !out_count)
         return fail(MD_EINVAL, "encode_merge: x and the out_* arrays are required");
     if (std::isnan(tau)) return fail(MD_EINVAL, "encode_merge: tau is NaN");
     const size_t xe = elt_size(x_dtype);
     if ((D * xe) % 16) return fail(MD_EALIGN, "encode_merge: a row of D=%d elements is not a multiple of 16 bytes", D);
     if (!aligned16(x) || !aligned16(out_x)) return fail(MD_EALIGN, "encode_merge: x / out_x must be 16-byte aligned");
-    if (key_budget > 0) {
+    if (with_keys) {
         if (qk_dtype != MD_F32 && qk_dtype != MD_BF16) return fail(MD_EDTYPE, "encode_merge: unknown qk_dtype %d", (int)qk_dtype);
-        if (!q_cls || !k_cls || !key_index) return fail(MD_EINVAL, "encode_merge: q_cls, k_cls, key_index are required when key_budget > 0");
+        if (!q_cls || !k_cls || (key_budget > 0 && !key_index))
+            return fail(MD_EINVAL, "encode_merge: q_cls, k_cls (and key_index, if it has room) are required when keys are selected");
         if (Hc <= 0 || dc <= 0) return fail(MD_EINVAL, "encode_merge: Hc and dc must be positive");
         if (Hc > kMaxClsHeads) return fail(MD_ESHAPE, "encode_merge: Hc=%d exceeds the limit of %d", Hc, kMaxClsHeads);
         if ((long)Hc * dc != D) return fail(MD_ESHAPE, "encode_merge: Hc*dc = %ld differs from D = %d", (long)Hc * dc, D);
@@ -762,21 +815,21 @@ extern "C" int mustdrop_encode_merge(
     }
     const size_t xbytes = (size_t)B * M * D * xe;
     if (overlaps(x, xbytes, out_x, xbytes)) return fail(MD_EALIAS, "encode_merge: out_x overlaps x");
-    const EncodeWorkspace wsp = carve_encode(workspace, B, M, W, key_budget > 0 ? Hc : 0);
+    const EncodeWorkspace wsp = carve_encode(workspace, B, M, W, with_keys ? Hc : 0);
     if (!workspace || workspace_bytes < wsp.bytes)
         return fail(MD_EWORKSPACE, "encode_merge: workspace of %zu bytes needed, %zu given", wsp.bytes, workspace ? workspace_bytes : (size_t)0);
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(MD_EALIGN, "encode_merge: workspace must be 256-byte aligned");
 
     EncodeDims p;
-    p.B = B; p.T = T; p.Hg = Hg; p.Wg = Wg; p.D = D; p.Hc = key_budget > 0 ? Hc : 0; p.dc = dc;
+    p.B = B; p.T = T; p.Hg = Hg; p.Wg = Wg; p.D = D; p.Hc = with_keys ? Hc : 0; p.dc = dc;
     p.kt = kt; p.kh = kh; p.kw = kw; p.M = M; p.W = W; p.ws = ws;
     p.nwx = Wg / kw; p.nwy = Hg / kh; p.nwt = T / kt;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const long items = (long)B * W + (key_budget > 0 ? (long)B * cls_groups(M) : 0);
+    const long items = (long)B * W + (with_keys ? (long)B * cls_groups(M) : 0);
     dim3 sgrid((unsigned)((items + kEncWaves - 1) / kEncWaves));
     const bool xbf = x_dtype == MD_BF16, qkbf = qk_dtype == MD_BF16;
-    const int with_cls = key_budget > 0;
+    const int with_cls = with_keys;
     if (ws <= 2) launch_scores<2>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     else if (ws <= 4) launch_scores<4>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
     else if (ws <= 8) launch_scores<8>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
@@ -784,7 +837,8 @@ extern "C" int mustdrop_encode_merge(
     dim3 wgrid((unsigned)(((long)B * W + kEncWaves - 1) / kEncWaves));
 #define MD_DECIDE_FAST(IPT_)                                                                                  \
     MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_>), B, 1024, 6 * (size_t)M,              \
-        p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.wmerged, wsp.dstpos,                          \
+        p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,              \
+        wsp.wmerged, wsp.dstpos,                                                                                   \
         out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)
     if (M <= 1024) MD_DECIDE_FAST(1);
     else if (M <= 2048) MD_DECIDE_FAST(2);
@@ -792,10 +846,45 @@ extern "C" int mustdrop_encode_merge(
     else if (M <= 8192) MD_DECIDE_FAST(8);
     else
         MD_LAUNCH("encode_decide", st, (encode_decide_kernel), B, 1024, 0,
-            p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
+            p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,
+            wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
             out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out);
 #undef MD_DECIDE_FAST
     if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true>), wgrid, 64 * kEncWaves, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
     else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false>), wgrid, 64 * kEncWaves, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
     return check_launch("encode_merge");
+}
+}  // namespace
+}  // namespace md
+
+extern "C" int mustdrop_encode_merge(
+    const void* x, md_dtype x_dtype,
+    const void* q_cls, const void* k_cls, md_dtype qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, int key_budget,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
+    int32_t* out_count, int32_t* key_index,
+    float* a_cls_out, float* window_sim_out,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return encode_merge_impl(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, B, T, Hg, Wg, D, Hc, dc, kt, kh, kw, tau,
+                             0, key_budget, 0.f, out_x, out_index, out_mass, out_is_key, out_valid, out_count,
+                             key_index, nullptr, a_cls_out, window_sim_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mustdrop_encode_merge_adaptive(
+    const void* x, md_dtype x_dtype,
+    const void* q_cls, const void* k_cls, md_dtype qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, float key_lambda, int key_cap,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
+    int32_t* out_count, int32_t* key_index, int32_t* key_count,
+    float* a_cls_out, float* window_sim_out,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return encode_merge_impl(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, B, T, Hg, Wg, D, Hc, dc, kt, kh, kw, tau,
+                             1, key_cap, key_lambda, out_x, out_index, out_mass, out_is_key, out_valid, out_count,
+                             key_index, key_count, a_cls_out, window_sim_out, workspace, workspace_bytes, stream);
 }

@@ -42,6 +42,17 @@ def encode_on_gpu(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, T, Hg, Wg,
     return g
 
 
+def encode_adaptive_on_gpu(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, T, Hg, Wg, kt, kh, kw, tau, key_lambda,
+                           key_cap):
+    out = md.mustdrop_encode_merge_adaptive(
+        to_dev(x, x_dtype == md.BF16), to_dev(q_cls, qk_dtype == md.BF16), to_dev(k_cls, qk_dtype == md.BF16),
+        to_dev(mass_in), to_dev(valid), T, Hg, Wg, kt, kh, kw, tau, key_lambda, key_cap)
+    g = outputs_to_host(out)
+    if key_cap == 0:
+        g["key_index"] = np.zeros((x.shape[0], 0), dtype=np.int32)
+    return g
+
+
 def prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, mode, budget, gamma, alpha, Rcap=None):
     out = md.mustdrop_prefill_filter(
         to_dev(t["q_txt"], True), to_dev(t["k"], True), to_dev(t["v"], True), to_dev(t["hidden"], True),

@@ -41,8 +41,10 @@ def _f64(a, dtype):
 
 
 # ------------------------------------------------------------------------------------------ stage 1
-def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget):
-    """g: GPU outputs, o: oracle outputs (dicts of numpy arrays)."""
+def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget, key_lambda=None):
+    """g: GPU outputs, o: oracle outputs (dicts of numpy arrays).  key_lambda given: the key set is the
+    printed form of Eq. 7 (a_cls > mean + key_lambda * std), key_budget then being the capacity of
+    key_index; a token is decisive iff |a_cls - mu| > 1e-3 * |mu|."""
     B, M, D = x.shape
     ws = kt * kh * kw
     nwx, nwy = Wg // kw, Hg // kh
@@ -61,7 +63,31 @@ def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget
     for b in range(B):
         vb = np.ones(M, bool) if valid is None else valid[b].astype(bool)
         amb_tok = np.zeros(M, bool)
-        if key_budget > 0:
+        if key_lambda is not None and vb.any():
+            ra = rel_err(g["a_cls"][b][vb], o["a_cls"][b][vb])
+            assert ra.max() <= RTOL, f"a_cls relative error {ra.max()}"
+            summary["max_acls_rel"] = max(summary["max_acls_rel"], float(ra.max()))
+            cand = np.flatnonzero(vb)
+            a = o["a_cls"][b][cand]
+            mu = a.mean() + float(np.float32(key_lambda)) * a.std()
+            dec = np.abs(a - mu) > MARGIN * abs(mu)
+            ng_k, no_k = int(g["key_count"][b]), int(o["key_count"][b])
+            if dec.all():
+                assert ng_k == no_k, f"key count {ng_k} != {no_k}"
+                assert np.array_equal(g["key_index"][b], o["key_index"][b]), "key_index differs"
+            stored = g["key_index"][b][:min(ng_k, key_budget)]
+            assert np.all(np.diff(stored) > 0) and np.all(g["key_index"][b][min(ng_k, key_budget):] == -1)
+            # membership of the decisive tokens: from out_is_key of the survivors (a key token always survives)
+            gkeys = set(int(t) for t, kf in zip(g["out_index"][b, :g["out_count"][b]], g["out_is_key"][b]) if kf)
+            okeys = set(int(t) for t, kf in zip(o["out_index"][b, :o["out_count"][b]], o["out_is_key"][b]) if kf)
+            assert len(gkeys) == ng_k and len(okeys) == no_k
+            for j, d in zip(cand, dec):
+                if d:
+                    assert (int(j) in gkeys) == (int(j) in okeys), f"sample {b}: decisive key token {j} differs"
+                else:
+                    amb_tok[j] = True
+            summary["ambiguous_keys"] += int((~dec).sum())
+        elif key_budget > 0:
             ra = rel_err(g["a_cls"][b][vb], o["a_cls"][b][vb])
             assert ra.max() <= RTOL, f"a_cls relative error {ra.max()}"
             summary["max_acls_rel"] = max(summary["max_acls_rel"], float(ra.max()))

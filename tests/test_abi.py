@@ -138,3 +138,18 @@ def test_decode_keep_argument_errors(lib):
     assert keep(v=P(0x10000000 + 3 * 2 * 640 * 32 * 128 * 2)) == 4     # overlaps the fourth layer of k
     assert keep(wsb=0) == 5
     assert keep(k=P(0x10000008)) == 3
+
+
+def test_encode_adaptive_argument_errors(lib):
+    def enc(**kw):
+        a = dict(x=P(0x1000000), q=P(0x2000000), k=P(0x3000000), out=P(0x8000000), cnt=X, kc=X, lam=F(1.0), cap=16,
+                 ws=P(0x100000000), wsb=1 << 30)
+        a.update(kw)
+        return lib.mustdrop_encode_merge_adaptive(
+            a["x"], 1, a["q"], a["k"], 1, None, None, 2, 1, 24, 24, 1024, 16, 64, 1, 2, 2, F(0.9), a["lam"], a["cap"],
+            a["out"], X, X, X, None, a["cnt"], X, a["kc"], None, None, a["ws"], C.c_size_t(a["wsb"]), None)
+    assert enc(kc=None) == 1                         # key_count is required
+    assert enc(q=None) == 1                          # q_cls is always required
+    assert enc(lam=F(float("nan"))) == 1
+    assert enc(cap=-1) == 1
+    assert enc(wsb=16) == 5

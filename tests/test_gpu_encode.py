@@ -128,3 +128,29 @@ def test_determinism():
     for r in runs[1:]:
         for name in ("out_x", "out_index", "out_mass", "out_count", "key_index", "a_cls", "window_sim"):
             assert np.array_equal(runs[0][name], r[name]), name
+
+
+@pytest.mark.parametrize("shape", ["cfg2_slice", "ragged_small", "long_general"])
+def test_adaptive_key_threshold(shape):
+    """Eq. 7 as printed: keys = {a_cls > mean + lambda * std}, several lambdas, with and without padding."""
+    from paper_2411_10803_amd import harness
+    if shape == "cfg2_slice":
+        cfg, samples = wl.CONFIGS[2], [0, 5, 11]
+    elif shape == "ragged_small":
+        cfg, samples = wl.tiny(wl.CONFIGS[2], B=3, T=2, Hg=6, Wg=10, D=200, Hc=25, dc=8, kt=2, kh=3, kw=2), None
+    else:                                            # more than 8192 tokens per sample: the general kernels
+        cfg, samples = wl.tiny(wl.CONFIGS[2], B=1, T=1, Hg=96, Wg=96, D=64, Hc=4, dc=16), None
+    e = wl.encode_inputs(cfg, samples)
+    B = e["x"].shape[0]
+    rng = np.random.default_rng(9)
+    tau = median_tau(cfg) if samples is None else cfg.tau
+    for lam, masked, cap in ((0.0, False, cfg.M), (1.0, True, cfg.M), (2.5, False, 4), (-0.5, True, 7), (50.0, False, 0)):
+        valid = (rng.random((B, cfg.M)) > 0.2).astype(np.uint8) if masked else None
+        g = harness.encode_adaptive_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, valid,
+                                           cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, lam, cap)
+        o = oracle.encode_merge_adaptive(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, valid,
+                                         cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, lam, cap)
+        check_encode(g, o, e["x"], cfg.x_dtype, valid, cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, cap,
+                     key_lambda=lam)
+        if lam == 50.0:
+            assert np.all(g["key_count"] == 0)
