@@ -305,7 +305,7 @@ def cpu_baseline(cfg, pipe, min_seconds=10.0):
             list(ex.map(one, range(cfg.B)))
             reps += 1
             dt = time.perf_counter() - t0
-            if dt >= min_seconds or reps >= 20:
+            if dt >= min_seconds or reps >= 500:
                 break
     return {"value": reps * cfg.B * cfg.M / dt, "unit": "vision tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"the full batch of {cfg.B} samples through all three oracle stages, {reps} repetitions, "
