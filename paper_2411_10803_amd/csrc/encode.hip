@@ -548,7 +548,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         for (int t = 0; t < IPT; ++t) {
             if (t * 1024 >= M) continue;             // block-uniform
             const int j = tid + t * 1024;
-            if (j < M) s_key[j] = sel[t];
+            if (j < M) { s_key[j] = sel[t]; s_state[j] = 0; }
             int total;
             const int r = block_rank(sel[t], s_red, total);
             if (sel[t] && running + r < key_budget) key_index[(size_t)b * key_budget + running + r] = j;
@@ -560,20 +560,14 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
             const int j = tid + t * 1024;
-            if (j < M) { s_key[j] = 0; if (a_cls_out) a_cls_out[(size_t)b * M + j] = 0.f; }
+            if (j < M) { s_key[j] = 0; s_state[j] = 0; if (a_cls_out) a_cls_out[(size_t)b * M + j] = 0.f; }
         }
     }
     __syncthreads();
 
     // ---- merge decision per window: S > tau, >= 2 valid members, no key member.  The window's thread
     // leaves each member's fate (and the merged mass at the first valid member) in LDS, so that the
-    // per-token pass below needs no index arithmetic.
-#pragma unroll
-    for (int t = 0; t < IPT; ++t) {
-        const int j = tid + t * 1024;
-        if (j < M) s_state[j] = 0;
-    }
-    __syncthreads();
+    // per-token pass below needs no index arithmetic (the states were cleared with the key flags).
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
         const int w = tid + t * 1024;
