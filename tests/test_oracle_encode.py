@@ -409,6 +409,26 @@ def test_adaptive_key_set_is_the_threshold_rule_on_an_independent_a_cls():
         assert np.all(o["key_index"][b, want.size:] == -1)
 
 
+def test_adaptive_threshold_uses_the_population_standard_deviation():
+    """On eight tokens the population and the sample standard deviation differ by 7 %: a lambda is searched for
+    which the two thresholds separate a token, and the oracle must side with the population form."""
+    cfg = wl.tiny(wl.CONFIGS[2], B=1, Hg=2, Wg=4, D=32, Hc=2, dc=16)
+    e = wl.encode_inputs(cfg)
+    base = _adaptive(cfg, e, None, 0.0)
+    a = base["a_cls"][0]
+    found = None
+    for lam in np.linspace(0.05, 2.5, 400):
+        l32 = np.float64(np.float32(lam))
+        pop = set(np.flatnonzero(a > a.mean() + l32 * a.std()).tolist())
+        smp = set(np.flatnonzero(a > a.mean() + l32 * a.std(ddof=1)).tolist())
+        if pop != smp:
+            found = (float(lam), pop)
+            break
+    assert found is not None
+    o = _adaptive(cfg, e, None, found[0])
+    assert set(o["key_index"][0, :o["key_count"][0]].tolist()) == found[1]
+
+
 def test_adaptive_key_set_limits_monotonicity_and_the_budget_form():
     cfg, e, valid = _adaptive_case()
     tau = 0.5                                        # low enough for many windows to merge when no key blocks them
