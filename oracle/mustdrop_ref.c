@@ -14,10 +14,14 @@
  * Pins (tests/test_oracle_*.py): closed forms (constant image, orthogonal
  * tokens, zero queries -> harmonic numbers), conservation of token mass,
  * brute-force enumeration on tiny grids, an independent numpy einsum+softmax,
- * stable-argsort selection, subset brute force for eviction.  Unpinned by
+ * stable-argsort selection, subset brute force for eviction, a direct
+ * construction of the hole-filling layout over several layers, and the figures
+ * printed in Tables 1 and 3 (tests/test_golden.py).  Parity unpinned by
  * anything the paper prints: the numeric values of tau, mu, gamma, alpha and
  * the layer schedule (the paper defers them to an appendix that is not
- * available) -- they are caller parameters here.
+ * available) -- they are caller parameters here; the form of the adaptive
+ * threshold of Eq. 7 (read as mean + lambda * std; that rule itself is pinned
+ * against numpy, except strict > against >= at an exact tie).
  */
 #include <math.h>
 #include <stdint.h>
