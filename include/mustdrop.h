@@ -224,6 +224,71 @@ int mustdrop_decode_keep(
     void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Other memory layouts of Q, K and V (the tensors of Eq. 3-4; what the stages compute is unchanged).
+ *
+ * The entry points above take the token-major layout [B, tokens, H, d].  The *_strided twins below
+ * take, per tensor group, the ELEMENT strides of the batch, token and head axes; the d elements of
+ * one (sample, token, head) stay contiguous.  A head-major cache [B, H, tokens, d] is
+ * {H*tokens*d, d, tokens*d}; a token-major one with padded rows {tokens*pitch, pitch, d}.
+ * A NULL layout means dense token-major, and a call whose layouts are all dense token-major takes
+ * exactly the path of the plain entry point.  For other layouts the score kernels run with strided
+ * addressing and the row copies gather a token's row head slice by head slice (d*2 contiguous
+ * bytes at a time).
+ *
+ * Every stride must be a positive multiple of 8 elements (16 bytes), and the three axes must nest
+ * without overlap: sorted by stride, stride[0] >= d, stride[1] >= stride[0]*extent[0],
+ * stride[2] >= stride[1]*extent[1] (else MD_ESHAPE).  The caller's allocation must cover
+ * (B-1)*batch + (tokens-1)*token + (H-1)*head + d elements from the base pointer.
+ * All other arguments, outputs, limits and errors are those of the plain entry point.
+ */
+typedef struct {
+    int64_t batch;   /* elements between consecutive samples       */
+    int64_t token;   /* elements between consecutive tokens/slots  */
+    int64_t head;    /* elements between consecutive heads         */
+} md_kv_layout;      /* host memory; read during the call only     */
+
+/* q_layout: q_txt over N tokens; kv_layout: k and v over L = Mv+N tokens (one layout for both);
+ * kv_out_layout: k_out and v_out over Rcap+N rows.  hidden and hidden_out stay [B, rows, C]. */
+int mustdrop_prefill_filter_strided(
+    const void* q_txt, const void* k, const void* v, const void* hidden,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    int B, int Mv, int N, int H, int d, int C,
+    float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
+    int Rcap,
+    void* hidden_out, void* k_out, void* v_out,
+    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
+    float* score_global, float* score_indiv,
+    const md_kv_layout* q_layout, const md_kv_layout* kv_layout, const md_kv_layout* kv_out_layout,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* cache_layout: k_cache and v_cache over Lcap slots.  q, k_new, v_new stay [B, H, d]. */
+int mustdrop_decode_evict_strided(
+    const void* q, void* k_cache, void* v_cache,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d,
+    float softmax_scale, float decay, int budget,
+    int32_t* evicted_ids, int32_t* evicted_count,
+    const md_kv_layout* cache_layout,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+int mustdrop_decode_append_strided(
+    const void* k_new, const void* v_new,
+    void* k_cache, void* v_cache,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d, int32_t new_id, int protect_new,
+    const md_kv_layout* cache_layout, void* stream);
+
+/* layer_stride: elements between the caches of consecutive layers (ignored when n_layers == 1;
+ * a positive multiple of 8 that is at least the extent of one layer's cache, else MD_ESHAPE). */
+int mustdrop_decode_keep_strided(
+    void* k_cache, void* v_cache, const uint8_t* keep,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int n_layers, int B, int Lcap, int H, int d,
+    int32_t* evicted_ids, int32_t* evicted_count,
+    const md_kv_layout* cache_layout, int64_t layer_stride,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Benchmarking aid (not part of the method): per-kernel timing with HIP events.
  * Between mustdrop_profile_start() and mustdrop_profile_stop() every kernel the library launches
  * carries an event pair that receives the begin and end timestamps of that dispatch on its stream

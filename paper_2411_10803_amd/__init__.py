@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     decode_workspace, encode_workspace, library, library_path, prefill_workspace,
     mustdrop_decode_append, mustdrop_decode_evict, mustdrop_decode_keep, mustdrop_encode_merge, mustdrop_encode_merge_adaptive,
     mustdrop_prefill_filter,
+    KvLayout, mustdrop_decode_append_strided, mustdrop_decode_evict_strided, mustdrop_decode_keep_strided,
+    mustdrop_prefill_filter_strided,
 )
 
 __all__ = [
@@ -16,4 +18,6 @@ __all__ = [
     "library", "library_path", "encode_workspace", "prefill_workspace", "decode_workspace",
     "mustdrop_encode_merge", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
     "mustdrop_decode_keep", "mustdrop_encode_merge_adaptive",
+    "KvLayout", "mustdrop_prefill_filter_strided", "mustdrop_decode_evict_strided", "mustdrop_decode_append_strided",
+    "mustdrop_decode_keep_strided",
 ]

@@ -18,8 +18,15 @@ EXPORTS = [
     "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge", "mustdrop_encode_merge_adaptive",
     "mustdrop_prefill_filter_workspace_bytes", "mustdrop_prefill_filter",
     "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append", "mustdrop_decode_keep",
+    "mustdrop_prefill_filter_strided", "mustdrop_decode_evict_strided", "mustdrop_decode_append_strided",
+    "mustdrop_decode_keep_strided",
     "mustdrop_profile_start", "mustdrop_profile_stop",
 ]
+
+
+class KvLayout(C.Structure):
+    """md_kv_layout: element strides of the batch, token and head axes."""
+    _fields_ = [("batch", C.c_int64), ("token", C.c_int64), ("head", C.c_int64)]
 
 
 class MustDropError(RuntimeError):
@@ -46,7 +53,8 @@ def library() -> C.CDLL:
                   "mustdrop_decode_evict_workspace_bytes"):
             getattr(lib, n).restype = C.c_size_t
         for n in ("mustdrop_encode_merge", "mustdrop_encode_merge_adaptive", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
-                  "mustdrop_decode_keep"):
+                  "mustdrop_decode_keep", "mustdrop_prefill_filter_strided", "mustdrop_decode_evict_strided",
+                  "mustdrop_decode_append_strided", "mustdrop_decode_keep_strided"):
             getattr(lib, n).restype = C.c_int
         _lib = lib
     return _lib
@@ -65,6 +73,18 @@ def _ptr(t) -> C.c_void_p:
         return C.c_void_p(t)
     assert t.is_contiguous(), "tensors handed to the C ABI must be contiguous"
     return C.c_void_p(t.data_ptr())
+
+
+def _view_ptr(t) -> C.c_void_p:
+    """Device pointer of a [.., tokens, H, d] view whose last axis is contiguous (any other strides)."""
+    assert t.stride(-1) == 1, "the head dimension must be contiguous"
+    return C.c_void_p(t.data_ptr())
+
+
+def _layout(t):
+    """md_kv_layout of a [B, tokens, H, d] view (the last three axes of a [layers, B, tokens, H, d] one)."""
+    st = t.stride()
+    return KvLayout(st[-4], st[-3], st[-2])
 
 
 def _stream(stream=None) -> C.c_void_p:
@@ -250,6 +270,79 @@ def mustdrop_decode_keep(k_caches, v_caches, keep, acc, ids, protect, length, ev
         _ptr(k_caches), _ptr(v_caches), _ptr(keep), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
         C.c_int(n_layers), C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d),
         _ptr(evicted_ids), _ptr(evicted_count),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return workspace
+
+
+def mustdrop_prefill_filter_strided(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_scale, mode, budget,
+                                    gamma, alpha, out: Dict, Rcap=None, workspace=None, stream=None) -> Dict:
+    """Sec. 3.4 on Q / K / V in any layout: q_txt, k, v and out["k_out"], out["v_out"] are [B, tokens, H, d] VIEWS
+    (e.g. a permuted head-major tensor); their strides are handed over as md_kv_layout.  k and v share one
+    layout, k_out and v_out another.  `out` must hold every output tensor (see mustdrop_prefill_filter)."""
+    B, N, H, d = q_txt.shape
+    Cdim = hidden.shape[2]
+    if Rcap is None:
+        Rcap = budget if mode == FILTER_BUDGET else Mv
+    assert k.stride() == v.stride() and out["k_out"].stride() == out["v_out"].stride()
+    assert tuple(out["k_out"].shape) == (B, Rcap + N, H, d)
+    if workspace is None:
+        workspace = prefill_workspace(B, Mv, N, H, Rcap, q_txt.device)
+    out["workspace"] = workspace
+    lq, lkv, lo = _layout(q_txt), _layout(k), _layout(out["k_out"])
+    _check(library().mustdrop_prefill_filter_strided(
+        _view_ptr(q_txt), _view_ptr(k), _view_ptr(v), _ptr(hidden), _ptr(vis_valid), _ptr(txt_len), _ptr(is_key),
+        C.c_int(B), C.c_int(Mv), C.c_int(N), C.c_int(H), C.c_int(d), C.c_int(Cdim),
+        C.c_float(softmax_scale), C.c_int(mode), C.c_int(budget), C.c_float(gamma), C.c_float(alpha),
+        C.c_int(Rcap),
+        _ptr(out["hidden_out"]), _view_ptr(out["k_out"]), _view_ptr(out["v_out"]),
+        _ptr(out["kept_index"]), _ptr(out["kept_count"]), _ptr(out.get("out_len")), _ptr(out.get("out_protect")), _ptr(out.get("out_ids")),
+        _ptr(out.get("score_global")), _ptr(out.get("score_indiv")),
+        C.byref(lq), C.byref(lkv), C.byref(lo),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return out
+
+
+def mustdrop_decode_evict_strided(q, k_cache, v_cache, acc, ids, protect, length, softmax_scale, decay, budget,
+                                  evicted_ids=None, evicted_count=None, workspace=None, stream=None):
+    """Sec. 3.5, one decode step on caches given as [B, Lcap, H, d] views of any layout."""
+    B, Lcap, H, d = k_cache.shape
+    assert k_cache.stride() == v_cache.stride()
+    if workspace is None:
+        workspace = decode_workspace(B, Lcap, H, k_cache.device)
+    lay = _layout(k_cache)
+    _check(library().mustdrop_decode_evict_strided(
+        _ptr(q), _view_ptr(k_cache), _view_ptr(v_cache), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
+        C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d),
+        C.c_float(softmax_scale), C.c_float(decay), C.c_int(budget),
+        _ptr(evicted_ids), _ptr(evicted_count), C.byref(lay),
+        _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return workspace
+
+
+def mustdrop_decode_append_strided(k_new, v_new, k_cache, v_cache, acc, ids, protect, length, new_id, protect_new=1,
+                                   stream=None):
+    """Eq. 3 on caches given as [B, Lcap, H, d] views of any layout."""
+    B, Lcap, H, d = k_cache.shape
+    assert k_cache.stride() == v_cache.stride()
+    lay = _layout(k_cache)
+    _check(library().mustdrop_decode_append_strided(
+        _ptr(k_new), _ptr(v_new), _view_ptr(k_cache), _view_ptr(v_cache), _ptr(acc), _ptr(ids), _ptr(protect),
+        _ptr(length), C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d), C.c_int(int(new_id)),
+        C.c_int(int(protect_new)), C.byref(lay), _stream(stream)))
+
+
+def mustdrop_decode_keep_strided(k_caches, v_caches, keep, acc, ids, protect, length, evicted_ids=None,
+                                 evicted_count=None, workspace=None, stream=None):
+    """Sec. 3.5, the static policy on caches given as [n_layers, B, Lcap, H, d] views of any layout."""
+    n_layers, B, Lcap, H, d = k_caches.shape
+    assert k_caches.stride() == v_caches.stride()
+    if workspace is None:
+        workspace = decode_workspace(B, Lcap, H, k_caches.device)
+    lay = _layout(k_caches)
+    _check(library().mustdrop_decode_keep_strided(
+        _view_ptr(k_caches), _view_ptr(v_caches), _ptr(keep), _ptr(acc), _ptr(ids), _ptr(protect), _ptr(length),
+        C.c_int(n_layers), C.c_int(B), C.c_int(Lcap), C.c_int(H), C.c_int(d),
+        _ptr(evicted_ids), _ptr(evicted_count), C.byref(lay), C.c_int64(k_caches.stride(0)),
         _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
     return workspace
 

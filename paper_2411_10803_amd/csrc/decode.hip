@@ -26,7 +26,7 @@ constexpr int kMaxStatParts = 256;               // blocks per sample of the str
 template <int LPH>
 __global__ __launch_bounds__(256) void decode_logits_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
-    DecodeDims p, float scale, int tokens_per_block, float* __restrict__ logits)
+    DecodeDims p, KvLayout lay, float scale, int tokens_per_block, float* __restrict__ logits)
 {
     const int lane = lane_id(), wv = wave_id();
     const int b = blockIdx.y;
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
     const int nvec = row / 8;                       // 16-byte vectors per entry
     const int iters = (nvec + kWave - 1) / kWave;
     const uint16_t* qb = q + (long)b * row;
-    const uint16_t* kb = k_cache + (long)b * p.Lcap * row;
+    const uint16_t* kb = k_cache + (long)b * lay.batch;
     float* lb = logits + (long)b * p.Lcap * p.H;
 
     for (int it = 0; it < iters; ++it) {
@@ -53,10 +53,11 @@ __global__ __launch_bounds__(256) void decode_logits_kernel(
             for (int e = 0; e < 8; ++e) qv[e] = 0.f;
         }
         const int head = idx / LPH;
+        const long in_row = (long)head * lay.head + (idx % LPH) * 8;      // dense: idx * 8
         for (int j = t0 + wv; j < t1; j += 4) {
             float part = 0.f;
             if (idx < nvec) {
-                const u32x4 w = *reinterpret_cast<const u32x4*>(kb + (long)j * row + idx * 8);
+                const u32x4 w = *reinterpret_cast<const u32x4*>(kb + (long)j * lay.token + in_row);
                 part = qv[0] * bf16_lo(w.x);
                 part = fmaf(qv[1], bf16_hi(w.x), part);
                 part = fmaf(qv[2], bf16_lo(w.y), part);
@@ -90,10 +91,12 @@ __device__ __forceinline__ float dot8(const u32x4& a, const float (&qv)[8]) {
 // Each wave also keeps online softmax statistics (max, sum of exp2) of every head over the entries
 // it has seen; the block's four waves are merged and written as one partial per (sample, block, head),
 // so the selection kernel does not have to sweep the logits for them.
-template <int LPH, int NIT>
+// STRIDED: the cache has another layout; a load instruction then covers kWave/LPH head slices of
+// d*2 contiguous bytes each instead of 1 KiB of one row.
+template <int LPH, int NIT, bool STRIDED>
 __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
-    DecodeDims p, float scale, float* __restrict__ logits, float2* __restrict__ stat_partial)
+    DecodeDims p, KvLayout lay, float scale, float* __restrict__ logits, float2* __restrict__ stat_partial)
 {
     constexpr int HPI = kWave / LPH;                 // heads per load instruction
     __shared__ float s_m[4][NIT * HPI], s_z[4][NIT * HPI];
@@ -105,6 +108,13 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     const int row = p.H * p.d;
     const u32x4* qb = reinterpret_cast<const u32x4*>(q + (long)b * row);
     const u32x4* kb = reinterpret_cast<const u32x4*>(k_cache + (long)b * p.Lcap * row);
+    const uint16_t* ks = k_cache + (long)b * lay.batch;
+    long off[NIT];                                   // STRIDED: element offset of this lane's vectors within an entry
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int idx = it * kWave + lane;
+        off[it] = (long)(idx / LPH) * lay.head + (idx % LPH) * 8;
+    }
     float* lb = logits + (long)b * p.Lcap * p.H;
     const float scale_l2 = scale * kLog2eD;
 
@@ -120,10 +130,16 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     for (int it = 0; it < NIT; ++it) { m[it] = -INFINITY; z[it] = 0.f; }
 
     for (int j = wave_global; j < n; j += nwaves) {
-        const u32x4* kr = kb + (long)j * (row / 8);
         u32x4 kv[NIT];
+        if constexpr (STRIDED) {
+            const uint16_t* kr = ks + (long)j * lay.token;
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) kv[it] = kr[it * kWave + lane];
+            for (int it = 0; it < NIT; ++it) kv[it] = *reinterpret_cast<const u32x4*>(kr + off[it]);
+        } else {
+            const u32x4* kr = kb + (long)j * (row / 8);
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) kv[it] = kr[it * kWave + lane];
+        }
         float part[NIT];
 #pragma unroll
         for (int it = 0; it < NIT; ++it) part[it] = dot8(kv[it], qv[it]);
@@ -612,6 +628,56 @@ __global__ __launch_bounds__(256) void decode_append_kernel(
     }
 }
 
+// The two kernels above for caches in other layouts: a row is walked head slice by head slice.
+__global__ __launch_bounds__(256) void decode_move_strided_kernel(
+    DecodeDims p, KvLayout lay, const int32_t* __restrict__ holes, const int32_t* __restrict__ movers,
+    const int32_t* __restrict__ n_move, uint16_t* __restrict__ k_cache, uint16_t* __restrict__ v_cache, long layer_stride)
+{
+    const int b = blockIdx.y;
+    const int nm = n_move[b];
+    const int lph = p.d / 8, rv = p.H * lph;
+    k_cache += blockIdx.z * layer_stride + (long)b * lay.batch;
+    v_cache += blockIdx.z * layer_stride + (long)b * lay.batch;
+    for (int t = blockIdx.x; t < nm; t += gridDim.x) {
+        const long src = (long)movers[(long)b * p.Lcap + t] * lay.token;
+        const long dst = (long)holes[(long)b * p.Lcap + t] * lay.token;
+        for (int c = threadIdx.x; c < rv; c += blockDim.x) {
+            const int h = c / lph, w = c - h * lph;
+            const long off = (long)h * lay.head + w * 8;
+            const u32x4 k0 = *reinterpret_cast<const u32x4*>(k_cache + src + off);
+            const u32x4 v0 = *reinterpret_cast<const u32x4*>(v_cache + src + off);
+            *reinterpret_cast<u32x4*>(k_cache + dst + off) = k0;
+            *reinterpret_cast<u32x4*>(v_cache + dst + off) = v0;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void decode_append_strided_kernel(
+    DecodeDims p, KvLayout lay, const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new,
+    uint16_t* __restrict__ k_cache, uint16_t* __restrict__ v_cache,
+    float* __restrict__ acc, int32_t* __restrict__ ids, uint8_t* __restrict__ protect, int32_t* __restrict__ len,
+    int32_t new_id, int protect_new)
+{
+    const int b = blockIdx.x;
+    const int slot = len[b];
+    if (slot < 0 || slot >= p.Lcap) return;
+    const int lph = p.d / 8, rv = p.H * lph;
+    const long dst = (long)b * lay.batch + (long)slot * lay.token;
+    for (int c = threadIdx.x; c < rv; c += blockDim.x) {
+        const int h = c / lph, w = c - h * lph;
+        const long off = dst + (long)h * lay.head + w * 8;
+        *reinterpret_cast<u32x4*>(k_cache + off) = k_new[(long)b * rv + c];
+        *reinterpret_cast<u32x4*>(v_cache + off) = v_new[(long)b * rv + c];
+    }
+    __syncthreads();                                   // every thread has read len[b] before it changes
+    if (threadIdx.x == 0) {
+        acc[(long)b * p.Lcap + slot] = 0.f;
+        ids[(long)b * p.Lcap + slot] = new_id;
+        protect[(long)b * p.Lcap + slot] = protect_new ? 1 : 0;
+        len[b] = slot + 1;
+    }
+}
+
 #ifndef MD_DEC_BLOCKS
 #define MD_DEC_BLOCKS 4096   // target number of blocks of the streaming logits kernel
 #endif
@@ -654,24 +720,32 @@ extern "C" size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H) 
     return carve_decode(nullptr, B, Lcap, H).bytes;
 }
 
-extern "C" int mustdrop_decode_evict(
+namespace md {
+namespace {
+
+int decode_evict_impl(
     const void* q, void* k_cache, void* v_cache,
     float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
     int B, int Lcap, int H, int d,
     float softmax_scale, float decay, int budget,
     int32_t* evicted_ids, int32_t* evicted_count,
+    const md_kv_layout* cache_layout,
     void* workspace, size_t workspace_bytes, void* stream)
 {
     clear_error();
     int rc = check_decode_dims("decode_evict", B, Lcap, H, d);
     if (rc != MD_OK) return rc;
+    KvLayout lay;
+    rc = read_layout("decode_evict", "cache", cache_layout, B, Lcap, H, d, &lay);
+    if (rc != MD_OK) return rc;
+    const bool dense = is_dense(lay, Lcap, H, d);
     if (!q || !k_cache || !v_cache || !acc || !ids || !protect || !len)
         return fail(MD_EINVAL, "decode_evict: q, the caches and the state arrays are required");
     if (budget < 0) return fail(MD_EINVAL, "decode_evict: negative budget");
     if (std::isnan(softmax_scale) || std::isnan(decay)) return fail(MD_EINVAL, "decode_evict: NaN parameter");
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache))
         return fail(MD_EALIGN, "decode_evict: q and the caches must be 16-byte aligned");
-    const size_t cache_bytes = (size_t)B * Lcap * H * d * 2;
+    const size_t cache_bytes = layout_extent_bytes(lay, B, Lcap, H, d);
     if (overlaps(k_cache, cache_bytes, v_cache, cache_bytes)) return fail(MD_EALIAS, "decode_evict: k_cache overlaps v_cache");
     if (overlaps(q, (size_t)B * H * d * 2, k_cache, cache_bytes) || overlaps(q, (size_t)B * H * d * 2, v_cache, cache_bytes))
         return fail(MD_EALIAS, "decode_evict: q overlaps a cache");
@@ -695,25 +769,38 @@ extern "C" int mustdrop_decode_evict(
         if (blocks_x > kMaxStatParts) blocks_x = kMaxStatParts;
         if (blocks_x < 1) blocks_x = 1;
         dim3 g1(blocks_x, B);
-        switch (nit) {
-            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 1>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
-            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 2>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
-            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 4>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
-            default: MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, 8>), g1, 256, 0, qp, kp, len, p, softmax_scale, w.logits, w.stat_partial); break;
+#define MD_STREAM(NIT_, S_)                                                                                        \
+        MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, NIT_, S_>), g1, 256, 0,                    \
+            qp, kp, len, p, lay, softmax_scale, w.logits, w.stat_partial)
+        if (dense) {
+            switch (nit) {
+                case 1: MD_STREAM(1, false); break;
+                case 2: MD_STREAM(2, false); break;
+                case 4: MD_STREAM(4, false); break;
+                default: MD_STREAM(8, false); break;
+            }
+        } else {
+            switch (nit) {
+                case 1: MD_STREAM(1, true); break;
+                case 2: MD_STREAM(2, true); break;
+                case 4: MD_STREAM(4, true); break;
+                default: MD_STREAM(8, true); break;
+            }
         }
+#undef MD_STREAM
         n_part = blocks_x;
     } else {
         int tpb = (int)(((long)B * Lcap + 4095) / 4096);
         tpb = tpb < 4 ? 4 : (tpb > 32 ? 32 : tpb);
         dim3 g1((Lcap + tpb - 1) / tpb, B);
         switch (d / 8) {
-            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-            case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-            case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
-            default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64>), g1, 256, 0, qp, kp, len, p, softmax_scale, tpb, w.logits); break;
+            case 1: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<1>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
+            case 2: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<2>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
+            case 4: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<4>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
+            case 8: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<8>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
+            case 16: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<16>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
+            case 32: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<32>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
+            default: MD_LAUNCH("decode_logits", st, (decode_logits_kernel<64>), g1, 256, 0, qp, kp, len, p, lay, softmax_scale, tpb, w.logits); break;
         }
     }
     const bool fast_h = H == 4 || H == 8 || H == 16 || H == 32 || H == 64;
@@ -744,27 +831,42 @@ extern "C" int mustdrop_decode_evict(
             p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
     }
     dim3 g3(32, B);
-    MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
-        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), 0l);
+    if (dense)
+        MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
+            p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), 0l);
+    else
+        MD_LAUNCH("decode_move", st, (decode_move_strided_kernel), g3, 256, 0,
+            p, lay, w.holes, w.movers, w.n_move, static_cast<uint16_t*>(k_cache), static_cast<uint16_t*>(v_cache), 0l);
     return check_launch("decode_evict");
 }
 
-extern "C" int mustdrop_decode_keep(
+int decode_keep_impl(
     void* k_cache, void* v_cache, const uint8_t* keep,
     float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
     int n_layers, int B, int Lcap, int H, int d,
     int32_t* evicted_ids, int32_t* evicted_count,
+    const md_kv_layout* cache_layout, int64_t layer_stride_in,
     void* workspace, size_t workspace_bytes, void* stream)
 {
     clear_error();
     int rc = check_decode_dims("decode_keep", B, Lcap, H, d);
     if (rc != MD_OK) return rc;
     if (n_layers <= 0 || n_layers > 65535) return fail(MD_EINVAL, "decode_keep: n_layers=%d out of range", n_layers);
+    KvLayout lay;
+    rc = read_layout("decode_keep", "cache", cache_layout, B, Lcap, H, d, &lay);
+    if (rc != MD_OK) return rc;
+    const size_t layer_bytes = layout_extent_bytes(lay, B, Lcap, H, d);
+    long layer_stride = cache_layout ? (long)layer_stride_in : (long)B * Lcap * H * d;
+    if (n_layers == 1) layer_stride = (long)(layer_bytes / 2);
+    if (layer_stride <= 0 || layer_stride % 8 || (size_t)layer_stride * 2 < layer_bytes)
+        return fail(MD_ESHAPE, "decode_keep: layer_stride=%ld must be a multiple of 8 elements covering one layer (%zu elements)",
+                    layer_stride, layer_bytes / 2);
+    const bool dense = is_dense(lay, Lcap, H, d);
     if (!k_cache || !v_cache || !keep || !ids || !protect || !len)
         return fail(MD_EINVAL, "decode_keep: null pointer among the required arguments");
     if ((H * d * 2) % 16) return fail(MD_EALIGN, "decode_keep: a row of H*d=%d bf16 is not a multiple of 16 bytes", H * d);
     if (!aligned16(k_cache) || !aligned16(v_cache)) return fail(MD_EALIGN, "decode_keep: caches must be 16-byte aligned");
-    const size_t cache_bytes = (size_t)n_layers * B * Lcap * H * d * 2;
+    const size_t cache_bytes = (size_t)(n_layers - 1) * layer_stride * 2 + layer_bytes;
     if (overlaps(k_cache, cache_bytes, v_cache, cache_bytes)) return fail(MD_EALIAS, "decode_keep: k_cache overlaps v_cache");
     const DecodeWorkspace w = carve_decode(workspace, B, Lcap, H);
     if (!workspace || workspace_bytes < w.bytes)
@@ -776,19 +878,27 @@ extern "C" int mustdrop_decode_keep(
     MD_LAUNCH("decode_keep_plan", st, (decode_keep_plan_kernel), B, 1024, 0,
         p, keep, acc, ids, protect, len, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
     dim3 g3(32, B, n_layers);
-    MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
-        p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
-        (long)B * Lcap * (H * d / 8));
+    if (dense)
+        MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
+            p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
+            layer_stride / 8);
+    else
+        MD_LAUNCH("decode_move", st, (decode_move_strided_kernel), g3, 256, 0,
+            p, lay, w.holes, w.movers, w.n_move, static_cast<uint16_t*>(k_cache), static_cast<uint16_t*>(v_cache),
+            layer_stride);
     return check_launch("decode_keep");
 }
 
-extern "C" int mustdrop_decode_append(
+int decode_append_impl(
     const void* k_new, const void* v_new, void* k_cache, void* v_cache,
     float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
-    int B, int Lcap, int H, int d, int32_t new_id, int protect_new, void* stream)
+    int B, int Lcap, int H, int d, int32_t new_id, int protect_new, const md_kv_layout* cache_layout, void* stream)
 {
     clear_error();
     int rc = check_decode_dims("decode_append", B, Lcap, H, d);
+    if (rc != MD_OK) return rc;
+    KvLayout lay;
+    rc = read_layout("decode_append", "cache", cache_layout, B, Lcap, H, d, &lay);
     if (rc != MD_OK) return rc;
     if (!k_new || !v_new || !k_cache || !v_cache || !acc || !ids || !protect || !len)
         return fail(MD_EINVAL, "decode_append: all pointers are required");
@@ -797,8 +907,71 @@ extern "C" int mustdrop_decode_append(
         return fail(MD_EALIGN, "decode_append: tensors must be 16-byte aligned");
     DecodeDims p{B, Lcap, H, d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    MD_LAUNCH("decode_append", st, (decode_append_kernel), B, 256, 0,
-        p, static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
-        static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new);
+    if (is_dense(lay, Lcap, H, d))
+        MD_LAUNCH("decode_append", st, (decode_append_kernel), B, 256, 0,
+            p, static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
+            static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), acc, ids, protect, len, new_id, protect_new);
+    else
+        MD_LAUNCH("decode_append", st, (decode_append_strided_kernel), B, 256, 0,
+            p, lay, static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
+            static_cast<uint16_t*>(k_cache), static_cast<uint16_t*>(v_cache), acc, ids, protect, len, new_id, protect_new);
     return check_launch("decode_append");
+}
+
+}  // namespace
+}  // namespace md
+
+extern "C" int mustdrop_decode_evict(
+    const void* q, void* k_cache, void* v_cache, float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d, float softmax_scale, float decay, int budget,
+    int32_t* evicted_ids, int32_t* evicted_count, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_evict_impl(q, k_cache, v_cache, acc, ids, protect, len, B, Lcap, H, d, softmax_scale, decay, budget,
+                             evicted_ids, evicted_count, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mustdrop_decode_evict_strided(
+    const void* q, void* k_cache, void* v_cache, float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d, float softmax_scale, float decay, int budget,
+    int32_t* evicted_ids, int32_t* evicted_count, const md_kv_layout* cache_layout,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_evict_impl(q, k_cache, v_cache, acc, ids, protect, len, B, Lcap, H, d, softmax_scale, decay, budget,
+                             evicted_ids, evicted_count, cache_layout, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mustdrop_decode_keep(
+    void* k_cache, void* v_cache, const uint8_t* keep, float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int n_layers, int B, int Lcap, int H, int d, int32_t* evicted_ids, int32_t* evicted_count,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_keep_impl(k_cache, v_cache, keep, acc, ids, protect, len, n_layers, B, Lcap, H, d, evicted_ids,
+                            evicted_count, nullptr, 0, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mustdrop_decode_keep_strided(
+    void* k_cache, void* v_cache, const uint8_t* keep, float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int n_layers, int B, int Lcap, int H, int d, int32_t* evicted_ids, int32_t* evicted_count,
+    const md_kv_layout* cache_layout, int64_t layer_stride, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_keep_impl(k_cache, v_cache, keep, acc, ids, protect, len, n_layers, B, Lcap, H, d, evicted_ids,
+                            evicted_count, cache_layout, layer_stride, workspace, workspace_bytes, stream);
+}
+
+extern "C" int mustdrop_decode_append(
+    const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d, int32_t new_id, int protect_new, void* stream)
+{
+    return decode_append_impl(k_new, v_new, k_cache, v_cache, acc, ids, protect, len, B, Lcap, H, d, new_id, protect_new,
+                              nullptr, stream);
+}
+
+extern "C" int mustdrop_decode_append_strided(
+    const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+    float* acc, int32_t* ids, uint8_t* protect, int32_t* len,
+    int B, int Lcap, int H, int d, int32_t new_id, int protect_new, const md_kv_layout* cache_layout, void* stream)
+{
+    return decode_append_impl(k_new, v_new, k_cache, v_cache, acc, ids, protect, len, B, Lcap, H, d, new_id, protect_new,
+                              cache_layout, stream);
 }

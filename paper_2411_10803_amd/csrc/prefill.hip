@@ -31,6 +31,7 @@ struct PrefillDims {
     int chunk;        // keys per chunk (multiple of 32)
     int Npad;         // 32 * NB
     int Rcap;
+    KvLayout q, kv;   // element strides of q_txt and of k (v shares them)
 };
 
 // key row of accumulator register r in the 32x32 result tile
@@ -123,9 +124,9 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const int lane = lane_id(), wv = wave_id();
     const int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y, b = blockIdx.z;
     const int i_base = tg * 32 * NB;                 // first text row of this block's group
-    const long tok_stride = (long)p.H * p.d;
-    const uint16_t* kb = k + ((long)b * p.L * p.H + h) * p.d;
-    const uint16_t* qb = q_txt + ((long)b * p.N * p.H + h) * p.d;
+    const long tok_stride = p.kv.token;
+    const uint16_t* kb = k + (long)b * p.kv.batch + (long)h * p.kv.head;
+    const uint16_t* qb = q_txt + (long)b * p.q.batch + (long)h * p.q.head;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
     char* tile = s_tile[wv];
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         u32x4 sq[NST][KS];
 #pragma unroll
         for (int e = 0; e < NST; ++e)
-            Tile::gload(qb, tok_stride, i_base + 32 * (nb0 + e), tl, lane, sq[e]);   // rows >= txt_len read as zero
+            Tile::gload(qb, p.q.token, i_base + 32 * (nb0 + e), tl, lane, sq[e]);   // rows >= txt_len read as zero
 #pragma unroll
         for (int e = 0; e < NST; ++e) {
             const int nb = nb0 + e;
@@ -329,13 +330,14 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
         tile_idx = blockIdx.x % nt;
     }
     const int j0 = tile_idx * 32;
-    const long tok_stride = (long)p.H * p.d;
+    const long tok_stride = p.kv.token;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
     char* tile = s_buf[wv];
 
     u32x4 st[KS];
-    if (wv < p.H) Tile::gload(k + ((long)b * p.L * p.H + wv) * p.d, tok_stride, j0, p.Mv, lane, st);
+    const uint16_t* kb = k + (long)b * p.kv.batch;
+    if (wv < p.H) Tile::gload(kb + (long)wv * p.kv.head, tok_stride, j0, p.Mv, lane, st);
 
     f32x16 a_acc[NB];
 #pragma unroll
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
         Tile::frags(tile, lane, kf);
         wave_lds_sync();
         if (h + NW < p.H)                                                      // prefetch the next head's K tile
-            Tile::gload(k + ((long)b * p.L * p.H + (h + NW)) * p.d, tok_stride, j0, p.Mv, lane, st);
+            Tile::gload(kb + (long)(h + NW) * p.kv.head, tok_stride, j0, p.Mv, lane, st);
 #pragma unroll
         for (int tp = 0; tp < TP; ++tp) {
             if (tp > 0) load_pair(tp);
@@ -668,6 +670,35 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
     }
 }
 
+// The same for K / V in other layouts: a row is gathered head slice by head slice (d contiguous
+// elements each) from the input layout and scattered to the output layout.
+__global__ __launch_bounds__(256) void prefill_compact_strided_kernel(
+    PrefillDims p, const int32_t* __restrict__ src_row,
+    const u32x4* __restrict__ hidden, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    u32x4* __restrict__ hidden_out, uint16_t* __restrict__ k_out, uint16_t* __restrict__ v_out, KvLayout out)
+{
+    const int o = blockIdx.x, b = blockIdx.y;
+    const int rows_cap = p.Rcap + p.N;
+    const int src = src_row[(long)b * rows_cap + o];
+    if (src < 0) return;
+    const int lph = p.d / 8;                             // 16-byte vectors per head slice
+    const int kvn = p.H * lph;
+    const long sbase = (long)b * p.kv.batch + (long)src * p.kv.token;
+    const long dbase = (long)b * out.batch + (long)o * out.token;
+    for (int c = threadIdx.x; c < kvn; c += blockDim.x) {
+        const int h = c / lph, w = c - h * lph;
+        const long so = sbase + (long)h * p.kv.head + w * 8, d_o = dbase + (long)h * out.head + w * 8;
+        const u32x4 a = *reinterpret_cast<const u32x4*>(k + so);
+        const u32x4 c2 = *reinterpret_cast<const u32x4*>(v + so);
+        *reinterpret_cast<u32x4*>(k_out + d_o) = a;
+        *reinterpret_cast<u32x4*>(v_out + d_o) = c2;
+    }
+    const int hv = p.C / 8;
+    const u32x4* hs = hidden + ((long)b * p.L + src) * hv;
+    u32x4* hd = hidden_out + ((long)b * rows_cap + o) * hv;
+    for (int c = threadIdx.x; c < hv; c += blockDim.x) hd[c] = hs[c];
+}
+
 // Prompts of more than 128 text rows: V = sum, I = max over the launches' partial results (group 0 holds the result).
 __global__ __launch_bounds__(256) void prefill_merge_groups_kernel(long n, int groups, float* __restrict__ V, float* __restrict__ I)
 {
@@ -773,7 +804,10 @@ extern "C" size_t mustdrop_prefill_filter_workspace_bytes(int B, int Mv, int N, 
     return carve_prefill(nullptr, B, Mv, N, H, Rcap).bytes;
 }
 
-extern "C" int mustdrop_prefill_filter(
+namespace md {
+namespace {
+
+int prefill_filter_impl(
     const void* q_txt, const void* k, const void* v, const void* hidden,
     const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
     int B, int Mv, int N, int H, int d, int C,
@@ -782,6 +816,7 @@ extern "C" int mustdrop_prefill_filter(
     void* hidden_out, void* k_out, void* v_out,
     int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
     float* score_global, float* score_indiv,
+    const md_kv_layout* q_layout, const md_kv_layout* kv_layout, const md_kv_layout* kv_out_layout,
     void* workspace, size_t workspace_bytes, void* stream)
 {
     clear_error();
@@ -807,10 +842,17 @@ extern "C" int mustdrop_prefill_filter(
     for (const void* ptr : big)
         if (!aligned16(ptr)) return fail(MD_EALIGN, "prefill_filter: tensor pointers must be 16-byte aligned");
     const size_t L = (size_t)Mv + N;
-    const size_t kv_in = (size_t)B * L * H * d * 2, h_in = (size_t)B * L * C * 2;
-    const size_t kv_out = (size_t)B * (Rcap + N) * H * d * 2, h_out = (size_t)B * (Rcap + N) * C * 2;
+    KvLayout lq, lkv, lout;
+    int lrc = read_layout("prefill_filter", "q_txt", q_layout, B, N, H, d, &lq);
+    if (lrc == MD_OK) lrc = read_layout("prefill_filter", "k / v", kv_layout, B, (long)L, H, d, &lkv);
+    if (lrc == MD_OK) lrc = read_layout("prefill_filter", "k_out / v_out", kv_out_layout, B, (long)Rcap + N, H, d, &lout);
+    if (lrc != MD_OK) return lrc;
+    if (lq.token > (1l << 26) || lkv.token > (1l << 26))
+        return fail(MD_ESHAPE, "prefill_filter: token stride above 2^26 elements");
+    const size_t kv_in = layout_extent_bytes(lkv, B, (long)L, H, d), h_in = (size_t)B * L * C * 2;
+    const size_t kv_out = layout_extent_bytes(lout, B, (long)Rcap + N, H, d), h_out = (size_t)B * (Rcap + N) * C * 2;
     const void* ins[] = {k, v, hidden, q_txt};
-    const size_t in_sz[] = {kv_in, kv_in, h_in, (size_t)B * N * H * d * 2};
+    const size_t in_sz[] = {kv_in, kv_in, h_in, layout_extent_bytes(lq, B, N, H, d)};
     const void* outs[] = {k_out, v_out, hidden_out};
     const size_t out_sz[] = {kv_out, kv_out, h_out};
     for (int a = 0; a < 3; ++a)
@@ -823,6 +865,7 @@ extern "C" int mustdrop_prefill_filter(
 
     PrefillDims p;
     p.B = B; p.Mv = Mv; p.N = N; p.H = H; p.d = d; p.C = C; p.L = Mv + N; p.Rcap = Rcap;
+    p.q = lq; p.kv = lkv;
     p.Npad = (N + 31) / 32 * 32;
     p.nch = pick_chunks(B, H, p.L, (p.Npad / 32 + 1) / 2);
     const int tiles = (p.L + 31) / 32;
@@ -849,8 +892,51 @@ extern "C" int mustdrop_prefill_filter(
             w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv);
 #undef MD_PSELECT_FAST
     dim3 gc(Rcap + N, B);
-    MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel), gc, 256, 0, p, src_row,
-        static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
-        static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out));
+    if (is_dense(lkv, (long)L, H, d) && is_dense(lout, (long)Rcap + N, H, d))
+        MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel), gc, 256, 0, p, src_row,
+            static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
+            static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out));
+    else
+        MD_LAUNCH("prefill_compact", st, (prefill_compact_strided_kernel), gc, 256, 0, p, src_row,
+            static_cast<const u32x4*>(hidden), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
+            static_cast<u32x4*>(hidden_out), static_cast<uint16_t*>(k_out), static_cast<uint16_t*>(v_out), lout);
     return check_launch("prefill_filter");
+}
+
+}  // namespace
+}  // namespace md
+
+extern "C" int mustdrop_prefill_filter(
+    const void* q_txt, const void* k, const void* v, const void* hidden,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    int B, int Mv, int N, int H, int d, int C,
+    float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
+    int Rcap,
+    void* hidden_out, void* k_out, void* v_out,
+    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
+    float* score_global, float* score_indiv,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return prefill_filter_impl(q_txt, k, v, hidden, vis_valid, txt_len, is_key, B, Mv, N, H, d, C, softmax_scale, mode,
+                               budget, gamma, alpha, Rcap, hidden_out, k_out, v_out, kept_index, kept_count, out_len,
+                               out_protect, out_ids, score_global, score_indiv, nullptr, nullptr, nullptr,
+                               workspace, workspace_bytes, stream);
+}
+
+extern "C" int mustdrop_prefill_filter_strided(
+    const void* q_txt, const void* k, const void* v, const void* hidden,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    int B, int Mv, int N, int H, int d, int C,
+    float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
+    int Rcap,
+    void* hidden_out, void* k_out, void* v_out,
+    int32_t* kept_index, int32_t* kept_count, int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
+    float* score_global, float* score_indiv,
+    const md_kv_layout* q_layout, const md_kv_layout* kv_layout, const md_kv_layout* kv_out_layout,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return prefill_filter_impl(q_txt, k, v, hidden, vis_valid, txt_len, is_key, B, Mv, N, H, d, C, softmax_scale, mode,
+                               budget, gamma, alpha, Rcap, hidden_out, k_out, v_out, kept_index, kept_count, out_len,
+                               out_protect, out_ids, score_global, score_indiv, q_layout, kv_layout, kv_out_layout,
+                               workspace, workspace_bytes, stream);
 }

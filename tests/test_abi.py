@@ -153,3 +153,55 @@ def test_encode_adaptive_argument_errors(lib):
     assert enc(lam=F(float("nan"))) == 1
     assert enc(cap=-1) == 1
     assert enc(wsb=16) == 5
+
+
+def test_layout_argument_errors(lib):
+    """md_kv_layout is checked on the host: positive multiples of 8 elements, axes nested without overlap."""
+    from paper_2411_10803_amd.binding import KvLayout
+
+    def pre(q=None, kv=None, out=None, **kw):
+        a = dict(k=P(0x2000000), ko=P(0x28000000), wsb=1 << 30)
+        a.update(kw)
+        ref = lambda l: C.byref(l) if l is not None else None
+        return lib.mustdrop_prefill_filter_strided(
+            P(0x1000000), a["k"], P(0x8000000), P(0x10000000), None, None, None, 1, 576, 64, 32, 128, 4096,
+            F(0.088), 0, 192, F(1 / 576), F(2 / 640), 192, P(0x20000000), a["ko"], P(0x30000000), X, X, None, None, None,
+            None, None, ref(q), ref(kv), ref(out), P(0x40000000), C.c_size_t(a["wsb"]), None)
+
+    L, H, d = 640, 32, 128
+    head_major = KvLayout(H * L * d, d, L * d)
+    assert pre(kv=KvLayout(L * H * d, H * d, 0)) == 1 and b"strides" in lib.mustdrop_last_error()
+    assert pre(kv=KvLayout(L * H * d, H * d, d + 4)) == 1                   # not a multiple of 8 elements
+    assert pre(kv=KvLayout(L * H * d, H * d - 8, d)) == 2 and b"overlaps" in lib.mustdrop_last_error()
+    assert pre(kv=KvLayout(L * H * d, d, (L - 1) * d)) == 2                 # head slices overlap in a head-major cache
+    assert pre(q=KvLayout(64 * H * d, 64, d)) == 2
+    assert pre(out=KvLayout(256 * H * d, H * d, 64)) == 2                   # head stride below d
+    assert pre(kv=head_major, wsb=16) == 5                                  # a valid layout gets as far as the workspace check
+    assert pre(kv=KvLayout(1 << 41, H * d, d)) == 1
+    # a padded layout's extent counts for the alias check: 4 KiB beyond the dense extent of k
+    padded = KvLayout(L * (H * d + 4096), H * d + 4096, d)
+    dense_end = 0x2000000 + L * H * d * 2
+    assert pre(kv=padded, ko=P(dense_end + 4096), wsb=16) == 4
+    assert pre(ko=P(dense_end + 4096), wsb=16) == 5
+
+    def dec(lay, fn="evict"):
+        if fn == "evict":
+            return lib.mustdrop_decode_evict_strided(P(0x1000), P(0x10000000), P(0x80000000), X, X, X, X, 2, 4096, 32, 128,
+                                                     F(0.088), F(1.0), 1024, None, None, C.byref(lay), P(0x100000000),
+                                                     C.c_size_t(16), None)
+        return lib.mustdrop_decode_append_strided(None, X, X, X, X, X, X, X, 2, 4096, 32, 128, 5, 1, C.byref(lay), None)
+
+    assert dec(KvLayout(32 * 4096 * 128, 128, 4096 * 128)) == 5             # head-major: valid, stops at the workspace
+    assert dec(KvLayout(32 * 4096 * 128, 128, 4095 * 128)) == 2
+    assert dec(KvLayout(32 * 4096 * 128, -128, 4096 * 128)) == 1
+    assert dec(KvLayout(32 * 4096 * 128, 128, 4096 * 128), "append") == 1   # null k_new
+    lay = KvLayout(32 * 640 * 128, 128, 640 * 128)
+
+    def keep(layer_stride, layers=4):
+        return lib.mustdrop_decode_keep_strided(P(0x10000000), P(0x80000000), X, None, X, X, X, layers, 2, 640, 32, 128,
+                                                None, None, C.byref(lay), C.c_int64(layer_stride), P(0x100000000),
+                                                C.c_size_t(16), None)
+    assert keep(2 * 32 * 640 * 128) == 5
+    assert keep(2 * 32 * 640 * 128 - 8) == 2 and b"layer_stride" in lib.mustdrop_last_error()
+    assert keep(0) == 2
+    assert keep(0, layers=1) == 5                                           # one layer: the stride is not used
