@@ -113,17 +113,25 @@ __device__ __forceinline__ void cls_logits_rows(
     const int gps = cls_groups(p.M);
     if (item >= (long)p.B * gps) return;
     const int b = (int)(item / gps), j0 = (int)(item % gps) * R;
-    bool act[R];                                     // wave-uniform; padding rows are never read
+    // wave-uniform.  Loads are never guarded one by one (a guarded load waits for the one before it):
+    // addresses are clamped into the sample instead and what was read for an inactive row is ignored.
+    bool act[R];
+    uint32_t vbyte[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) vbyte[r] = valid ? valid[(size_t)b * p.M + min(max(j0 + r - 1, 0), p.M - 1)] : 1u;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int j = j0 + r;
-        act[r] = j <= p.M && (j == 0 || !valid || valid[(size_t)b * p.M + (j - 1)]);
+        act[r] = j <= p.M && (j == 0 || vbyte[r] != 0);
     }
 
     const size_t esz = BF ? 2 : 4;
     const char* qrow = static_cast<const char*>(q_cls) + (size_t)b * p.D * esz;
-    const char* krow = static_cast<const char*>(k_cls) + ((size_t)b * (p.M + 1) + j0) * p.D * esz;
     const size_t rowb = (size_t)p.D * esz;
+    const char* kb0 = static_cast<const char*>(k_cls) + (size_t)b * (p.M + 1) * rowb;
+    const char* krow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) krow[r] = kb0 + (size_t)min(j0 + r, p.M) * rowb;
     const int nvec = p.D / VEC, vph = p.dc / VEC;
     const float scale = 1.0f / sqrtf((float)p.dc);
     float* out = logits + (size_t)b * p.Hc * (p.M + 1) + j0;
@@ -141,8 +149,7 @@ __device__ __forceinline__ void cls_logits_rows(
             float qv[VEC], kv[R][VEC];
             Vec<BF>::load(qrow, idx * VEC, qv);
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (act[r]) Vec<BF>::load(krow + r * rowb, idx * VEC, kv[r]);
+            for (int r = 0; r < R; ++r) Vec<BF>::load(krow[r], idx * VEC, kv[r]);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 if (!act[r]) continue;
@@ -192,12 +199,11 @@ __device__ __forceinline__ void window_sim_item(
     const int ok_l = lane < p.ws && (!valid || valid[(size_t)b * p.M + tok_l]);
 #pragma unroll
     for (int m = 0; m < WSM; ++m) {
-        ok[m] = false;
-        rows[m] = nullptr;
-        if (m < p.ws) {
-            ok[m] = wave_member(ok_l, m) != 0;
-            rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + wave_member(tok_l, m)) * p.D * esz;
-        }
+        // every slot gets a readable row (members beyond the window repeat member 0, invalid members
+        // keep their own row): the loads below are unconditional and what they return is zeroed
+        const int mm = m < p.ws ? m : 0;
+        ok[m] = m < p.ws && wave_member(ok_l, mm) != 0;
+        rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + wave_member(tok_l, mm)) * p.D * esz;
     }
     float G[WSM * (WSM + 1) / 2];
 #pragma unroll
@@ -206,9 +212,10 @@ __device__ __forceinline__ void window_sim_item(
     for (int c = lane * VEC; c < p.D; c += kWave * VEC) {
         float v[WSM][VEC];
 #pragma unroll
+        for (int m = 0; m < WSM; ++m) Vec<BF>::load(rows[m], c, v[m]);
+#pragma unroll
         for (int m = 0; m < WSM; ++m) {
-            if (ok[m]) Vec<BF>::load(rows[m], c, v[m]);
-            else {
+            if (!ok[m]) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) v[m][e] = 0.f;
             }
@@ -445,14 +452,24 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     const float* mb = mass_in ? mass_in + (size_t)b * M : nullptr;
 
     // own tokens' state and own windows' similarity: requested first
+    // (clamped addresses, no guarded loads: a guarded load would wait for the one before it)
     bool ok[IPT];
     float mass[IPT], simv[IPT];
+    {
+        uint32_t vbyte[IPT];
 #pragma unroll
-    for (int t = 0; t < IPT; ++t) {
-        const int j = tid + t * 1024;
-        ok[t] = j < M && (!vb || vb[j]);
-        mass[t] = (j < M && mb) ? mb[j] : 1.0f;
-        simv[t] = j < W ? sim[(size_t)b * W + j] : 0.f;
+        for (int t = 0; t < IPT; ++t) vbyte[t] = vb ? vb[min(tid + t * 1024, M - 1)] : 1u;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) mass[t] = mb ? mb[min(tid + t * 1024, M - 1)] : 1.0f;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) simv[t] = sim[(size_t)b * W + min(tid + t * 1024, W - 1)];
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const int j = tid + t * 1024;
+            ok[t] = j < M && vbyte[t] != 0;
+            if (j >= M) mass[t] = 1.0f;
+            if (j >= W) simv[t] = 0.f;
+        }
     }
     bool sel[IPT];
 #pragma unroll
@@ -474,12 +491,24 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
             const float* l = lg + (size_t)h * (M + 1);
             float mx = -INFINITY, z = 0.f;
             for (int j0 = lane; j0 <= M; j0 += 16 * kWave) {
+                // all 16 logits (and validity bytes) are requested before any is used: clamped
+                // addresses instead of guarded loads, which would each wait for the one before
                 float x[16];
+                uint32_t vv[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) x[u] = l[min(j0 + u * kWave, M)];
+                if (vb) {
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) vv[u] = vb[min(max(j0 + u * kWave - 1, 0), M - 1)];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) vv[u] = 1u;
+                }
                 float bm = -INFINITY;
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
                     const int j = j0 + u * kWave;
-                    x[u] = (j <= M && (j == 0 || !vb || vb[j - 1])) ? l[j] * kLog2eE : -INFINITY;
+                    x[u] = (j <= M && (j == 0 || vv[u] != 0)) ? x[u] * kLog2eE : -INFINITY;
                     bm = fmaxf(bm, x[u]);
                 }
                 const float mn = fmaxf(mx, bm);
@@ -502,21 +531,27 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         for (int t = 0; t < IPT; ++t) {
             const int j = tid + t * 1024;
             float a = -INFINITY;
-            if (ok[t] && pre) {
-                a = 0.f;
+            if (pre) {
+                if (ok[t]) {
+                    a = 0.f;
 #pragma unroll
-                for (int u = 0; u < PRE; ++u)
-                    if (u < p.Hc) a += fast_exp2(fmaf(xl[u], kLog2eE, -s_max[u])) * s_inv[u];
-            } else if (ok[t]) {
-                a = 0.f;
+                    for (int u = 0; u < PRE; ++u)
+                        if (u < p.Hc) a += fast_exp2(fmaf(xl[u], kLog2eE, -s_max[u])) * s_inv[u];
+                }
+            } else {
+                // unguarded loads at a clamped token, eight heads in flight; the sum of a token that is
+                // not there is dropped afterwards
+                const int jc = min(j, M - 1);
+                float acc = 0.f;
                 for (int h0 = 0; h0 < p.Hc; h0 += 8) {
                     float x[8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) x[u] = h0 + u < p.Hc ? lg[(size_t)(h0 + u) * (M + 1) + j + 1] : 0.f;
+                    for (int u = 0; u < 8; ++u) x[u] = lg[(size_t)min(h0 + u, p.Hc - 1) * (M + 1) + jc + 1];
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
-                        if (h0 + u < p.Hc) a += fast_exp2(fmaf(x[u], kLog2eE, -s_max[h0 + u])) * s_inv[h0 + u];
+                        if (h0 + u < p.Hc) acc += fast_exp2(fmaf(x[u], kLog2eE, -s_max[h0 + u])) * s_inv[h0 + u];
                 }
+                if (ok[t]) a = acc;
             }
             if (j < M && a_cls_out) a_cls_out[(size_t)b * M + j] = a;
             rk[t] = ok[t] ? rank_key(a, j) : 0ull;
@@ -576,19 +611,32 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         bool has_key = false;
         float total = 0.f;
         const int base = window_base(p, w);
-        for (int m = 0; m < p.ws; ++m) {
-            const int tok = base + s_moff[m];
-            if (vb && !vb[tok]) continue;
-            ++n;
-            if (first < 0) first = tok;
-            has_key |= s_key[tok] != 0;
-            total += mb ? mb[tok] : 1.0f;
+        uint32_t vmask = 0;                          // bit m: member m is valid
+        for (int m0 = 0; m0 < p.ws; m0 += 4) {       // four members' flags and masses in flight
+            uint32_t vv[4];
+            float mm[4];
+            int tk[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) tk[u] = base + s_moff[min(m0 + u, p.ws - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vv[u] = vb ? vb[tk[u]] : 1u;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) mm[u] = mb ? mb[tk[u]] : 1.0f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (m0 + u >= p.ws || vv[u] == 0) continue;
+                vmask |= 1u << (m0 + u);
+                ++n;
+                if (first < 0) first = tk[u];
+                has_key |= s_key[tk[u]] != 0;
+                total += mm[u];
+            }
         }
         const bool mg = n >= 2 && !has_key && simv[t] > tau;
         if (mg) {
             for (int m = 0; m < p.ws; ++m) {
+                if (!((vmask >> m) & 1u)) continue;
                 const int tok = base + s_moff[m];
-                if (vb && !vb[tok]) continue;
                 s_state[tok] = tok == first ? 1 : 2;
             }
             s_tmass[first] = total;
@@ -673,8 +721,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
             for (int c = lane; c < nchunk; c += kWave) {
                 u32x4 v[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (okm[u]) v[u] = __builtin_nontemporal_load(src[u] + c);
+                for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src[u] + c);   // unguarded: all in flight
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     if (okm[u]) __builtin_nontemporal_store(v[u], dst[u] + c);
@@ -702,7 +749,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
                 const int m = min(m0 + u, p.ws - 1);
                 okm[u] = m0 + u < p.ws && ((okmask >> m) & 1ull);
                 mm[u] = __builtin_bit_cast(float, wave_member(__builtin_bit_cast(int, mass_l), m));
-                if (okm[u]) Vec<BF>::load_once(xb + (size_t)wave_member(tok_l, m) * rowb, c, v[u]);
+                Vec<BF>::load_once(xb + (size_t)wave_member(tok_l, m) * rowb, c, v[u]);      // unguarded, see above
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
