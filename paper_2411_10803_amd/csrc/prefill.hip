@@ -557,14 +557,24 @@ __global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
     const int rows_cap = p.Rcap + p.N;
     float v[IPT], iv[IPT];
     bool ok[IPT], key[IPT];
+    {
+        // every load at a clamped address and none guarded by another's result: one round trip
+        uint32_t vv[IPT], kk[IPT];
 #pragma unroll
-    for (int t = 0; t < IPT; ++t) {
-        const int j = tid + t * 1024;
-        const bool in = j < Mv;
-        v[t] = in ? V[(long)b * Mv + j] : 0.f;
-        iv[t] = in ? I[(long)b * Mv + j] : 0.f;
-        ok[t] = in && (!vis_valid || vis_valid[(long)b * Mv + j]);
-        key[t] = ok[t] && is_key && is_key[(long)b * Mv + j];
+        for (int t = 0; t < IPT; ++t) v[t] = V[(long)b * Mv + min(tid + t * 1024, Mv - 1)];
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) iv[t] = I[(long)b * Mv + min(tid + t * 1024, Mv - 1)];
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) vv[t] = vis_valid ? vis_valid[(long)b * Mv + min(tid + t * 1024, Mv - 1)] : 1u;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) kk[t] = is_key ? is_key[(long)b * Mv + min(tid + t * 1024, Mv - 1)] : 0u;
+#pragma unroll
+        for (int t = 0; t < IPT; ++t) {
+            const bool in = tid + t * 1024 < Mv;
+            if (!in) { v[t] = 0.f; iv[t] = 0.f; }
+            ok[t] = in && vv[t] != 0;
+            key[t] = ok[t] && kk[t] != 0;
+        }
     }
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
     // G = sum of V_j over valid vision tokens (Eq. 9, right-hand side); fixed summation tree
