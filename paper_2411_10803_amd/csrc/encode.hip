@@ -209,27 +209,40 @@ __device__ __forceinline__ void window_sim_item(
 #pragma unroll
     for (int i = 0; i < WSM * (WSM + 1) / 2; ++i) G[i] = 0.f;
 
-    for (int c = lane * VEC; c < p.D; c += kWave * VEC) {
-        float v[WSM][VEC];
+    // small windows take two slices of the feature dimension per round (2*WSM loads in flight)
+    constexpr int NS = WSM <= 4 ? 2 : 1;
+    for (int c0 = lane * VEC; c0 < p.D; c0 += NS * kWave * VEC) {
+        float v[NS][WSM][VEC];
+        bool in[NS];
 #pragma unroll
-        for (int m = 0; m < WSM; ++m) Vec<BF>::load(rows[m], c, v[m]);
+        for (int q = 0; q < NS; ++q) {
+            const int c = c0 + q * kWave * VEC;
+            in[q] = c < p.D;
 #pragma unroll
-        for (int m = 0; m < WSM; ++m) {
-            if (!ok[m]) {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) v[m][e] = 0.f;
-            }
+            for (int m = 0; m < WSM; ++m) Vec<BF>::load(rows[m], in[q] ? c : c0, v[q][m]);
         }
-        int idx = 0;
 #pragma unroll
-        for (int m = 0; m < WSM; ++m)
+        for (int q = 0; q < NS; ++q)
 #pragma unroll
-            for (int n = m; n < WSM; ++n) {
-                float s = G[idx];
+            for (int m = 0; m < WSM; ++m) {
+                if (!ok[m] || !in[q]) {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) s = fmaf(v[m][e], v[n][e], s);
-                G[idx++] = s;
+                    for (int e = 0; e < VEC; ++e) v[q][m][e] = 0.f;
+                }
             }
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            int idx = 0;
+#pragma unroll
+            for (int m = 0; m < WSM; ++m)
+#pragma unroll
+                for (int n = m; n < WSM; ++n) {
+                    float s = G[idx];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) s = fmaf(v[q][m][e], v[q][n][e], s);
+                    G[idx++] = s;
+                }
+        }
     }
 #pragma unroll
     for (int i = 0; i < WSM * (WSM + 1) / 2; ++i) G[i] = wave_sum(G[i]);
