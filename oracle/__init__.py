@@ -59,7 +59,7 @@ def encode_merge(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid,
         Hc, dc = q_cls.shape[1], q_cls.shape[2]
     else:
         Hc, dc = 1, D
-    W = (T // kt) * (Hg // kh) * (Wg // kw)
+    W = -(-T // kt) * -(-Hg // kh) * -(-Wg // kw)        # border windows are clipped to the grid
     out = {
         "out_x": np.zeros((B, M, D), dtype=_stored_dtype(x_dtype)),
         "out_index": np.full((B, M), -1, dtype=np.int32),
@@ -92,7 +92,7 @@ def encode_merge_adaptive(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid,
     B, M, D = x.shape
     assert M == T * Hg * Wg
     Hc, dc = q_cls.shape[1], q_cls.shape[2]
-    W = (T // kt) * (Hg // kh) * (Wg // kw)
+    W = -(-T // kt) * -(-Hg // kh) * -(-Wg // kw)        # border windows are clipped to the grid
     out = {
         "out_x": np.zeros((B, M, D), dtype=_stored_dtype(x_dtype)),
         "out_index": np.full((B, M), -1, dtype=np.int32),

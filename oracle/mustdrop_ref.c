@@ -103,14 +103,17 @@ static int encode_merge_core(
     double* a_cls_out, double* window_sim_out)
 {
     if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || D <= 0) return REF_EINVAL;
-    if (kt <= 0 || kh <= 0 || kw <= 0 || T % kt || Hg % kh || Wg % kw) return REF_EINVAL;
+    if (kt <= 0 || kh <= 0 || kw <= 0) return REF_EINVAL;
     const int M = T * Hg * Wg;
     if (key_budget < 0 || (key_mode == 0 && key_budget > M)) return REF_EINVAL;
     const int with_keys = key_mode == 1 || key_budget > 0;
     if (with_keys && (!q_cls || !k_cls || Hc <= 0 || dc <= 0)) return REF_EINVAL;
     if (key_mode == 1 && !key_count) return REF_EINVAL;
     const int ws = kt * kh * kw;
-    const int nwt = T / kt, nwy = Hg / kh, nwx = Wg / kw;
+    /* Sec. 3.3 tiles the grid with windows of one size; where the window does not divide the grid, the
+       windows at the far border are clipped to the grid and hold fewer tokens (a window left with fewer
+       than two valid tokens is never merged, like any other). */
+    const int nwt = (T + kt - 1) / kt, nwy = (Hg + kh - 1) / kh, nwx = (Wg + kw - 1) / kw;
     const int W = nwt * nwy * nwx;
 
     double* a_cls = (double*)malloc(sizeof(double) * (size_t)M);
@@ -193,6 +196,7 @@ static int encode_merge_core(
             for (int dt = 0; dt < kt; ++dt)
             for (int dy = 0; dy < kh; ++dy)
             for (int dx = 0; dx < kw; ++dx) {
+                if (wt * kt + dt >= T || wy * kh + dy >= Hg || wx * kw + dx >= Wg) continue;   /* clipped */
                 int tok = ((wt * kt + dt) * Hg + (wy * kh + dy)) * Wg + (wx * kw + dx);
                 if (vb && !vb[tok]) continue;
                 mem[n++] = tok;
@@ -244,6 +248,7 @@ static int encode_merge_core(
                 for (int dt = 0; dt < kt; ++dt)
                 for (int dy = 0; dy < kh; ++dy)
                 for (int dx = 0; dx < kw; ++dx) {
+                    if (wt * kt + dt >= T || wy * kh + dy >= Hg || wx * kw + dx >= Wg) continue;
                     int t2 = ((wt * kt + dt) * Hg + (wy * kh + dy)) * Wg + (wx * kw + dx);
                     if (vb && !vb[t2]) continue;
                     double mm = mb ? (double)mb[t2] : 1.0;

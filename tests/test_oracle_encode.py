@@ -106,11 +106,12 @@ def brute_encode(x, T, Hg, Wg, kt, kh, kw, tau, keys, mass, valid):
     """Pure-Python enumeration of windows, pairs and merges for one sample (float64 lists)."""
     M, D = len(x), len(x[0])
     merged_into = {}
-    for wt in range(T // kt):
-        for wy in range(Hg // kh):
-            for wx in range(Wg // kw):
+    for wt in range(-(-T // kt)):
+        for wy in range(-(-Hg // kh)):
+            for wx in range(-(-Wg // kw)):
                 mem = [((wt * kt + dt) * Hg + wy * kh + dy) * Wg + wx * kw + dx
-                       for dt in range(kt) for dy in range(kh) for dx in range(kw)]
+                       for dt in range(kt) for dy in range(kh) for dx in range(kw)
+                       if wt * kt + dt < T and wy * kh + dy < Hg and wx * kw + dx < Wg]      # border windows are clipped
                 mem = [m for m in mem if valid[m]]
                 if len(mem) < 2 or any(m in keys for m in mem):
                     continue
@@ -137,7 +138,7 @@ def brute_encode(x, T, Hg, Wg, kt, kh, kw, tau, keys, mass, valid):
     return rows
 
 
-@pytest.mark.parametrize("T,Hg,Wg,kt", [(1, 6, 6, 1), (2, 4, 6, 2)])
+@pytest.mark.parametrize("T,Hg,Wg,kt", [(1, 6, 6, 1), (2, 4, 6, 2), (1, 5, 7, 1), (3, 3, 5, 2)])
 def test_brute_force_tiny_grids(T, Hg, Wg, kt):
     rng = np.random.default_rng(11 + T)
     M, D = T * Hg * Wg, 8
@@ -165,6 +166,54 @@ def test_brute_force_tiny_grids(T, Hg, Wg, kt):
         assert o["out_valid"][b].tolist() == [1] * n + [0] * (M - n)
     assert n_merged_total > 0          # the case does merge something
     assert (o["window_sim"] <= tau).any()  # ... and leaves something unmerged
+
+
+def test_grid_the_window_does_not_divide_equals_the_padded_grid():
+    """A grid that the window does not divide behaves like the next larger grid that it does divide, with
+    the added cells marked as padding (clipped border windows hold fewer tokens)."""
+    rng = np.random.default_rng(23)
+    T, Hg, Wg, kt, kh, kw, D = 3, 5, 7, 2, 2, 3, 16
+    Tp, Hp, Wp = 4, 6, 9
+    M, Mp = T * Hg * Wg, Tp * Hp * Wp
+    base = rng.standard_normal((1, 1, D))
+    x = (base + 0.5 * rng.standard_normal((2, M, D))).astype(np.float32)
+    mass = rng.integers(1, 4, size=(2, M)).astype(np.float32)
+    valid = (rng.random((2, M)) > 0.1).astype(np.uint8)
+    # the same tokens placed in the padded grid; pad cells hold garbage and are invalid
+    pos = np.array([((t * Hp) + y) * Wp + xx for t in range(T) for y in range(Hg) for xx in range(Wg)])
+    xp = np.full((2, Mp, D), np.nan, np.float32)
+    mp = np.full((2, Mp), 7.0, np.float32)
+    vp = np.zeros((2, Mp), np.uint8)
+    xp[:, pos], mp[:, pos], vp[:, pos] = x, mass, valid
+    k = rng.standard_normal((2, 1 + M, 2, 8)).astype(np.float32)
+    q = rng.standard_normal((2, 2, 8)).astype(np.float32)
+    kp = np.full((2, 1 + Mp, 2, 8), np.nan, np.float32)
+    kp[:, 0], kp[:, 1 + pos] = k[:, 0], k[:, 1:]
+    sims = np.sort(run(x, T, Hg, Wg, kt, kh, kw, tau=2.0, valid=valid)["window_sim"].ravel())
+    tau = float(0.5 * (sims[len(sims) // 2 - 1] + sims[len(sims) // 2]))
+    a = run(x, T, Hg, Wg, kt, kh, kw, tau=tau, key_budget=4, q=q, k=k, mass=mass, valid=valid)
+    b = run(xp, Tp, Hp, Wp, kt, kh, kw, tau=tau, key_budget=4, q=q, k=kp, mass=mp, valid=vp)
+    assert a["window_sim"].shape == b["window_sim"].shape == (2, 2 * 3 * 3)
+    assert np.array_equal(a["window_sim"], b["window_sim"])
+    assert np.array_equal(a["out_count"], b["out_count"]) and (a["out_count"] < valid.sum(1)).all()
+    for s in range(2):
+        n = a["out_count"][s]
+        assert np.array_equal(pos[a["out_index"][s, :n]], b["out_index"][s, :n])
+        assert np.array_equal(pos[a["key_index"][s]], b["key_index"][s])
+        for name in ("out_mass", "out_is_key", "out_x"):
+            assert np.array_equal(a[name][s, :n], b[name][s, :n]), name
+
+
+def test_window_wider_than_the_grid_is_one_clipped_window():
+    # 1 x 3 x 3 grid under a 1 x 4 x 4 window: a single window of nine tokens, 36 pairs
+    rng = np.random.default_rng(29)
+    from sklearn.metrics.pairwise import cosine_similarity
+    x = rng.standard_normal((1, 9, 12)).astype(np.float32)
+    o = run(x, 1, 3, 3, 1, 4, 4, tau=-2.0)
+    assert o["window_sim"].shape == (1, 1) and o["out_count"][0] == 1 and o["out_mass"][0, 0] == 9.0
+    cs = cosine_similarity(x[0].astype(np.float64))
+    assert o["window_sim"][0, 0] == pytest.approx(cs[np.triu_indices(9, 1)].mean(), abs=1e-12)
+    assert np.allclose(o["out_x"][0, 0], x[0].astype(np.float64).mean(0), rtol=1e-6)
 
 
 # ---------------------------------------------------------------- invariants
