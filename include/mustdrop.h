@@ -60,8 +60,9 @@ int mustdrop_version(void);
  * the softmax running over all 1+M keys (key 0 is the [CLS] key, whose own probability is
  * discarded).  The key set O is the `key_budget` valid tokens with the largest a_cls (ties: lower
  * index).  Local Spatial Merging (Eq. 5): the T x Hg x Wg grid is cut into non-overlapping
- * kt x kh x kw windows; S = mean over unordered member pairs of their cosine similarity (zero-norm
- * member: cosine 0).  A window merges iff S > tau, it has at least two valid members and none of
+ * kt x kh x kw windows (where the window does not divide the grid, the windows at the far border are
+ * clipped to the grid and hold fewer tokens); S = mean over unordered member pairs of their cosine
+ * similarity (zero-norm member: cosine 0).  A window merges iff S > tau, it has at least two valid members and none of
  * them is in O; its members are replaced by one token: the mass-weighted mean of the members, with
  * mass = sum of member masses, at the position of the lowest member index.  Survivors are written
  * in ascending original index.
@@ -77,11 +78,11 @@ int mustdrop_version(void);
  *   out_index, out_mass, out_is_key [B, M]; out_valid [B, M] u8 (1 for slots < out_count[b]; may be NULL)
  *   out_count  [B]
  *   key_index  [B, key_budget] ascending, padded with -1 if fewer valid tokens exist
- *   a_cls_out  [B, M] f32 or NULL;  window_sim_out [B, W] f32 or NULL (W = M / ws)
+ *   a_cls_out  [B, M] f32 or NULL;  window_sim_out [B, W] f32 or NULL,
+ *              W = ceil(T/kt)*ceil(Hg/kh)*ceil(Wg/kw), window index = (wt*ceil(Hg/kh) + wy)*ceil(Wg/kw) + wx
  *
  * Limits: kt*kh*kw <= 16; D*elt and dc*elt multiples of 16 bytes.
- * Errors: MD_EINVAL, MD_ESHAPE (grid not divisible by the window, window too large, Hc*dc
- * unusable), MD_EALIGN, MD_EALIAS (out_x overlaps x), MD_EWORKSPACE, MD_EDTYPE, MD_EHIP.
+ * Errors: MD_EINVAL, MD_ESHAPE (window too large, Hc*dc unusable), MD_EALIGN, MD_EALIAS (out_x overlaps x), MD_EWORKSPACE, MD_EDTYPE, MD_EHIP.
  */
 size_t mustdrop_encode_merge_workspace_bytes(int B, int T, int Hg, int Wg, int Hc, int kt, int kh, int kw);
 

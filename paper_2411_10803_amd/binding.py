@@ -133,7 +133,7 @@ def mustdrop_encode_merge(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, kt, kh, kw
         qk_dtype = _dtype_code(q_cls)
     else:
         Hc, dc, qk_dtype = 1, D, _dtype_code(x)
-    W = M // (kt * kh * kw)
+    W = -(-T // kt) * -(-Hg // kh) * -(-Wg // kw)          # border windows are clipped to the grid
     if out is None:
         out = {
             "out_x": torch.zeros_like(x),
@@ -168,7 +168,7 @@ def mustdrop_encode_merge_adaptive(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, k
     B, M, D = x.shape
     dev = x.device
     Hc, dc = q_cls.shape[1], q_cls.shape[2]
-    W = M // (kt * kh * kw)
+    W = -(-T // kt) * -(-Hg // kh) * -(-Wg // kw)          # border windows are clipped to the grid
     if out is None:
         out = {
             "out_x": torch.zeros_like(x),

@@ -26,12 +26,19 @@ struct EncodeDims {
     int B, T, Hg, Wg, D, Hc, dc;
     int kt, kh, kw;
     int M, W, ws, nwx, nwy, nwt;
+    int clipped;      // the window does not divide the grid: windows at the far border hold fewer tokens
 };
 
+// Token of member m of window w; -1 for a member that a clipped border window does not have.
 __device__ __forceinline__ int member_token(const EncodeDims& p, int w, int m) {
     const int wx = w % p.nwx, wy = (w / p.nwx) % p.nwy, wt = w / (p.nwx * p.nwy);
     const int dx = m % p.kw, dy = (m / p.kw) % p.kh, dt = m / (p.kw * p.kh);
-    return ((wt * p.kt + dt) * p.Hg + (wy * p.kh + dy)) * p.Wg + (wx * p.kw + dx);
+    const int t = wt * p.kt + dt, y = wy * p.kh + dy, x = wx * p.kw + dx;
+    if (p.clipped && (t >= p.T || y >= p.Hg || x >= p.Wg)) return -1;
+    return (t * p.Hg + y) * p.Wg + x;
+}
+__device__ __forceinline__ bool member_in_grid(const EncodeDims& p, int w, int m) {
+    return !p.clipped || member_token(p, w, m) >= 0;
 }
 // member_token(p, w, m) = window_base(p, w) + member_offset(p, m)
 __device__ __forceinline__ int window_base(const EncodeDims& p, int w) {
@@ -196,14 +203,14 @@ __device__ __forceinline__ void window_sim_item(
     const char* rows[WSM];
     bool ok[WSM];
     const int tok_l = lane_member_token(p, w, lane);
-    const int ok_l = lane < p.ws && (!valid || valid[(size_t)b * p.M + tok_l]);
+    const int ok_l = lane < p.ws && tok_l >= 0 && (!valid || valid[(size_t)b * p.M + max(tok_l, 0)]);
 #pragma unroll
     for (int m = 0; m < WSM; ++m) {
         // every slot gets a readable row (members beyond the window repeat member 0, invalid members
         // keep their own row): the loads below are unconditional and what they return is zeroed
         const int mm = m < p.ws ? m : 0;
         ok[m] = m < p.ws && wave_member(ok_l, mm) != 0;
-        rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + wave_member(tok_l, mm)) * p.D * esz;
+        rows[m] = static_cast<const char*>(x) + ((size_t)b * p.M + max(wave_member(tok_l, mm), 0)) * p.D * esz;
     }
     float G[WSM * (WSM + 1) / 2];
 #pragma unroll
@@ -386,7 +393,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
         bool has_key = false;
         for (int m = 0; m < p.ws; ++m) {
             const int tok = member_token(p, w, m);
-            if (vb && !vb[tok]) continue;
+            if (tok < 0 || (vb && !vb[tok])) continue;
             ++n;
             has_key |= iskey_b[tok] != 0;
         }
@@ -412,7 +419,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
                 int first = -1;
                 for (int m = 0; m < p.ws; ++m) {
                     const int tok = member_token(p, w, m);
-                    if (vb && !vb[tok]) continue;
+                    if (tok < 0 || (vb && !vb[tok])) continue;
                     if (first < 0) first = tok;
                     mass += mb ? mb[tok] : 1.0f;
                 }
@@ -629,10 +636,17 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
             uint32_t vv[4];
             float mm[4];
             int tk[4];
+            bool inb[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) tk[u] = base + s_moff[min(m0 + u, p.ws - 1)];
+            for (int u = 0; u < 4; ++u) {
+                const int m = min(m0 + u, p.ws - 1);
+                inb[u] = member_in_grid(p, w, m);
+                tk[u] = inb[u] ? base + s_moff[m] : base;        // the window's first token is always there
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u) vv[u] = vb ? vb[tk[u]] : 1u;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) if (!inb[u]) vv[u] = 0u;
 #pragma unroll
             for (int u = 0; u < 4; ++u) mm[u] = mb ? mb[tk[u]] : 1.0f;
 #pragma unroll
@@ -713,7 +727,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
     // lane m < ws: token, validity, destination row and mass of member m, all requested at once
     const int is_merged = wmerged[(size_t)b * p.W + w];
     const int tok_l = lane_member_token(p, w, lane);
-    const int ok_l = lane < p.ws && (!vb || vb[tok_l]);
+    const int ok_l = lane < p.ws && tok_l >= 0 && (!vb || vb[max(tok_l, 0)]);
     const int pos_l = ok_l ? dst_b[tok_l] : -1;
     const float mass_l = ok_l ? (mb ? mb[tok_l] : 1.0f) : 0.f;
     const int nchunk = (int)(rowb / 16);
@@ -728,7 +742,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
             for (int u = 0; u < 4; ++u) {
                 const int m = min(m0 + u, p.ws - 1);
                 okm[u] = m0 + u < p.ws && wave_member(ok_l, m) != 0;
-                src[u] = reinterpret_cast<const u32x4*>(xb + (size_t)wave_member(tok_l, m) * rowb);
+                src[u] = reinterpret_cast<const u32x4*>(xb + (size_t)max(wave_member(tok_l, m), 0) * rowb);
                 dst[u] = reinterpret_cast<u32x4*>(ob + (size_t)max(wave_member(pos_l, m), 0) * rowb);
             }
             for (int c = lane; c < nchunk; c += kWave) {
@@ -762,7 +776,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
                 const int m = min(m0 + u, p.ws - 1);
                 okm[u] = m0 + u < p.ws && ((okmask >> m) & 1ull);
                 mm[u] = __builtin_bit_cast(float, wave_member(__builtin_bit_cast(int, mass_l), m));
-                Vec<BF>::load_once(xb + (size_t)wave_member(tok_l, m) * rowb, c, v[u]);      // unguarded, see above
+                Vec<BF>::load_once(xb + (size_t)max(wave_member(tok_l, m), 0) * rowb, c, v[u]);   // unguarded, see above
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -812,8 +826,8 @@ using namespace md;
 extern "C" size_t mustdrop_encode_merge_workspace_bytes(int B, int T, int Hg, int Wg, int Hc, int kt, int kh, int kw) {
     if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || kt <= 0 || kh <= 0 || kw <= 0) return 0;
     const long M = (long)T * Hg * Wg;
-    const long W = M / ((long)kt * kh * kw);
-    return carve_encode(nullptr, B, (int)M, (int)(W > 0 ? W : 1), Hc).bytes;
+    const long W = (long)((T + kt - 1) / kt) * ((Hg + kh - 1) / kh) * ((Wg + kw - 1) / kw);
+    return carve_encode(nullptr, B, (int)M, (int)W, Hc).bytes;
 }
 
 namespace md {
@@ -836,13 +850,12 @@ int encode_merge_impl(
     if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || D <= 0)
         return fail(MD_EINVAL, "encode_merge: B, T, Hg, Wg, D must be positive (got %d %d %d %d %d)", B, T, Hg, Wg, D);
     if (kt <= 0 || kh <= 0 || kw <= 0) return fail(MD_EINVAL, "encode_merge: window sizes must be positive");
-    if (T % kt || Hg % kh || Wg % kw)
-        return fail(MD_ESHAPE, "encode_merge: grid %dx%dx%d is not divisible by window %dx%dx%d", T, Hg, Wg, kt, kh, kw);
     const long ws_l = (long)kt * kh * kw;
     if (ws_l > kMaxWindow) return fail(MD_ESHAPE, "encode_merge: window of %ld tokens exceeds the limit of %d", ws_l, kMaxWindow);
     const long M_l = (long)T * Hg * Wg;
     if (M_l > (1l << 24) || (long)B * M_l > (1l << 30)) return fail(MD_ESHAPE, "encode_merge: too many tokens");
-    const int M = (int)M_l, ws = (int)ws_l, W = M / ws;
+    const int nwt = (T + kt - 1) / kt, nwy = (Hg + kh - 1) / kh, nwx = (Wg + kw - 1) / kw;   // border windows are clipped
+    const int M = (int)M_l, ws = (int)ws_l, W = nwt * nwy * nwx;
     if (key_budget < 0 || (!key_adaptive && key_budget > M))
         return fail(MD_EINVAL, "encode_merge: key_budget %d outside [0, %d]", key_budget, M);
     if (key_adaptive && (std::isnan(key_lambda) || !key_count))
@@ -877,7 +890,8 @@ int encode_merge_impl(
     EncodeDims p;
     p.B = B; p.T = T; p.Hg = Hg; p.Wg = Wg; p.D = D; p.Hc = with_keys ? Hc : 0; p.dc = dc;
     p.kt = kt; p.kh = kh; p.kw = kw; p.M = M; p.W = W; p.ws = ws;
-    p.nwx = Wg / kw; p.nwy = Hg / kh; p.nwt = T / kt;
+    p.nwx = nwx; p.nwy = nwy; p.nwt = nwt;
+    p.clipped = (T % kt || Hg % kh || Wg % kw) ? 1 : 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     const long items = (long)B * W + (with_keys ? (long)B * cls_groups(M) : 0);

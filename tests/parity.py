@@ -47,7 +47,7 @@ def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget
     key_index; a token is decisive iff |a_cls - mu| > 1e-3 * |mu|."""
     B, M, D = x.shape
     ws = kt * kh * kw
-    nwx, nwy = Wg // kw, Hg // kh
+    nwx, nwy = -(-Wg // kw), -(-Hg // kh)          # border windows are clipped to the grid
     tau64 = float(np.float32(tau))
     summary = {"ambiguous_windows": 0, "ambiguous_keys": 0, "max_sim_err": 0.0, "max_acls_rel": 0.0,
                "max_feat_rel": 0.0, "merged_rows_checked": 0, "copied_rows_checked": 0}
@@ -104,7 +104,7 @@ def check_encode(g, o, x, x_dtype, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget
                     amb_tok[j] = True
             summary["ambiguous_keys"] += int((~dec).sum())
         # ambiguous windows: similarity inside the margin band, or holding a non-decisive key candidate
-        W = M // ws
+        W = -(-T // kt) * nwy * nwx
         amb_w = np.abs(o["window_sim"][b] - tau64) <= MARGIN
         for j in np.flatnonzero(amb_tok):
             amb_w[window_of(int(j))] = True

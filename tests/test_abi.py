@@ -35,6 +35,9 @@ def test_workspace_sizes_are_host_arithmetic(lib):
     b = lib.mustdrop_encode_merge_workspace_bytes(32, 1, 24, 24, 16, 1, 2, 2)
     assert 0 < a < b and a % 256 == 0
     assert lib.mustdrop_encode_merge_workspace_bytes(0, 1, 24, 24, 16, 1, 2, 2) == 0
+    # 27 x 27 under 2 x 2 windows: 14 x 14 windows (the border ones clipped), more than 27*27 // 4
+    assert (lib.mustdrop_encode_merge_workspace_bytes(1, 1, 27, 27, 16, 1, 2, 2)
+            > lib.mustdrop_encode_merge_workspace_bytes(1, 1, 26, 26, 16, 1, 2, 2))
     assert lib.mustdrop_prefill_filter_workspace_bytes(16, 576, 64, 32, 192) > 0
     assert lib.mustdrop_decode_evict_workspace_bytes(64, 4352, 32) >= 64 * 4352 * 32 * 4
 
@@ -60,7 +63,7 @@ def test_encode_argument_errors(lib):
     assert encode(lib, x=None) == E["EINVAL"] and b"required" in lib.mustdrop_last_error()
     assert encode(lib, B=0) == E["EINVAL"]
     assert encode(lib, x_dtype=7) == E["EDTYPE"]
-    assert encode(lib, Hg=25) == E["ESHAPE"] and b"divisible" in lib.mustdrop_last_error()
+    assert encode(lib, Hg=25, wsb=1024) == E["EWORKSPACE"]                      # a grid the window does not divide is accepted
     assert encode(lib, kh=8, kw=3, Hg=24, Wg=24) == E["ESHAPE"]                 # 24-token window > limit
     assert encode(lib, key_budget=-1) == E["EINVAL"]
     assert encode(lib, key_budget=577) == E["EINVAL"]

@@ -91,6 +91,30 @@ def test_window_shapes(kt, kh, kw):
         assert np.all(g["out_count"] == cfg.M)
 
 
+@pytest.mark.parametrize("T,Hg,Wg,kt,kh,kw,bf16", [
+    (1, 27, 27, 1, 2, 2, True),      # a 27 x 27 patch grid under 2 x 2 windows: clipped last row and column
+    (3, 7, 10, 2, 2, 4, False),      # clipped in all three directions
+    (1, 5, 3, 1, 3, 4, False),       # window wider than the grid
+    (5, 6, 6, 2, 2, 2, True),        # odd number of frames under frame pairs
+    (1, 40, 33, 1, 2, 2, True),      # more than 1024 tokens: two rounds per thread in the decision kernel
+])
+def test_grids_the_window_does_not_divide(T, Hg, Wg, kt, kh, kw, bf16):
+    cfg = wl.tiny(wl.CONFIGS[4], B=3, T=T, Hg=Hg, Wg=Wg, D=128, Hc=2, dc=64, kt=kt, kh=kh, kw=kw, key_budget=5,
+                  x_dtype=wl.BF16 if bf16 else wl.F32)
+    tau = median_tau(cfg)
+    rng = np.random.default_rng(T * 100 + Hg)
+    run_cfg(cfg, tau=tau)
+    valid = (rng.random((cfg.B, cfg.M)) > 0.2).astype(np.uint8)
+    mass = rng.integers(1, 5, size=(cfg.B, cfg.M)).astype(np.float32)
+    run_cfg(cfg, tau=tau, valid=valid, mass=mass)
+    run_cfg(cfg, tau=tau, valid=valid, mass=mass, key_budget=0)
+    # every window merges: one survivor per window (all of them hold at least one token)
+    g, o, s = run_cfg(cfg, tau=-2.0, key_budget=0)
+    W = -(-T // kt) * -(-Hg // kh) * -(-Wg // kw)
+    assert (g["out_count"] == W).all() and g["window_sim"].shape == (cfg.B, W)
+    assert np.allclose(g["out_mass"][:, :W].sum(1), cfg.M)
+
+
 def test_special_cases_and_key_budget_edges():
     from paper_2411_10803_amd import harness
     # constant image: everything merges; orthogonal tokens: nothing does

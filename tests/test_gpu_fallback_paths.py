@@ -11,10 +11,11 @@ from parity import check_decode, check_encode, check_prefill
 pytestmark = pytest.mark.gpu
 
 
-def test_encode_more_than_8192_tokens_per_sample():
+@pytest.mark.parametrize("T,Hg,Wg", [(4, 48, 48), (3, 55, 53)])      # the second: windows clipped in every direction
+def test_encode_more_than_8192_tokens_per_sample(T, Hg, Wg):
     from paper_2411_10803_amd import harness
-    cfg = wl.tiny(wl.CONFIGS[4], B=2, T=4, Hg=48, Wg=48, D=64, Hc=2, dc=32, kt=2, kh=2, kw=2, key_budget=40)
-    assert cfg.M == 9216
+    cfg = wl.tiny(wl.CONFIGS[4], B=2, T=T, Hg=Hg, Wg=Wg, D=64, Hc=2, dc=32, kt=2, kh=2, kw=2, key_budget=40)
+    assert cfg.M > 8192
     e = wl.encode_inputs(cfg)
     args = (cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, 0.9, cfg.key_budget)
     g = harness.encode_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None, *args)
