@@ -23,6 +23,8 @@ def test_random_shapes(seed, n_iter, big):
         # ---- encode
         kt, kh, kw = [(1,1,1),(1,1,2),(1,2,2),(2,2,2),(1,3,3),(1,4,4),(2,2,4),(1,2,1)][rng.integers(8)]
         T, Hg, Wg = int(kt * rng.integers(1, 4)), int(kh * rng.integers(1, big * 9)), int(kw * rng.integers(1, big * 9))
+        if rng.random() < 0.4:                           # a grid that the window does not divide
+            T, Hg, Wg = T + int(rng.integers(0, kt)), Hg + int(rng.integers(0, kh)), Wg + int(rng.integers(0, kw))
         dc = [8, 16, 32, 64][rng.integers(4)]; Hc = int(rng.integers(1, 17)); D = Hc * dc
         bf = bool(rng.integers(2))
         B = int(rng.integers(1, 5))
