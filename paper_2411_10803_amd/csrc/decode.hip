@@ -93,7 +93,9 @@ __device__ __forceinline__ float dot8(const u32x4& a, const float (&qv)[8]) {
 // so the selection kernel does not have to sweep the logits for them.
 // STRIDED: the cache has another layout; a load instruction then covers kWave/LPH head slices of
 // d*2 contiguous bytes each instead of 1 KiB of one row.
-template <int LPH, int NIT, bool STRIDED>
+// STREAM_ONCE: the cache is larger than what the L2 / Infinity Cache can hold until the row moves, so
+// the K rows are read with streaming loads (they would only evict each other and everything else).
+template <int LPH, int NIT, bool STRIDED, bool STREAM_ONCE>
 __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const int32_t* __restrict__ len,
     DecodeDims p, KvLayout lay, float scale, float* __restrict__ logits, float2* __restrict__ stat_partial)
@@ -134,11 +136,15 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
         if constexpr (STRIDED) {
             const uint16_t* kr = ks + (long)j * lay.token;
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) kv[it] = *reinterpret_cast<const u32x4*>(kr + off[it]);
+            for (int it = 0; it < NIT; ++it) {
+                const u32x4* src = reinterpret_cast<const u32x4*>(kr + off[it]);
+                kv[it] = STREAM_ONCE ? __builtin_nontemporal_load(src) : *src;
+            }
         } else {
             const u32x4* kr = kb + (long)j * (row / 8);
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) kv[it] = kr[it * kWave + lane];
+            for (int it = 0; it < NIT; ++it)
+                kv[it] = STREAM_ONCE ? __builtin_nontemporal_load(kr + it * kWave + lane) : kr[it * kWave + lane];
         }
         float part[NIT];
 #pragma unroll
@@ -577,6 +583,9 @@ __global__ __launch_bounds__(1024) void decode_keep_plan_kernel(
 
 // Row moves: block (g, b, layer) copies movers[t] -> holes[t] for t = g, g + gridDim.x, ... in the
 // cache of its layer (layer_stride 16-byte vectors apart; one layer for the per-step policy).
+// STREAM_ONCE: caches too large to stay resident -- the source rows are dead after the move and the
+// destination rows will not be read from cache either, so both sides bypass it.
+template <bool STREAM_ONCE>
 __global__ __launch_bounds__(256) void decode_move_kernel(
     DecodeDims p, const int32_t* __restrict__ holes, const int32_t* __restrict__ movers,
     const int32_t* __restrict__ n_move, u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, long layer_stride)
@@ -594,12 +603,14 @@ __global__ __launch_bounds__(256) void decode_move_kernel(
         for (int c = threadIdx.x; c < rv; c += 2 * blockDim.x) {
             const int c2 = c + blockDim.x;
             const bool two = c2 < rv;
-            const u32x4 k0 = k_cache[src + c], v0 = v_cache[src + c];
+            auto ld = [](const u32x4* q) { return STREAM_ONCE ? __builtin_nontemporal_load(q) : *q; };
+            auto st = [](u32x4* q, const u32x4& v) { if (STREAM_ONCE) __builtin_nontemporal_store(v, q); else *q = v; };
+            const u32x4 k0 = ld(k_cache + src + c), v0 = ld(v_cache + src + c);
             u32x4 k1 = k0, v1 = v0;
-            if (two) { k1 = k_cache[src + c2]; v1 = v_cache[src + c2]; }
-            k_cache[dst + c] = k0;
-            v_cache[dst + c] = v0;
-            if (two) { k_cache[dst + c2] = k1; v_cache[dst + c2] = v1; }
+            if (two) { k1 = ld(k_cache + src + c2); v1 = ld(v_cache + src + c2); }
+            st(k_cache + dst + c, k0);
+            st(v_cache + dst + c, v0);
+            if (two) { st(k_cache + dst + c2, k1); st(v_cache + dst + c2, v1); }
         }
     }
 }
@@ -769,9 +780,13 @@ int decode_evict_impl(
         if (blocks_x > kMaxStatParts) blocks_x = kMaxStatParts;
         if (blocks_x < 1) blocks_x = 1;
         dim3 g1(blocks_x, B);
-#define MD_STREAM(NIT_, S_)                                                                                        \
-        MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, NIT_, S_>), g1, 256, 0,                    \
+#define MD_STREAM2(NIT_, S_, O_)                                                                                   \
+        MD_LAUNCH("decode_logits", st, (decode_logits_stream_kernel<16, NIT_, S_, O_>), g1, 256, 0,                \
             qp, kp, len, p, lay, softmax_scale, w.logits, w.stat_partial)
+#define MD_STREAM(NIT_, S_) do { if (stream_once) MD_STREAM2(NIT_, S_, true); else MD_STREAM2(NIT_, S_, false); } while (0)
+        // a cache beyond half of the 256 MB Infinity Cache is streamed; a smaller one is kept cached for
+        // the row moves that follow
+        const bool stream_once = cache_bytes > (size_t)128 << 20;
         if (dense) {
             switch (nit) {
                 case 1: MD_STREAM(1, false); break;
@@ -787,6 +802,7 @@ int decode_evict_impl(
                 default: MD_STREAM(8, true); break;
             }
         }
+#undef MD_STREAM2
 #undef MD_STREAM
         n_part = blocks_x;
     } else {
@@ -831,8 +847,11 @@ int decode_evict_impl(
             p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
     }
     dim3 g3(32, B);
-    if (dense)
-        MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
+    if (dense && cache_bytes > (size_t)128 << 20)
+        MD_LAUNCH("decode_move", st, (decode_move_kernel<true>), g3, 256, 0,
+            p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), 0l);
+    else if (dense)
+        MD_LAUNCH("decode_move", st, (decode_move_kernel<false>), g3, 256, 0,
             p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), 0l);
     else
         MD_LAUNCH("decode_move", st, (decode_move_strided_kernel), g3, 256, 0,
@@ -878,8 +897,12 @@ int decode_keep_impl(
     MD_LAUNCH("decode_keep_plan", st, (decode_keep_plan_kernel), B, 1024, 0,
         p, keep, acc, ids, protect, len, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
     dim3 g3(32, B, n_layers);
-    if (dense)
-        MD_LAUNCH("decode_move", st, (decode_move_kernel), g3, 256, 0,
+    if (dense && cache_bytes > (size_t)128 << 20)
+        MD_LAUNCH("decode_move", st, (decode_move_kernel<true>), g3, 256, 0,
+            p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
+            layer_stride / 8);
+    else if (dense)
+        MD_LAUNCH("decode_move", st, (decode_move_kernel<false>), g3, 256, 0,
             p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
             layer_stride / 8);
     else
