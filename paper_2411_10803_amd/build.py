@@ -13,6 +13,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    # MFMA results straight into VGPRs: the score sweeps read every accumulator right after the MFMA chain,
+    # and the AGPR form costs a v_accvgpr_read per value
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 
