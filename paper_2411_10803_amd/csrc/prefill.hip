@@ -122,7 +122,19 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     __shared__ __attribute__((aligned(16))) char s_tile[4][Tile::BYTES];
     __shared__ float s_m[4][32 * NB], s_z[4][32 * NB];
     const int lane = lane_id(), wv = wave_id();
-    const int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y, b = blockIdx.z;
+    // Blocks go round-robin over the 8 XCDs in launch order.  With several text groups, the blocks that
+    // read the same K chunk (same chunk and head, different text group) are placed 8 apart in that order:
+    // same XCD, launched together, so the second reader finds the chunk in that XCD's L2.
+    int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y;
+    const int b = blockIdx.z;
+    const int ntg = gridDim.x / p.nch;
+    if (ntg > 1 && (p.nch * p.H) % 8 == 0) {
+        const int lin = blockIdx.x + gridDim.x * blockIdx.y;
+        const int r = lin % (8 * ntg), pair = lin / (8 * ntg) * 8 + r % 8;
+        tg = r / 8;
+        ch = pair % p.nch;
+        h = pair / p.nch;
+    }
     const int i_base = tg * 32 * NB;                 // first text row of this block's group
     const long tok_stride = p.kv.token;
     const uint16_t* kb = k + (long)b * p.kv.batch + (long)h * p.kv.head;
