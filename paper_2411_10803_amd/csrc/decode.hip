@@ -104,7 +104,6 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
     __shared__ float s_m[4][NIT * HPI], s_z[4][NIT * HPI];
     const int lane = lane_id(), wv = wave_id();
     const int b = blockIdx.y;
-    const int n = min(max(len[b], 0), p.Lcap);
     const int wave_global = blockIdx.x * 4 + wv;
     const int nwaves = gridDim.x * 4;
     const int row = p.H * p.d;
@@ -131,6 +130,7 @@ __global__ __launch_bounds__(256) void decode_logits_stream_kernel(
 #pragma unroll
     for (int it = 0; it < NIT; ++it) { m[it] = -INFINITY; z[it] = 0.f; }
 
+    const int n = min(max(len[b], 0), p.Lcap);
     for (int j = wave_global; j < n; j += nwaves) {
         u32x4 kv[NIT];
         if constexpr (STRIDED) {
@@ -591,6 +591,10 @@ __global__ __launch_bounds__(256) void decode_move_kernel(
     const int32_t* __restrict__ n_move, u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, long layer_stride)
 {
     const int b = blockIdx.y;
+    // the first pair of the lists is requested together with the count (the entry exists whatever the
+    // count is; it is used only if the count says so)
+    const int t0 = min((int)blockIdx.x, p.Lcap - 1);
+    int mv = movers[(long)b * p.Lcap + t0], hl = holes[(long)b * p.Lcap + t0];
     const int nm = n_move[b];
     const int rv = p.H * p.d / 8;
     k_cache += blockIdx.z * layer_stride;
@@ -598,8 +602,11 @@ __global__ __launch_bounds__(256) void decode_move_kernel(
     // source rows (beyond the new length) and destination rows (holes below it) never coincide, but
     // the compiler cannot know: the vectors of a round are read into registers before any is written
     for (int t = blockIdx.x; t < nm; t += gridDim.x) {
-        const long src = ((long)b * p.Lcap + movers[(long)b * p.Lcap + t]) * rv;
-        const long dst = ((long)b * p.Lcap + holes[(long)b * p.Lcap + t]) * rv;
+        const long src = ((long)b * p.Lcap + mv) * rv;
+        const long dst = ((long)b * p.Lcap + hl) * rv;
+        const int tn = min(t + (int)gridDim.x, p.Lcap - 1);                  // next pair, in flight during the copy
+        mv = movers[(long)b * p.Lcap + tn];
+        hl = holes[(long)b * p.Lcap + tn];
         for (int c = threadIdx.x; c < rv; c += 2 * blockDim.x) {
             const int c2 = c + blockDim.x;
             const bool two = c2 < rv;
