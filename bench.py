@@ -120,13 +120,14 @@ def timed(torch, fn, iters):
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
 # The runs and the raw figures are in profiles/hbm_traffic_cfg2_llava15_b16.txt.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "prefill_compact": int((49007.1 * 2.0 + 97728.0) * 1024),
-    "prefill_rowstats": int((45191.7 * 2.0 + 8320.0) * 1024),
-    "prefill_colscore": int((41102.4 * 2.0 + 72.0) * 1024),
-    "encode_scores": int((18672.1 * 2.0 + 855.7) * 1024),
-    "encode_emit": int((9335.5 * 2.0 + 14286.0) * 1024),
+    "prefill_compact": int((36690.0 * 2.0 + 73152.0) * 1024),
+    "prefill_select": int((12443.1 * 2.0 + 24609.0) * 1024),
+    "prefill_rowstats": int((45197.4 * 2.0 + 8320.0) * 1024),
+    "prefill_colscore": int((41248.8 * 2.0 + 72.0) * 1024),
+    "encode_scores": int((18683.6 * 2.0 + 854.2) * 1024),
+    "encode_emit": int((9330.5 * 2.0 + 14287.5) * 1024),
     "decode_logits": int((16837.0 * 2.0 + 765.0) * 1024),
-    "decode_move": int((8077.0 * 2.0 + 16000.0) * 1024),
+    "decode_move": int((8105.0 * 2.0 + 16000.0) * 1024),
 }
 
 
@@ -146,8 +147,10 @@ def kernel_bytes(cfg, pipe, counts):
         "prefill_rowstats": B * (L + N) * H * d * 2,
         "prefill_cstat": B * H * N * 12,
         "prefill_colscore": B * (M + N) * H * d * 2,
-        "prefill_select": B * M * 16,
-        "prefill_compact": 2 * rows * (C + 2 * H * d) * 2,
+        # budget mode on dense layouts: the text rows are copied by further blocks of the selection launch,
+        # the compaction kernel moves the kept vision rows only
+        "prefill_select": B * M * 16 + 2 * counts["prefill_text_rows"] * (C + 2 * H * d) * 2,
+        "prefill_compact": 2 * (rows - counts["prefill_text_rows"]) * (C + 2 * H * d) * 2,
         "decode_logits": dec_len * H * d * 2 + dec_len * H * 4,
         "decode_select": 3 * dec_len * H * 4,
         "decode_move": 2 * moves * 2 * H * d * 2,
@@ -533,6 +536,7 @@ def main():
     torch.cuda.synchronize()
     dec_after = pipe.pre_out["out_len"].cpu().numpy()
     counts = {"encode_survivors": int(out_count.sum()), "prefill_rows": int((kept + cfg.N).sum()),
+              "prefill_text_rows": int(cfg.B * cfg.N),
               "decode_entries": int(dec_len.sum()), "decode_moves": int(np.minimum(dec_after, dec_len - dec_after).sum())}
     kb = kernel_bytes(cfg, pipe, counts)
     kernels = {}

@@ -551,6 +551,52 @@ __global__ __launch_bounds__(1024) void prefill_select_kernel(
 // The same selection with a sample's scores held in registers (Mv <= 1024*IPT): tokens are dealt
 // round-robin (thread t owns t, t+1024, ...), every global load is issued up front, the radix passes
 // and the prefix sums touch no memory.
+// The text rows of the outputs need no selection: in budget mode their place follows from counting the
+// valid and the key tokens.  While the one block per sample of the selection kernel works through its
+// dependent steps on 1 CU in 16, further blocks of the same launch copy those rows (hidden, K, V).
+struct TextRows {
+    const u32x4* hidden; const u32x4* k; const u32x4* v;
+    u32x4* hidden_out; u32x4* k_out; u32x4* v_out;
+    int enabled;
+};
+constexpr int kTextRowsPerBlock = 4;                 // 1024 threads = four rows of 256 threads
+
+template <int IPT>
+__device__ __forceinline__ void copy_text_rows(
+    const PrefillDims& p, const TextRows& tr, const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len,
+    const uint8_t* __restrict__ is_key, int budget, int* s_red)
+{
+    const int tid = threadIdx.x, Mv = p.Mv;
+    const int bps = (p.N + kTextRowsPerBlock - 1) / kTextRowsPerBlock;        // blocks per sample
+    const int e = blockIdx.x - p.B, b = e / bps, i = (e % bps) * kTextRowsPerBlock + tid / 256;
+    // the number of vision rows kept, exactly as the selection block of this sample counts it
+    uint32_t vv[IPT], kk[IPT];
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) vv[t] = vis_valid ? vis_valid[(long)b * Mv + min(tid + t * 1024, Mv - 1)] : 1u;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) kk[t] = is_key ? is_key[(long)b * Mv + min(tid + t * 1024, Mv - 1)] : 0u;
+    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
+    int cnt = 0;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const bool ok = tid + t * 1024 < Mv && vv[t] != 0;
+        cnt += (ok && kk[t] != 0 ? 1 : 0) + ((ok && kk[t] == 0) ? 1 << 16 : 0);
+    }
+    cnt = block_sum_i(cnt, s_red);
+    const int nk = cnt & 0xFFFF, no = cnt >> 16;
+    const int nkept = min(nk + min(max(budget - nk, 0), no), p.Rcap);
+    if (i >= tl) return;
+    const int rows_cap = p.Rcap + p.N;
+    const int hv = p.C / 8, kv = p.H * p.d / 8, c0 = tid % 256;
+    const long src = (long)b * p.L + Mv + i, dst = (long)b * rows_cap + nkept + i;
+    for (int c = c0; c < kv; c += 256) {
+        const u32x4 a = __builtin_nontemporal_load(tr.k + src * kv + c), a2 = __builtin_nontemporal_load(tr.v + src * kv + c);
+        tr.k_out[dst * kv + c] = a;
+        tr.v_out[dst * kv + c] = a2;
+    }
+    for (int c = c0; c < hv; c += 256) tr.hidden_out[dst * hv + c] = __builtin_nontemporal_load(tr.hidden + src * hv + c);
+}
+
 template <int IPT>
 __global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
     PrefillDims p, const float* __restrict__ V, const float* __restrict__ I,
@@ -559,11 +605,15 @@ __global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
     int32_t* __restrict__ src_row,
     int32_t* __restrict__ kept_index, int32_t* __restrict__ kept_count,
     int32_t* __restrict__ out_len, uint8_t* __restrict__ out_protect,
-    float* __restrict__ score_global, float* __restrict__ score_indiv)
+    float* __restrict__ score_global, float* __restrict__ score_indiv, TextRows tr)
 {
     __shared__ float s_redf[16];
     __shared__ int s_red[16];
     __shared__ int s_hist[256];
+    if ((int)blockIdx.x >= p.B) {                    // block-uniform: the blocks that copy the text rows
+        copy_text_rows<IPT>(p, tr, vis_valid, txt_len, is_key, budget, s_red);
+        return;
+    }
     const int b = blockIdx.x, tid = threadIdx.x;
     const int Mv = p.Mv;
     const int rows_cap = p.Rcap + p.N;
@@ -654,12 +704,12 @@ __global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
 __global__ __launch_bounds__(256) void prefill_compact_kernel(
     PrefillDims p, const int32_t* __restrict__ src_row,
     const u32x4* __restrict__ hidden, const u32x4* __restrict__ k, const u32x4* __restrict__ v,
-    u32x4* __restrict__ hidden_out, u32x4* __restrict__ k_out, u32x4* __restrict__ v_out)
+    u32x4* __restrict__ hidden_out, u32x4* __restrict__ k_out, u32x4* __restrict__ v_out, int text_done)
 {
     const int o = blockIdx.x, b = blockIdx.y;
     const int rows_cap = p.Rcap + p.N;
     const int src = src_row[(long)b * rows_cap + o];
-    if (src < 0) return;
+    if (src < 0 || (text_done && src >= p.Mv)) return;     // text rows may have been copied by the selection launch
     const int hv = p.C / 8, kv = p.H * p.d / 8;          // 16-byte vectors per row
     const u32x4* hs = hidden + ((long)b * p.L + src) * hv;
     const u32x4* ks = k + ((long)b * p.L + src) * kv;
@@ -900,10 +950,15 @@ int prefill_filter_impl(
                       : launch_scores<4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
     if (rc != MD_OK) return rc;
     int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
+    const bool dense_io = is_dense(lkv, (long)L, H, d) && is_dense(lout, (long)Rcap + N, H, d);
+    TextRows tr{static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
+                static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out), 0};
+    tr.enabled = (mode == MD_FILTER_BUDGET && dense_io && Mv <= 8192) ? 1 : 0;
+    const int sel_blocks = B + (tr.enabled ? B * ((N + kTextRowsPerBlock - 1) / kTextRowsPerBlock) : 0);
 #define MD_PSELECT_FAST(IPT_)                                                                               \
-    MD_LAUNCH("prefill_select", st, (prefill_select_fast_kernel<IPT_>), B, 1024, 0,                 \
+    MD_LAUNCH("prefill_select", st, (prefill_select_fast_kernel<IPT_>), sel_blocks, 1024, 0,        \
         p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,                          \
-        src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv)
+        src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv, tr)
     if (Mv <= 1024) MD_PSELECT_FAST(1);
     else if (Mv <= 2048) MD_PSELECT_FAST(2);
     else if (Mv <= 4096) MD_PSELECT_FAST(4);
@@ -913,11 +968,11 @@ int prefill_filter_impl(
             p, w.V, w.I, vis_valid, txt_len, is_key, (int)mode, budget, gamma, alpha,
             w.score, src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv);
 #undef MD_PSELECT_FAST
-    dim3 gc(Rcap + N, B);
-    if (is_dense(lkv, (long)L, H, d) && is_dense(lout, (long)Rcap + N, H, d))
+    dim3 gc(tr.enabled ? Rcap : Rcap + N, B);         // the text rows beyond the kept vision rows are already in place
+    if (dense_io)
         MD_LAUNCH("prefill_compact", st, (prefill_compact_kernel), gc, 256, 0, p, src_row,
             static_cast<const u32x4*>(hidden), static_cast<const u32x4*>(k), static_cast<const u32x4*>(v),
-            static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out));
+            static_cast<u32x4*>(hidden_out), static_cast<u32x4*>(k_out), static_cast<u32x4*>(v_out), tr.enabled);
     else
         MD_LAUNCH("prefill_compact", st, (prefill_compact_strided_kernel), gc, 256, 0, p, src_row,
             static_cast<const u32x4*>(hidden), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v),
