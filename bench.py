@@ -400,6 +400,22 @@ def variable_length(torch, md, cfg, pipe):
             "paper_table3_average_tokens": {"encode": 440, "prefill": 64, "decode": 45}}
 
 
+def single_image_latency(torch, md, harness, iters=300):
+    """The latency workload: one image (1 x 24 x 24 fp32 patch tokens, 32 text tokens) through the same
+    chained three-stage step; microseconds per stage and per step."""
+    cfg = wl.CONFIGS[1]
+    pipe = Cfg2Pipeline(cfg, torch, md, harness)
+    for _ in range(10):
+        pipe.step()
+    step = timed(torch, pipe.step, iters)
+    enc = timed(torch, pipe.encode, iters)
+    pre = timed(torch, pipe.prefill, iters)
+    pipe.prefill()
+    dec = timed(torch, lambda: (pipe.prefill(), pipe.decode()), iters) - pre
+    return {"workload": cfg.name, "us_per_step": round(step * 1e3, 2), "encode_us": round(enc * 1e3, 2),
+            "prefill_us": round(pre * 1e3, 2), "decode_us": round(dec * 1e3, 2)}
+
+
 def cpu_info():
     model = "unknown"
     try:
@@ -580,6 +596,7 @@ def main():
         result["static_handoff"] = static_handoff(torch, md, binding, cfg)
         result["static_handoff_video"] = static_handoff(torch, md, binding, cfg, B=8, M=2048, kept_vision=1024, reps=5,
                                                         name="video_8x256_keep_half")
+        result["single_image_latency"] = single_image_latency(torch, md, harness)
         result["cold_vs_warm"] = cold_vs_warm(torch, pipe)
         result["variable_length"] = variable_length(torch, md, cfg, pipe)
     if not args.no_parity:
