@@ -174,12 +174,16 @@ int mustdrop_prefill_filter(
  *
  *   q        [B, H, d] bf16             query of the token being generated
  *   k_cache, v_cache [B, Lcap, H, d] bf16   in/out
- *   acc      [B, Lcap] f32, ids [B, Lcap] i32 (>= 0, unique per sample), protect [B, Lcap] u8, len [B] i32: in/out
+ *   acc      [B, Lcap] f32 (>= 0: entries are ranked by the bit pattern of their score), ids [B, Lcap] i32
+ *            (in [0, 2^31 - 2], unique per sample), protect [B, Lcap] u8, len [B] i32: in/out
+ *   decay    >= 0 (MD_EINVAL otherwise), so that the running scores stay non-negative
  *   evicted_ids [B, Lcap] or NULL: ids of the evicted entries in ascending (pre-compaction) slot order
  *   evicted_count [B] or NULL
  *
  * Limits: d a power of two in [8, 512]; H <= 1024 (rows of 1, 2, 4 or 8 KiB with d = 128 and
  * H in {4, 8, 16, 32, 64} take the streaming kernels, other shapes the general ones).
+ * MD_EALIAS: q, the two caches, acc, ids, protect, len, the optional outputs and the workspace must be
+ * pairwise disjoint.
  */
 size_t mustdrop_decode_evict_workspace_bytes(int B, int Lcap, int H);
 

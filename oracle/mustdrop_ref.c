@@ -21,7 +21,8 @@
  * the layer schedule (the paper defers them to an appendix that is not
  * available) -- they are caller parameters here; the form of the adaptive
  * threshold of Eq. 7 (read as mean + lambda * std; that rule itself is pinned
- * against numpy, except strict > against >= at an exact tie).
+ * against numpy, and its strict > by an exact tie: one head, a zero CLS query
+ * and 2^k - 1 tokens make every a_cls equal to mu).
  */
 #include <math.h>
 #include <stdint.h>

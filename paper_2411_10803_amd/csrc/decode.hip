@@ -761,6 +761,8 @@ int decode_evict_impl(
         return fail(MD_EINVAL, "decode_evict: q, the caches and the state arrays are required");
     if (budget < 0) return fail(MD_EINVAL, "decode_evict: negative budget");
     if (std::isnan(softmax_scale) || std::isnan(decay)) return fail(MD_EINVAL, "decode_evict: NaN parameter");
+    // the selection ranks entries by the bit pattern of their running score, which orders non-negative values only
+    if (decay < 0.f) return fail(MD_EINVAL, "decode_evict: decay must be >= 0 (running scores stay non-negative)");
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache))
         return fail(MD_EALIGN, "decode_evict: q and the caches must be 16-byte aligned");
     const size_t cache_bytes = layout_extent_bytes(lay, B, Lcap, H, d);
@@ -768,6 +770,17 @@ int decode_evict_impl(
     if (overlaps(q, (size_t)B * H * d * 2, k_cache, cache_bytes) || overlaps(q, (size_t)B * H * d * 2, v_cache, cache_bytes))
         return fail(MD_EALIAS, "decode_evict: q overlaps a cache");
     const DecodeWorkspace w = carve_decode(workspace, B, Lcap, H);
+    {
+        // the small state arrays, the optional outputs and the workspace against the caches, q and one another
+        const size_t n = (size_t)B * Lcap;
+        const void* pa[] = {acc, ids, protect, len, evicted_ids, evicted_count, workspace, k_cache, v_cache, q};
+        const size_t sa[] = {n * 4, n * 4, n, (size_t)B * 4, n * 4, (size_t)B * 4, workspace ? w.bytes : 0,
+                             cache_bytes, cache_bytes, (size_t)B * H * d * 2};
+        for (int a = 0; a < 7; ++a)
+            for (int c = a + 1; c < 10; ++c)
+                if (overlaps(pa[a], sa[a], pa[c], sa[c]))
+                    return fail(MD_EALIAS, "decode_evict: the state arrays, outputs, workspace, caches and q must not overlap");
+    }
     if (!workspace || workspace_bytes < w.bytes)
         return fail(MD_EWORKSPACE, "decode_evict: workspace of %zu bytes needed, %zu given", w.bytes, workspace ? workspace_bytes : (size_t)0);
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(MD_EALIGN, "decode_evict: workspace must be 256-byte aligned");

@@ -169,7 +169,13 @@ def check_prefill(g, o, t, Mv, vis_valid, is_key, mode, budget, gamma, alpha, Rc
             s = np.maximum(Vo[cand] / (g32 * G) if G > 0 else np.zeros(cand.size), Io[cand] / a32)
             dec = _topk_decisive(s, budget - int(kb.sum()))
         else:
-            dec = (np.abs(Vo[cand] - g32 * G) > MARGIN * abs(g32 * G)) & (np.abs(Io[cand] - a32) > MARGIN * abs(a32))
+            # drop iff V <= gamma*G and I < alpha: a token is decisive when its fate cannot change inside the
+            # margin band -- clearly above either threshold (kept whatever the other score does), or clearly
+            # below both (dropped)
+            tv, ta = g32 * G, a32
+            v_hi, v_lo = Vo[cand] > tv + MARGIN * abs(tv), Vo[cand] < tv - MARGIN * abs(tv)
+            i_hi, i_lo = Io[cand] > ta + MARGIN * abs(ta), Io[cand] < ta - MARGIN * abs(ta)
+            dec = v_hi | i_hi | (v_lo & i_lo)
         summary["ambiguous"] += int((~dec).sum())
         cg, co = int(g["kept_count"][b]), int(o["kept_count"][b])
         if mode == 0 or dec.all():

@@ -105,12 +105,17 @@ def test_prefill_argument_errors(lib):
     assert prefill(lib, q=P(0x1000004)) == 3
 
 
+ACC, IDS, PROT, LEN = P(0x200000), P(0x300000), P(0x400000), P(0x500000)   # the small state arrays, disjoint
+
+
 def decode(lib, **kw):
     a = dict(q=P(0x1000), k=P(0x10000000), v=P(0x80000000), B=2, Lcap=4096, H=32, d=128, budget=1024,
              ws=P(0x100000000), wsb=1 << 30)
     a.update(kw)
-    return lib.mustdrop_decode_evict(a["q"], a["k"], a["v"], X, X, X, X, a["B"], a["Lcap"], a["H"], a["d"],
-                                     F(0.088), F(1.0), a["budget"], None, None, a["ws"], C.c_size_t(a["wsb"]), None)
+    return lib.mustdrop_decode_evict(a["q"], a["k"], a["v"], a.get("acc", ACC), a.get("ids", IDS), PROT, LEN,
+                                     a["B"], a["Lcap"], a["H"], a["d"],
+                                     F(0.088), F(a.get("decay", 1.0)), a["budget"], None, None, a["ws"],
+                                     C.c_size_t(a["wsb"]), None)
 
 
 def test_decode_argument_errors(lib):
@@ -121,6 +126,11 @@ def test_decode_argument_errors(lib):
     assert decode(lib, v=P(0x10000000)) == 4
     assert decode(lib, wsb=0) == 5
     assert decode(lib, k=P(0x10000008)) == 3
+    assert decode(lib, decay=-0.5) == 1 and b"decay" in lib.mustdrop_last_error()
+    assert decode(lib, acc=IDS) == 4                                        # acc and ids share memory
+    assert decode(lib, ids=P(0x10000000 + 4096)) == 4                       # ids inside the K cache
+    assert decode(lib, ws=P(0x80000000 + 4096)) == 4                        # workspace inside the V cache
+    assert decode(lib, acc=P(0x100000000 + 1024)) == 4                      # acc inside the workspace
     rc = lib.mustdrop_decode_append(None, X, X, X, X, X, X, X, 2, 64, 32, 128, 5, 1, None)
     assert rc == 1
     rc = lib.mustdrop_decode_append(X, X, X, X, X, X, X, X, 2, 64, 32, 128, -1, 1, None)
@@ -189,7 +199,7 @@ def test_layout_argument_errors(lib):
 
     def dec(lay, fn="evict"):
         if fn == "evict":
-            return lib.mustdrop_decode_evict_strided(P(0x1000), P(0x10000000), P(0x80000000), X, X, X, X, 2, 4096, 32, 128,
+            return lib.mustdrop_decode_evict_strided(P(0x1000), P(0x10000000), P(0x80000000), ACC, IDS, PROT, LEN, 2, 4096, 32, 128,
                                                      F(0.088), F(1.0), 1024, None, None, C.byref(lay), P(0x100000000),
                                                      C.c_size_t(16), None)
         return lib.mustdrop_decode_append_strided(None, X, X, X, X, X, X, X, 2, 4096, 32, 128, 5, 1, C.byref(lay), None)

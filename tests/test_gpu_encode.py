@@ -34,6 +34,18 @@ def median_tau(cfg):
     return float(np.median(o["window_sim"]))
 
 
+def clear_tau(sims, q=0.5):
+    """A threshold near the q-quantile of the oracle's window similarities that no similarity comes closer to
+    than twice the margin: every merge decision is then decisive."""
+    v = np.sort(np.asarray(sims, dtype=np.float64).ravel())
+    i0 = int(q * (v.size - 1))
+    for step in range(v.size):
+        for i in (i0 + step, i0 - step):
+            if 0 <= i < v.size - 1 and v[i + 1] - v[i] > 4e-3:
+                return float(np.float32(0.5 * (v[i] + v[i + 1])))
+    raise AssertionError("no gap between the window similarities")
+
+
 def test_config1_single_image_fp32():
     cfg = wl.CONFIGS[1]
     g, o, s = run_cfg(cfg)
@@ -178,3 +190,92 @@ def test_adaptive_key_threshold(shape):
                      key_lambda=lam)
         if lam == 50.0:
             assert np.all(g["key_count"] == 0)
+
+
+@pytest.mark.parametrize("Hg,Wg", [(1, 3), (3, 5), (7, 9)])
+def test_adaptive_rule_is_strict_at_an_exact_tie(Hg, Wg):
+    """Eq. 7 prints '>'.  One head, a zero CLS query, M = 2^k - 1 tokens: every a_cls is exactly 1/(M+1),
+    so mu == a_cls in fp32 as in fp64 and the key set must be empty for any lambda (the oracle's pin, here
+    through the fp32 kernels)."""
+    from paper_2411_10803_amd import harness
+    M, D = Hg * Wg, 16
+    rng = np.random.default_rng(M)
+    x = rng.standard_normal((2, M, D)).astype(np.float32)
+    k = np.ascontiguousarray(rng.standard_normal((2, 1 + M, 1, D)).astype(np.float32))
+    q = np.zeros((2, 1, D), dtype=np.float32)
+    for lam in (-1.0, 0.0, 2.0):
+        g = harness.encode_adaptive_on_gpu(x, wl.F32, q, k, wl.F32, None, None, 1, Hg, Wg, 1, 1, 1, 2.0, lam, M)
+        o = oracle.encode_merge_adaptive(x, wl.F32, q, k, wl.F32, None, None, 1, Hg, Wg, 1, 1, 1, 2.0, lam, M)
+        assert np.all(o["key_count"] == 0)
+        assert np.all(g["a_cls"] == np.float32(1.0 / (M + 1)))
+        assert np.all(g["key_count"] == 0) and np.all(g["key_index"] == -1) and g["out_is_key"].sum() == 0
+        assert np.array_equal(g["out_count"], o["out_count"])
+
+
+def _second_call_inputs(o1, cls_row, Hc, dc):
+    B, M, D = o1["out_x"].shape
+    k2 = np.concatenate([cls_row.reshape(B, 1, D), o1["out_x"]], axis=1).reshape(B, 1 + M, Hc, dc)
+    return o1["out_x"], np.ascontiguousarray(k2), o1["out_mass"], o1["out_valid"]
+
+
+@pytest.mark.parametrize("which", ["small_f32", "cfg2_bf16"])
+def test_paper_order_merge_then_keys_as_a_chain(which):
+    """Sec. 3.3 in the paper's order, each side running its own chain: a merging call without keys, then a
+    key-selection call (1x1x1 windows) on that call's out_x / out_valid / out_mass as a 1 x 1 x M grid."""
+    from paper_2411_10803_amd import harness
+    if which == "small_f32":
+        cfg = wl.tiny(wl.CONFIGS[2], B=3, Hg=10, Wg=14, D=128, Hc=8, dc=16, x_dtype=wl.F32, key_budget=9)
+    else:
+        cfg = wl.tiny(wl.CONFIGS[2], B=4)
+    e = wl.encode_inputs(cfg)
+    dt, M = cfg.x_dtype, cfg.M
+    tau = clear_tau(oracle.encode_merge(e["x"], dt, None, None, dt, None, None, cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh,
+                                        cfg.kw, 2.0, 0)["window_sim"], 0.5 if which == "small_f32" else 0.3)
+    a1 = (cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, tau, 0)
+    g1, o1 = both(e["x"], dt, None, None, dt, None, None, *a1)
+    s1 = check_encode(g1, o1, e["x"], dt, None, *a1)
+    assert s1["ambiguous_windows"] == 0 and np.array_equal(g1["out_count"], o1["out_count"])
+    assert o1["out_count"].sum() < cfg.B * M and o1["out_count"].min() > cfg.key_budget
+    a2 = (1, 1, M, 1, 1, 1, 5.0, cfg.key_budget)
+    gx, gk, gm, gv = _second_call_inputs(g1, e["q_cls"], cfg.Hc, cfg.dc)
+    ox, ok, om, ov = _second_call_inputs(o1, e["q_cls"], cfg.Hc, cfg.dc)
+    g2 = harness.encode_on_gpu(gx, dt, e["q_cls"], gk, dt, gm, gv, *a2)
+    o2 = oracle.encode_merge(ox, dt, e["q_cls"], ok, dt, om, ov, *a2)
+    check_encode(g2, o2, gx, dt, gv, *a2)
+    for b in range(cfg.B):
+        n = int(g1["out_count"][b])
+        assert g2["out_count"][b] == n
+        assert np.array_equal(g2["out_x"][b, :n], g1["out_x"][b, :n])       # nothing merges: rows pass through
+        assert np.array_equal(g2["out_mass"][b, :n], g1["out_mass"][b, :n])
+        assert g2["out_mass"][b, :n].sum() == M                            # mass conserved over both calls
+        keys = g2["key_index"][b]
+        assert np.all(keys >= 0) and np.all(keys < n) and g2["out_is_key"][b, :n].sum() == cfg.key_budget
+
+
+def test_hierarchical_remerge_with_carried_masses():
+    """A second merging call on the survivors of the first (laid out as a 1 x 1 x M row, windows of four,
+    masses carried): each side runs its own chain; mass and the mass-weighted feature sum are conserved."""
+    from paper_2411_10803_amd import harness
+    cfg = wl.tiny(wl.CONFIGS[2], B=3, Hg=12, Wg=12, D=256, Hc=4, dc=64, x_dtype=wl.F32)
+    e = wl.encode_inputs(cfg)
+    dt, M = cfg.x_dtype, cfg.M
+    a1 = (1, cfg.Hg, cfg.Wg, 1, 2, 2, clear_tau(oracle.encode_merge(e["x"], dt, None, None, dt, None, None, 1, cfg.Hg,
+                                                                    cfg.Wg, 1, 2, 2, 2.0, 0)["window_sim"]), 0)
+    g1, o1 = both(e["x"], dt, None, None, dt, None, None, *a1)
+    s1 = check_encode(g1, o1, e["x"], dt, None, *a1)
+    assert s1["ambiguous_windows"] == 0 and o1["out_count"].sum() < cfg.B * M
+    sims2 = oracle.encode_merge(o1["out_x"], dt, None, None, dt, o1["out_mass"], o1["out_valid"],
+                                1, 1, M, 1, 1, 4, 2.0, 0)["window_sim"]
+    live = np.concatenate([sims2[b, : int(o1["out_count"][b]) // 4] for b in range(cfg.B)])
+    a2 = (1, 1, M, 1, 1, 4, clear_tau(live), 0)
+    g2 = harness.encode_on_gpu(g1["out_x"], dt, None, None, dt, g1["out_mass"], g1["out_valid"], *a2)
+    o2 = oracle.encode_merge(o1["out_x"], dt, None, None, dt, o1["out_mass"], o1["out_valid"], *a2)
+    s2 = check_encode(g2, o2, g1["out_x"], dt, g1["out_valid"], *a2)
+    assert s2["merged_rows_checked"] > 10
+    assert g2["out_count"].sum() < g1["out_count"].sum() and g2["out_mass"].max() > 4.0
+    tot = e["x"].astype(np.float64).sum(1)
+    for b in range(cfg.B):
+        n2 = int(g2["out_count"][b])
+        assert g2["out_mass"][b, :n2].sum() == M
+        lhs = (g2["out_mass"][b, :n2, None].astype(np.float64) * g2["out_x"][b, :n2]).sum(0)
+        assert np.allclose(lhs, tot[b], rtol=1e-4, atol=1e-3)

@@ -372,15 +372,95 @@ def test_window_with_fewer_than_two_valid_members_is_left_alone():
     assert o["out_count"][0] == 1 and o["out_index"][0, 0] == 1 and o["out_mass"][0, 0] == 2.0
 
 
+def chain_second_call_inputs(o1, cls_row, Hc, dc):
+    """Inputs of the key-selection call on an already merged sequence: the survivors of the first call as
+    a 1 x 1 x M grid (slots beyond out_count are padding), their masses, and keys made the way the
+    synthetic workload makes them (row 0 = the CLS row, then the token rows, viewed as Hc x dc)."""
+    B, M, D = o1["out_x"].shape
+    k2 = np.concatenate([cls_row.reshape(B, 1, D), o1["out_x"]], axis=1).reshape(B, 1 + M, Hc, dc)
+    return o1["out_x"], np.ascontiguousarray(k2), o1["out_mass"], o1["out_valid"]
+
+
 def test_two_call_form_matches_paper_order():
-    # merge first (layer-1 call, no keys), then key selection alone (window 1x1x1) on the merged sequence
+    """Sec. 3.3 in the paper's order: merge at the first layer (a call without keys), then Key Retaining
+    at a deep layer on the MERGED sequence (a call with 1x1x1 windows on the first call's outputs)."""
     cfg, e = smooth_case(T=1)
+    budget = 4
     o1 = run(e["x"], 1, cfg.Hg, cfg.Wg, tau=0.2)
-    assert np.all(o1["out_count"] < cfg.M)
-    o2 = run(e["x"], 1, cfg.Hg, cfg.Wg, 1, 1, 1, tau=5.0, key_budget=4, q=e["q_cls"], k=e["k_cls"])
-    assert np.all(o2["out_count"] == cfg.M)          # 1x1x1 windows never merge
-    assert np.array_equal(o2["out_x"], e["x"])
-    assert o2["out_is_key"].sum() == 4 * cfg.B
+    assert np.all(o1["out_count"] < cfg.M) and np.all(o1["out_count"] > budget)
+    x2, k2, mass2, valid2 = chain_second_call_inputs(o1, e["q_cls"], cfg.Hc, cfg.dc)
+    o2 = run(x2, 1, 1, cfg.M, 1, 1, 1, tau=5.0, key_budget=budget, q=e["q_cls"], k=k2, mass=mass2, valid=valid2)
+    q = wl.to_f64(e["q_cls"], F32)
+    for b in range(cfg.B):
+        n = int(o1["out_count"][b])
+        # 1x1x1 windows never merge: the second call passes the merged sequence through unchanged
+        assert o2["out_count"][b] == n
+        assert np.array_equal(o2["out_x"][b, :n], o1["out_x"][b, :n])
+        assert np.array_equal(o2["out_mass"][b, :n], o1["out_mass"][b, :n])
+        assert np.array_equal(o2["out_index"][b, :n], np.arange(n))
+        # token mass is conserved across both calls: every patch is still represented exactly once
+        assert o2["out_mass"][b, :n].sum() == cfg.M
+        lhs = (o2["out_mass"][b, :n, None].astype(np.float64) * o2["out_x"][b, :n]).sum(0)
+        assert np.allclose(lhs, e["x"][b].astype(np.float64).sum(0), rtol=1e-5, atol=1e-4)
+        # the keys are survivors (never a padding slot), and they are the top scores of the merged
+        # sequence: recomputed here with numpy on the first call's rows
+        keys = o2["key_index"][b]
+        assert np.all(keys >= 0) and np.all(keys < n) and o2["out_is_key"][b, :n].sum() == budget
+        rows = wl.to_f64(o1["out_x"][b, :n], F32).reshape(n, cfg.Hc, cfg.dc)
+        kk = np.concatenate([q[b][None], rows], axis=0)
+        logits = np.einsum("hc,jhc->hj", q[b], kk) / np.sqrt(cfg.dc)
+        p = np.exp(logits - logits.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        a = p[:, 1:].mean(axis=0)
+        assert sorted(np.argsort(-a, kind="stable")[:budget].tolist()) == keys.tolist()
+    # the one-call form scores the unmerged grid instead: a different computation (other softmax support)
+    o3 = run(e["x"], 1, cfg.Hg, cfg.Wg, tau=0.2, key_budget=budget, q=e["q_cls"], k=e["k_cls"])
+    assert not np.allclose(o3["a_cls"][0, :8], o2["a_cls"][0, :8], rtol=1e-3)
+
+
+def test_hierarchical_remerge_conserves_mass_and_matches_brute_force():
+    """Merging an already merged sequence again (the caller lays the survivors out on a new grid and
+    hands over their masses): the total mass and the mass-weighted feature sum survive both calls, and the
+    second call's rows are the brute-force mass-weighted means of the first call's rows."""
+    cfg, e = smooth_case(B=2, Hg=8, Wg=8, T=1)
+    M = cfg.M
+    sims = run(e["x"], 1, cfg.Hg, cfg.Wg, tau=2.0)["window_sim"]
+    o1 = run(e["x"], 1, cfg.Hg, cfg.Wg, tau=float(np.quantile(sims, 0.4)))
+    assert np.all(o1["out_count"] < M) and np.all(o1["out_count"] >= M // 4) and o1["out_count"].max() > M // 4
+    # second level: the survivors, in order, as a 1 x 1 x M row cut into windows of four; padding at the tail
+    x2, mass2, valid2 = o1["out_x"], o1["out_mass"], o1["out_valid"]
+    s2 = run(x2, 1, 1, M, 1, 1, 4, tau=2.0, mass=mass2, valid=valid2)["window_sim"]
+    tau2 = float(np.median(s2[0, : int(o1["out_count"][0]) // 4]))
+    o2 = run(x2, 1, 1, M, 1, 1, 4, tau=tau2, mass=mass2, valid=valid2)
+    total_x = e["x"].astype(np.float64).sum(1)
+    assert o2["out_count"].sum() < o1["out_count"].sum() and o2["out_mass"].max() > 4.0    # some merges of merges
+    for b in range(cfg.B):
+        n1, n2 = int(o1["out_count"][b]), int(o2["out_count"][b])
+        assert n2 <= n1
+        assert o1["out_mass"][b, :n1].sum() == M and o2["out_mass"][b, :n2].sum() == M
+        lhs = (o2["out_mass"][b, :n2, None].astype(np.float64) * o2["out_x"][b, :n2]).sum(0)
+        assert np.allclose(lhs, total_x[b], rtol=1e-5, atol=1e-4)
+        # brute force over the second level's windows
+        xs = x2[b].astype(np.float64)
+        want_idx, want_mass, want_rows = [], [], []
+        for w0 in range(0, M, 4):
+            mem = [j for j in range(w0, min(w0 + 4, M)) if valid2[b, j]]
+            if not mem:
+                continue
+            cs = []
+            for m, q in combinations(mem, 2):
+                den = np.linalg.norm(xs[m]) * np.linalg.norm(xs[q])
+                cs.append(xs[m] @ xs[q] / den if den > 0 else 0.0)
+            if len(mem) >= 2 and np.mean(cs) > np.float64(np.float32(tau2)):
+                mm = mass2[b, mem].astype(np.float64)
+                want_idx.append(mem[0]); want_mass.append(mm.sum())
+                want_rows.append((mm[:, None] * xs[mem]).sum(0) / mm.sum())
+            else:
+                for j in mem:
+                    want_idx.append(j); want_mass.append(float(mass2[b, j])); want_rows.append(xs[j])
+        assert o2["out_index"][b, :n2].tolist() == want_idx
+        assert np.allclose(o2["out_mass"][b, :n2], want_mass, rtol=0, atol=0)
+        assert np.allclose(o2["out_x"][b, :n2], np.asarray(want_rows), rtol=1e-6, atol=1e-7)
 
 
 # ---------------------------------------------------------------- storage rounding
@@ -517,3 +597,35 @@ def test_adaptive_key_index_capacity():
     assert np.array_equal(o["key_count"], full["key_count"]) and np.all(full["key_count"] > cap)
     assert np.array_equal(o["key_index"], full["key_index"][:, :cap])
     assert np.array_equal(o["out_index"], full["out_index"])         # the capacity limits the list, not the set
+
+
+@pytest.mark.parametrize("Hg,Wg", [(1, 3), (3, 5), (7, 9)])
+def test_adaptive_rule_is_strict_at_an_exact_tie(Hg, Wg):
+    """Eq. 7 prints a strict '>'.  One head, a zero CLS query and M = 2^k - 1 tokens make every logit 0,
+    so every a_cls is exactly 1/(M+1) (a power of two): the mean is exact, the standard deviation is 0
+    and mu == a_cls for any lambda.  Strict '>' selects nothing; '>=' would select every token."""
+    M, D = Hg * Wg, 16
+    assert (M + 1) & M == 0
+    rng = np.random.default_rng(M)
+    x = rng.standard_normal((2, M, D)).astype(np.float32)
+    k = np.ascontiguousarray(rng.standard_normal((2, 1 + M, 1, D)).astype(np.float32))
+    q = np.zeros((2, 1, D), dtype=np.float32)
+    for lam in (-1.0, 0.0, 2.0):
+        o = oracle.encode_merge_adaptive(x, F32, q, k, F32, None, None, 1, Hg, Wg, 1, 1, 1, 2.0, lam, M)
+        assert np.all(o["a_cls"] == 1.0 / (M + 1))
+        assert np.all(o["key_count"] == 0) and np.all(o["key_index"] == -1) and o["out_is_key"].sum() == 0
+    # the same tie among the valid tokens of a padded grid (15 valid of 20 slots)
+    if M == 15:
+        valid = np.ones((2, 20), dtype=np.uint8)
+        valid[:, [1, 6, 7, 13, 19]] = 0
+        x20 = rng.standard_normal((2, 20, D)).astype(np.float32)
+        k20 = np.ascontiguousarray(rng.standard_normal((2, 21, 1, D)).astype(np.float32))
+        o = oracle.encode_merge_adaptive(x20, F32, q, k20, F32, None, valid, 1, 4, 5, 1, 1, 1, 2.0, 0.0, 20)
+        assert np.all(o["a_cls"][valid.astype(bool)] == 1.0 / 16) and np.all(o["key_count"] == 0)
+    # one token lifted by a hair is the only one above the threshold: the rule is not vacuous here
+    q1 = np.zeros((2, 1, D), dtype=np.float32)
+    q1[:, 0, 0] = 1.0
+    k1 = np.zeros((2, 1 + M, 1, D), dtype=np.float32)
+    k1[:, 2, 0, 0] = 0.25
+    o = oracle.encode_merge_adaptive(x, F32, q1, k1, F32, None, None, 1, Hg, Wg, 1, 1, 1, 2.0, 0.0, M)
+    assert np.all(o["key_count"] == 1) and np.all(o["key_index"][:, 0] == 1)
