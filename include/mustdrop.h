@@ -97,6 +97,28 @@ int mustdrop_encode_merge(
     float* a_cls_out, float* window_sim_out,
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* mustdrop_encode_merge for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and
+ * errors as mustdrop_encode_merge, minus `workspace` / `workspace_bytes`: the scratch memory is a static
+ * device array of MUSTDROP_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on holds
+ * one until the process ends).  The call allocates and frees nothing.  A shape whose
+ * mustdrop_encode_merge_workspace_bytes(...) exceeds the static buffer is rejected with MD_EWORKSPACE
+ * (8 MiB covers up to 16 samples of 2880 tokens, or 4 of 4608, with 16 CLS heads).  The first call on
+ * a device looks up the array's device address; do that call outside a graph capture.  All calls on one
+ * GPU share the array, which keeps the previous call's contents (nothing in it needs clearing): calls
+ * that overlap in time on one GPU race -- order them on one stream. */
+#define MUSTDROP_STATIC_SCRATCH_BYTES (8u << 20)
+
+int mustdrop_encode_merge_noalloc(
+    const void* x, md_dtype x_dtype,
+    const void* q_cls, const void* k_cls, md_dtype qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, int key_budget,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
+    int32_t* out_count, int32_t* key_index,
+    float* a_cls_out, float* window_sim_out, void* stream);
+
 /* Stage 1 with the key set in the printed form of Eq. 7: O = { j : a_cls[j] > mu }.  The paper only says
  * that mu is adaptive and depends on a_cls; this library reads it as mu = mean + key_lambda * std of
  * a_cls over the valid tokens (population standard deviation, fp32).  Everything else is

@@ -16,6 +16,7 @@ _lib = None
 EXPORTS = [
     "mustdrop_last_error", "mustdrop_version",
     "mustdrop_encode_merge_workspace_bytes", "mustdrop_encode_merge", "mustdrop_encode_merge_adaptive",
+    "mustdrop_encode_merge_noalloc",
     "mustdrop_prefill_filter_workspace_bytes", "mustdrop_prefill_filter",
     "mustdrop_decode_evict_workspace_bytes", "mustdrop_decode_evict", "mustdrop_decode_append", "mustdrop_decode_keep",
     "mustdrop_prefill_filter_strided", "mustdrop_decode_evict_strided", "mustdrop_decode_append_strided",
@@ -52,7 +53,7 @@ def library() -> C.CDLL:
         for n in ("mustdrop_encode_merge_workspace_bytes", "mustdrop_prefill_filter_workspace_bytes",
                   "mustdrop_decode_evict_workspace_bytes"):
             getattr(lib, n).restype = C.c_size_t
-        for n in ("mustdrop_encode_merge", "mustdrop_encode_merge_adaptive", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
+        for n in ("mustdrop_encode_merge", "mustdrop_encode_merge_adaptive", "mustdrop_encode_merge_noalloc", "mustdrop_prefill_filter", "mustdrop_decode_evict", "mustdrop_decode_append",
                   "mustdrop_decode_keep", "mustdrop_prefill_filter_strided", "mustdrop_decode_evict_strided",
                   "mustdrop_decode_append_strided", "mustdrop_decode_keep_strided"):
             getattr(lib, n).restype = C.c_int
@@ -157,6 +158,26 @@ def mustdrop_encode_merge(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, kt, kh, kw
         _ptr(out["out_valid"]), _ptr(out["out_count"]), _ptr(out["key_index"]),
         _ptr(out.get("a_cls")), _ptr(out.get("window_sim")),
         _ptr(workspace), C.c_size_t(workspace.numel()), _stream(stream)))
+    return out
+
+
+def mustdrop_encode_merge_noalloc(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, kt, kh, kw, tau, key_budget, out: Dict,
+                                  stream=None) -> Dict:
+    """mustdrop_encode_merge on the library's static scratch buffer (no workspace argument; the call allocates
+    nothing, so `out` must hold every output tensor; "a_cls" and "window_sim" may be None)."""
+    B, M, D = x.shape
+    if key_budget > 0:
+        Hc, dc = q_cls.shape[1], q_cls.shape[2]
+        qk_dtype = _dtype_code(q_cls)
+    else:
+        Hc, dc, qk_dtype = 1, D, _dtype_code(x)
+    _check(library().mustdrop_encode_merge_noalloc(
+        _ptr(x), C.c_int(_dtype_code(x)), _ptr(q_cls), _ptr(k_cls), C.c_int(qk_dtype), _ptr(mass_in), _ptr(valid),
+        C.c_int(B), C.c_int(T), C.c_int(Hg), C.c_int(Wg), C.c_int(D), C.c_int(Hc), C.c_int(dc),
+        C.c_int(kt), C.c_int(kh), C.c_int(kw), C.c_float(tau), C.c_int(key_budget),
+        _ptr(out["out_x"]), _ptr(out["out_index"]), _ptr(out["out_mass"]), _ptr(out["out_is_key"]),
+        _ptr(out["out_valid"]), _ptr(out["out_count"]), _ptr(out["key_index"]),
+        _ptr(out.get("a_cls")), _ptr(out.get("window_sim")), _stream(stream)))
     return out
 
 

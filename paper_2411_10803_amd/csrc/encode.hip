@@ -11,6 +11,8 @@
 #include "md_device.hpp"
 #include "md_host.hpp"
 
+#include <mutex>
+
 namespace md {
 namespace {
 
@@ -939,6 +941,66 @@ extern "C" int mustdrop_encode_merge(
     return encode_merge_impl(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, B, T, Hg, Wg, D, Hc, dc, kt, kh, kw, tau,
                              0, key_budget, 0.f, out_x, out_index, out_mass, out_is_key, out_valid, out_count,
                              key_index, nullptr, a_cls_out, window_sim_out, workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same stage for callers that cannot hand over (or allocate) a workspace: the scratch memory is a
+// file-scope device array.  Every GPU the library runs on holds its own copy at its own address; the
+// host-side name of the array is only a handle, the address a kernel can use comes from
+// hipGetSymbolAddress (once per device, kept).
+static __device__ __align__(256) unsigned char scratch[MUSTDROP_STATIC_SCRATCH_BYTES];
+
+namespace md {
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (resolved at the first call on that device).
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(MD_EHIP, "encode_merge_noalloc: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MD_EHIP, "encode_merge_noalloc: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(MD_EHIP, "encode_merge_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MD_OK;
+}
+}  // namespace
+}  // namespace md
+
+extern "C" int mustdrop_encode_merge_noalloc(
+    const void* x, md_dtype x_dtype,
+    const void* q_cls, const void* k_cls, md_dtype qk_dtype,
+    const float* mass_in, const uint8_t* valid,
+    int B, int T, int Hg, int Wg, int D, int Hc, int dc,
+    int kt, int kh, int kw, float tau, int key_budget,
+    void* out_x, int32_t* out_index, float* out_mass, uint8_t* out_is_key, uint8_t* out_valid,
+    int32_t* out_count, int32_t* key_index,
+    float* a_cls_out, float* window_sim_out, void* stream)
+{
+    clear_error();
+    if (B <= 0 || T <= 0 || Hg <= 0 || Wg <= 0 || kt <= 0 || kh <= 0 || kw <= 0)
+        return fail(MD_EINVAL, "encode_merge_noalloc: B, T, Hg, Wg and the window sizes must be positive");
+    if ((long)T * Hg * Wg > (1l << 24) || (long)B * T * Hg * Wg > (1l << 30))
+        return fail(MD_ESHAPE, "encode_merge_noalloc: too many tokens");
+    const size_t need = mustdrop_encode_merge_workspace_bytes(B, T, Hg, Wg, key_budget > 0 ? Hc : 0, kt, kh, kw);
+    if (need > (size_t)MUSTDROP_STATIC_SCRATCH_BYTES)
+        return fail(MD_EWORKSPACE, "encode_merge_noalloc: this shape needs %zu bytes of scratch memory, the static buffer holds %zu; "
+                    "use mustdrop_encode_merge with a workspace", need, (size_t)MUSTDROP_STATIC_SCRATCH_BYTES);
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != MD_OK) return rc;
+    return encode_merge_impl(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, B, T, Hg, Wg, D, Hc, dc, kt, kh, kw, tau,
+                             0, key_budget, 0.f, out_x, out_index, out_mass, out_is_key, out_valid, out_count,
+                             key_index, nullptr, a_cls_out, window_sim_out, ptr, (size_t)MUSTDROP_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int mustdrop_encode_merge_adaptive(

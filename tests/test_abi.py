@@ -108,6 +108,16 @@ def test_prefill_argument_errors(lib):
 ACC, IDS, PROT, LEN = P(0x200000), P(0x300000), P(0x400000), P(0x500000)   # the small state arrays, disjoint
 
 
+def test_noalloc_rejects_shapes_beyond_the_static_buffer(lib):
+    # host-side arithmetic only: the size check comes before anything touches a device
+    def call(B, T):
+        return lib.mustdrop_encode_merge_noalloc(X, 1, X, X, 1, None, None, B, T, 24, 24, 1024, 16, 64, 1, 2, 2, F(0.9), 32,
+                                                 P(0x9000000), X, X, X, X, X, X, None, None, None)
+    assert lib.mustdrop_encode_merge_workspace_bytes(64, 8, 24, 24, 16, 1, 2, 2) > (8 << 20)
+    assert call(64, 8) == 5 and b"static buffer" in lib.mustdrop_last_error()
+    assert call(0, 1) == 1
+
+
 def decode(lib, **kw):
     a = dict(q=P(0x1000), k=P(0x10000000), v=P(0x80000000), B=2, Lcap=4096, H=32, d=128, budget=1024,
              ws=P(0x100000000), wsb=1 << 30)
