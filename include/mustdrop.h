@@ -50,7 +50,7 @@ typedef enum { MD_FILTER_BUDGET = 0, MD_FILTER_THRESHOLD = 1 } md_filter_mode;
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* mustdrop_last_error(void);
 
-/* Library version, major*100 + minor. */
+/* Library version, major*100 + minor (2: mustdrop_prefill_filter takes row_lse). */
 int mustdrop_version(void);
 
 /* ------------------------------------------------------------------------------------------
@@ -154,6 +154,12 @@ int mustdrop_encode_merge_adaptive(
  *   k, v       [B, L, H, d] bf16;  hidden [B, L, C] bf16
  *   vis_valid  [B, Mv] u8 or NULL; txt_len [B] i32 or NULL (= N; text is padded at the tail);
  *   is_key     [B, Mv] u8 or NULL (no key tokens)
+ *   row_lse    [B, H, N] f32 or NULL.  The scores a[i][j] are a by-product of the layer's own attention
+ *              (Sec. 3.4); a flash-style attention kernel keeps, per head and query row, the natural-log
+ *              sum of exp(softmax_scale * q.k) over the keys that row sees.  Given those values for the text rows
+ *              (over the valid vision keys and the text keys 0..i, with this call's softmax_scale), the
+ *              library skips its own pass over K for the softmax normalisers and reads K once instead
+ *              of twice.  Entries of rows >= txt_len are ignored.  NULL: the library computes them.
  *   Rcap       capacity, in rows, of the kept-vision part of the outputs (>= budget in budget mode;
  *              use Mv in threshold mode).  The caller must size it for max(budget, #keys).
  *   hidden_out [B, Rcap+N, C], k_out, v_out [B, Rcap+N, H, d]; rows >= out_len[b] untouched
@@ -174,7 +180,7 @@ size_t mustdrop_prefill_filter_workspace_bytes(int B, int Mv, int N, int H, int 
 
 int mustdrop_prefill_filter(
     const void* q_txt, const void* k, const void* v, const void* hidden,
-    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key, const float* row_lse,
     int B, int Mv, int N, int H, int d, int C,
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,
@@ -278,7 +284,7 @@ typedef struct {
  * kv_out_layout: k_out and v_out over Rcap+N rows.  hidden and hidden_out stay [B, rows, C]. */
 int mustdrop_prefill_filter_strided(
     const void* q_txt, const void* k, const void* v, const void* hidden,
-    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key, const float* row_lse,
     int B, int Mv, int N, int H, int d, int C,
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,

@@ -139,6 +139,7 @@ def prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_
         "out_ids": np.full((B, Rcap + N), -1, dtype=np.int32),
         "score_global": np.zeros((B, Mv), dtype=np.float64),
         "score_indiv": np.zeros((B, Mv), dtype=np.float64),
+        "row_lse": np.zeros((B, H, N), dtype=np.float64),
     }
     rc = lib().mustdrop_prefill_filter_ref(
         _p(q_txt), _p(k), _p(v), _p(hidden), _p(vis_valid), _p(txt_len), _p(is_key),
@@ -147,7 +148,7 @@ def prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_
         C.c_int(Rcap),
         _p(out["hidden_out"]), _p(out["k_out"]), _p(out["v_out"]),
         _p(out["kept_index"]), _p(out["kept_count"]), _p(out["out_len"]), _p(out["out_protect"]), _p(out["out_ids"]),
-        _p(out["score_global"]), _p(out["score_indiv"]))
+        _p(out["score_global"]), _p(out["score_indiv"]), _p(out["row_lse"]))
     if rc != 0:
         raise ValueError(f"mustdrop_prefill_filter_ref: error {rc}")
     return out

@@ -316,8 +316,10 @@ int mustdrop_prefill_filter_ref(
     uint16_t* hidden_out, uint16_t* k_out, uint16_t* v_out,
     int32_t* kept_index, int32_t* kept_count,
     int32_t* out_len, uint8_t* out_protect, int32_t* out_ids,
-    double* score_global, double* score_indiv)
+    double* score_global, double* score_indiv, double* row_lse_out)
 {
+    /* row_lse_out [B][H][N] (optional): the softmax normaliser of every text row as the attention of Sec. 3.4
+       leaves it behind, ln sum_j exp(scale * q_i . k_j) over the keys the row sees (0 for rows >= txt_len). */
     if (B <= 0 || Mv <= 0 || N <= 0 || H <= 0 || d <= 0 || C <= 0 || Rcap <= 0) return REF_EINVAL;
     if (mode == REF_FILTER_BUDGET && (!(gamma > 0.0f) || !(alpha > 0.0f) || budget < 0)) return REF_EINVAL;
     const int L = Mv + N;
@@ -337,6 +339,7 @@ int mustdrop_prefill_filter_ref(
 
         /* a[i][j] = mean over heads of softmax_j(scale * q_i . k_j) over the keys visible to text row i */
         for (size_t t = 0; t < (size_t)N * Mv; ++t) a[t] = 0.0;
+        if (row_lse_out) for (size_t t = 0; t < (size_t)H * N; ++t) row_lse_out[(size_t)b * H * N + t] = 0.0;
         for (int h = 0; h < H; ++h)
         for (int i = 0; i < tl; ++i) {
             double mx = -INFINITY;
@@ -354,6 +357,7 @@ int mustdrop_prefill_filter_ref(
             for (int j = 0; j < L; ++j) if (lg[j] != -INFINITY) z += exp(lg[j] - mx);
             for (int j = 0; j < Mv; ++j)
                 if (lg[j] != -INFINITY) a[(size_t)i * Mv + j] += exp(lg[j] - mx) / z / (double)H;
+            if (row_lse_out) row_lse_out[((size_t)b * H + h) * N + i] = mx + log(z);
         }
 
         /* Eq. 8: V_j = sum_i a_ij ; Eq. 10: I_j = max_i a_ij ; Eq. 9 right side: G = sum_j V_j */

@@ -219,8 +219,8 @@ def mustdrop_encode_merge_adaptive(x, q_cls, k_cls, mass_in, valid, T, Hg, Wg, k
 
 def mustdrop_prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_scale, mode, budget,
                             gamma, alpha, Rcap=None, out: Optional[Dict] = None, workspace=None, stream=None,
-                            want_scores=True) -> Dict:
-    """Sec. 3.4.  q_txt [B,N,H,d]; k, v [B,L,H,d]; hidden [B,L,C] (bf16)."""
+                            want_scores=True, row_lse=None) -> Dict:
+    """Sec. 3.4.  q_txt [B,N,H,d]; k, v [B,L,H,d]; hidden [B,L,C] (bf16); row_lse [B,H,N] f32 or None."""
     import torch
     B, N, H, d = q_txt.shape
     Cdim = hidden.shape[2]
@@ -244,7 +244,7 @@ def mustdrop_prefill_filter(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv,
         workspace = prefill_workspace(B, Mv, N, H, Rcap, dev)
     out["workspace"] = workspace
     _check(library().mustdrop_prefill_filter(
-        _ptr(q_txt), _ptr(k), _ptr(v), _ptr(hidden), _ptr(vis_valid), _ptr(txt_len), _ptr(is_key),
+        _ptr(q_txt), _ptr(k), _ptr(v), _ptr(hidden), _ptr(vis_valid), _ptr(txt_len), _ptr(is_key), _ptr(row_lse),
         C.c_int(B), C.c_int(Mv), C.c_int(N), C.c_int(H), C.c_int(d), C.c_int(Cdim),
         C.c_float(softmax_scale), C.c_int(mode), C.c_int(budget), C.c_float(gamma), C.c_float(alpha),
         C.c_int(Rcap),
@@ -296,7 +296,7 @@ def mustdrop_decode_keep(k_caches, v_caches, keep, acc, ids, protect, length, ev
 
 
 def mustdrop_prefill_filter_strided(q_txt, k, v, hidden, vis_valid, txt_len, is_key, Mv, softmax_scale, mode, budget,
-                                    gamma, alpha, out: Dict, Rcap=None, workspace=None, stream=None) -> Dict:
+                                    gamma, alpha, out: Dict, Rcap=None, workspace=None, stream=None, row_lse=None) -> Dict:
     """Sec. 3.4 on Q / K / V in any layout: q_txt, k, v and out["k_out"], out["v_out"] are [B, tokens, H, d] VIEWS
     (e.g. a permuted head-major tensor); their strides are handed over as md_kv_layout.  k and v share one
     layout, k_out and v_out another.  `out` must hold every output tensor (see mustdrop_prefill_filter)."""
@@ -311,7 +311,7 @@ def mustdrop_prefill_filter_strided(q_txt, k, v, hidden, vis_valid, txt_len, is_
     out["workspace"] = workspace
     lq, lkv, lo = _layout(q_txt), _layout(k), _layout(out["k_out"])
     _check(library().mustdrop_prefill_filter_strided(
-        _view_ptr(q_txt), _view_ptr(k), _view_ptr(v), _ptr(hidden), _ptr(vis_valid), _ptr(txt_len), _ptr(is_key),
+        _view_ptr(q_txt), _view_ptr(k), _view_ptr(v), _ptr(hidden), _ptr(vis_valid), _ptr(txt_len), _ptr(is_key), _ptr(row_lse),
         C.c_int(B), C.c_int(Mv), C.c_int(N), C.c_int(H), C.c_int(d), C.c_int(Cdim),
         C.c_float(softmax_scale), C.c_int(mode), C.c_int(budget), C.c_float(gamma), C.c_float(alpha),
         C.c_int(Rcap),

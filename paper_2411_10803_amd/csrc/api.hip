@@ -81,4 +81,4 @@ extern "C" int mustdrop_profile_stop(char* names, float* total_ms, int* calls, i
 }
 
 extern "C" const char* mustdrop_last_error(void) { return md::error_buffer(); }
-extern "C" int mustdrop_version(void) { return 1; }
+extern "C" int mustdrop_version(void) { return 2; }

@@ -3,13 +3,16 @@
 //
 // The column statistics V_j = sum_i a_ij and I_j = max_i a_ij need the row softmax normaliser of
 // every text row over the WHOLE key axis, and the head mean has to be taken before the max over
-// text rows.  So the scores take two sweeps over K:
+// text rows.  The normalisers are a by-product of the layer's own attention (Sec. 3.4): a caller
+// that has them (row_lse) pays one sweep over K; otherwise a first sweep computes them:
 //   prefill_rowstats_kernel  per (sample, head, key chunk): S = K Q^T on the MFMA units, online
-//                            (max, sum-exp) per text row -> partial row statistics
-//   prefill_colscore_kernel  per (sample, 32 vision keys): waves split the heads, recompute S,
-//                            p = exp(s - m)/Z, accumulate the head mean in registers, reduce the
-//                            waves through LDS in a fixed order, column sum / max -> V_j, I_j
-// The N x Mv probability matrix is never written to memory.
+//                            (max, sum-exp) per text row -> row statistics (prefill_cstat_kernel
+//                            merges the chunks); with row_lse only prefill_qpack_kernel runs
+//   prefill_colscore_kernel  persistent blocks over units of (128 vision keys, one head): recompute
+//                            S, p = exp(s - m)/Z, accumulate the head mean a[i][j] of a 128-key tile
+//                            in registers; a block's share of a tile is written as one piece
+//   prefill_colfix_kernel    sums a tile's pieces in a fixed order, column sum / max -> V_j, I_j
+// The N x Mv probability matrix of a head is never written to memory.
 //   prefill_select_kernel    per sample: G, the filter rule (threshold) or radix top-k (budget),
 //                            prefix sum -> kept_index, row map for the copy
 //   prefill_compact_kernel   one block per output row: 16-byte vector copies of hidden, K, V rows
@@ -24,12 +27,14 @@ namespace md {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kColKeys = 128;                        // vision keys per unit of the column-score sweep
+constexpr int kMaxChunks = 8;                        // key chunks per (sample, head) in the row-statistics sweep, at most
 
 struct PrefillDims {
     int B, Mv, N, H, d, C, L;
     int nch;          // key chunks per (sample, head) in the row-statistics sweep
-    int chunk;        // keys per chunk (multiple of 32)
-    int Npad;         // 32 * NB
+    int chunk;        // keys per chunk (multiple of 128)
+    int Npad;         // 32 * (number of 32-row text blocks)
     int Rcap;
     KvLayout q, kv;   // element strides of q_txt and of k (v shares them)
 };
@@ -37,60 +42,70 @@ struct PrefillDims {
 // key row of accumulator register r in the 32x32 result tile
 __device__ __forceinline__ int tile_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
-// A 32-row operand tile (32 keys or 32 text rows of one head, 16*KS bf16 each) on its way from
-// global memory to MFMA fragments.  Global loads are coalesced: a row's head slice is CH = 2*KS
-// consecutive 16-byte chunks, 64/CH rows per load instruction.  The tile is then written to a
-// wave-private LDS buffer (row pitch padded by 16 bytes: conflict-free 128-bit reads) and read back
-// in fragment layout: lane (g = lane/32, r = lane%32) holds row r, chunks 2*ks+g, ks = 0..KS-1.
-template <int KS>
-struct OperandTile {
-    static constexpr int CH = 2 * KS;
-    static constexpr int ROWS_PER_LOAD = kWave / CH;
-    static constexpr int PITCH = CH * 16 + 16;
-    static constexpr int BYTES = 32 * PITCH;
+#define MD_VM_WAIT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-    // rows row0..row0+31 of a matrix whose rows are `row_stride` elements apart; rows >= nrows read as zero
-    __device__ static __forceinline__ void gload(const uint16_t* base, long row_stride, int row0, int nrows, int lane,
-                                                 u32x4 (&st)[KS]) {
-        const int chunk = lane % CH, sub = lane / CH;
+// Every LDS access of this wave has completed, then the block barrier.  (The loads that write LDS
+// directly are counted by vmcnt: the caller waits for those itself.)
+__device__ __forceinline__ void block_sync_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// Rows of an MFMA operand (one head slice of a key or a text query: 16*KS bf16 = CH chunks of 16
+// bytes) on their way from global memory to MFMA fragments, through LDS.
+//   global -> LDS  buffer loads that write LDS directly (no staging registers): a wave instruction
+//                  moves 1 KiB = RPL whole rows, coalesced; rows outside the buffer resource's range
+//                  are never fetched.
+//   LDS layout     rows unpadded (pitch ROWB); the chunk a lane fetches for position `pos` of row
+//                  `row` is pos ^ swz(row), so that the 128-bit fragment reads below (32 rows, one
+//                  chunk index) spread over all banks.
+//   LDS -> frags   lane (g = lane/32, r = lane%32) of the 32x32x16 MFMA holds row r, chunks 2*ks+g.
+template <int KS>
+struct LdsRows {
+    static constexpr int CH = 2 * KS;
+    static constexpr int ROWB = CH * 16;             // 256 (d = 128) or 128 (d = 64) bytes
+    static constexpr int RPL = kWave / CH;           // rows per load instruction
+    static_assert(KS == 4 || KS == 8, "rows of 128 or 256 bytes");
+    __device__ static __forceinline__ int swz(int row) { return KS == 8 ? (row & 15) : ((row >> 1) & 7); }
+
+    // One wave instruction: rows slot_row .. slot_row+RPL-1 of the LDS block at `lds_base` (wave-uniform)
+    // receive the global rows grow0+slot_row.. of the matrix behind `rs` (rows row_bytes apart).
+    // `live` (wave-uniform) false: nothing is fetched.
+    __device__ static __forceinline__ void issue(__amdgpu_buffer_rsrc_t rs, uint32_t row_bytes, int grow0, int slot_row,
+                                                 char* lds_base, int lane, bool live) {
+        const int row = slot_row + lane / CH, pos = lane % CH;
+        const uint32_t off = live ? (uint32_t)(grow0 + row) * row_bytes + (uint32_t)((pos ^ swz(row)) << 4) : 0xFFFFFF00u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(lds_base + slot_row * ROWB), 16, off, 0, 0, 0);
+    }
+    // LDS byte address of this lane's fragment row in the 32-row tile at `tile` (aligned to 32*ROWB),
+    // with the swizzle and the lane half folded in; chunk index ks is applied with XOR.
+    __device__ static __forceinline__ uint32_t frag_base(const char* tile, int lane) {
+        const int r = lane & 31, g = lane >> 5;
+        const uint32_t a = (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<char*>(tile);
+        return (a + r * ROWB) ^ (uint32_t)((g << 4) ^ (swz(r) << 4));
+    }
+    // the KS fragments of a tile; returns once they are in registers
+    __device__ static __forceinline__ void frags(uint32_t fb, bf16x8 (&f)[KS]) {
 #pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            const int r = row0 + t * ROWS_PER_LOAD + sub;
-            if (r < nrows) st[t] = *reinterpret_cast<const u32x4*>(base + (long)r * row_stride + chunk * 8);
-            else st[t] = u32x4{0u, 0u, 0u, 0u};
+        for (int ks = 0; ks < KS; ++ks) {
+            uint32_t a;
+            asm volatile("v_xor_b32 %1, %2, %3\n\tds_read_b128 %0, %1" : "=v"(f[ks]), "=&v"(a) : "v"(ks << 5), "v"(fb) : "memory");
         }
-    }
-    // The same for a tile whose 32 rows all exist.  tile_base: first row of the tile (wave-uniform),
-    // lane_off: from lane_offset(); the addresses are a scalar base plus a tile-invariant lane offset,
-    // so a load costs no vector arithmetic.
-    __device__ static __forceinline__ uint32_t lane_offset(long row_stride, int lane) {
-        return (uint32_t)(((lane / CH) * row_stride + (lane % CH) * 8) * 2);
-    }
-    __device__ static __forceinline__ void gload_full(const uint16_t* tile_base, long row_stride, uint32_t lane_off,
-                                                      u32x4 (&st)[KS]) {
-#pragma unroll
-        for (int t = 0; t < KS; ++t)
-            st[t] = *reinterpret_cast<const u32x4*>(
-                reinterpret_cast<const char*>(tile_base + (long)t * ROWS_PER_LOAD * row_stride) + lane_off);
-    }
-    // either of the two, by a wave-uniform test
-    __device__ static __forceinline__ void gload_any(const uint16_t* base, long row_stride, int row0, int nrows, int lane,
-                                                     uint32_t lane_off, u32x4 (&st)[KS]) {
-        if (row0 + 32 <= nrows) gload_full(base + (long)row0 * row_stride, row_stride, lane_off, st);
-        else gload(base, row_stride, row0, nrows, lane, st);
-    }
-    __device__ static __forceinline__ void to_lds(char* tile, int lane, const u32x4 (&st)[KS]) {
-        const int chunk = lane % CH, sub = lane / CH;
-#pragma unroll
-        for (int t = 0; t < KS; ++t)
-            *reinterpret_cast<u32x4*>(tile + (t * ROWS_PER_LOAD + sub) * PITCH + chunk * 16) = st[t];
-    }
-    __device__ static __forceinline__ void frags(const char* tile, int lane, bf16x8 (&f)[KS]) {
-        const char* p = tile + (lane & 31) * PITCH + (lane >> 5) * 16;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) f[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 32);
+        if constexpr (KS == 8)
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]) :: "memory");
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) :: "memory");
     }
 };
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_buffer(const uint16_t* base, long rows, long row_stride, int d) {
+    // rows [0, rows) of `d` elements each, row_stride elements apart; anything beyond reads as "not there"
+    const long bytes = rows > 0 ? ((rows - 1) * row_stride + d) * 2 : 0;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)bytes, 0x00020000);
+}
 
 // Row statistics folded into one constant: a probability of the head mean is
 // exp2(s*scale*log2e + c) with c = -m - log2(Z) - log2(H); text rows beyond txt_len get -inf (-> 0).
@@ -98,182 +113,254 @@ __device__ __forceinline__ float fold_stats(float m, float z, bool row_ok, int H
     return (row_ok && z > 0.f) ? -m - fast_log2(z) - fast_log2((float)H) : -INFINITY;
 }
 
-// LDS traffic between lanes of one wave: LDS operations of a wave execute in order, the fence keeps
-// the compiler from moving the reads above the writes.
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+// The 32 text-query rows i0.. of head slice `qb` as MFMA fragments: global -> this wave's LDS tile ->
+// registers.  Rows at or beyond `tl` come out as zero rows.
+template <int KS>
+__device__ __forceinline__ void load_query_frags(const uint16_t* qb, long tok_stride, int d, int i0, int tl, char* tile,
+                                                 int lane, bf16x8 (&qf)[KS]) {
+    using T = LdsRows<KS>;
+    const __amdgpu_buffer_rsrc_t rq = row_buffer(qb, tl, tok_stride, d);
+#pragma unroll
+    for (int t = 0; t < 32 / T::RPL; ++t) T::issue(rq, (uint32_t)(tok_stride * 2), i0, t * T::RPL, tile, lane, true);
+    MD_VM_WAIT(0);
+    T::frags(T::frag_base(tile, lane), qf);
+    const bool row_ok = i0 + (lane & 31) < tl;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        if (!row_ok) qf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
 }
 
 // ---------------------------------------------------------------------------------------------
-// Sweep 1: row statistics.  Block = (key chunk x text group, head, sample), 4 waves; every wave
-// walks its share of the chunk's 32-key tiles with the next tile's global loads in flight during
-// the MFMAs.  A block covers NB <= 2 blocks of 32 text rows (one "text group"); longer prompts are
-// split over blockIdx.x.  Chunk 0 also stores the text-query fragments in fragment-major order
-// (qfrag), rows beyond txt_len zeroed, so that sweep 2 reads them with coalesced 16-byte loads.
-template <int NB, int KS>
+// Sweep 1: row statistics.  Block = (key chunk x text group, head, sample), 4 waves.  The waves of a
+// block share every K tile through LDS: wave w works on text block w % NBW of the group and on key
+// tile w / NBW of the TW = 4/NBW tiles in flight per step, so a wave keeps the fragments of ONE
+// 32-row text block in registers and K is read once per block.  K tiles stream through S LDS slots
+// (filled S-1 steps ahead, no staging registers); one block barrier per step.  Inside a step the
+// MFMA chain of the current tile is issued before the softmax arithmetic of the previous one (two
+// accumulators), so the matrix unit and the vector ALUs overlap within a wave.
+// Chunk 0 also stores the text-query fragments in fragment-major order (qfrag), rows beyond txt_len
+// zeroed, for the second sweep.
+template <int KS>
+__device__ __forceinline__ f32x16 score_tile(const bf16x8 (&kf)[KS], const bf16x8 (&qf)[KS]) {
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], acc, 0, 0, 0);
+    return acc;
+}
+
+// Online (max, sum of exp2) update of one lane's text row with the 16 keys it holds of a tile.
+// Fast form: every key of the tile is visible -- straight-line code (so that the compiler can
+// interleave it with the MFMA chain of the next tile), maximum and sum as trees.
+__device__ __forceinline__ void online_update_all(const f32x16& acc, float scale_log2e, float& m, float& z) {
+    const float b0 = fmaxf(fmaxf(acc[0], acc[1]), acc[2]), b1 = fmaxf(fmaxf(acc[3], acc[4]), acc[5]);
+    const float b2 = fmaxf(fmaxf(acc[6], acc[7]), acc[8]), b3 = fmaxf(fmaxf(acc[9], acc[10]), acc[11]);
+    const float b4 = fmaxf(fmaxf(acc[12], acc[13]), acc[14]);
+    const float bm = fmaxf(fmaxf(fmaxf(b0, b1), b2), fmaxf(fmaxf(b3, b4), acc[15]));
+    const float mn = fmaxf(m, bm * scale_log2e);     // the scale is positive: applied after the maximum
+    const float nmn = -mn;
+    float e[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) e[r] = fast_exp2(fmaf(acc[r], scale_log2e, nmn));
+    const float s = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7])) +
+                    (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
+    z = fmaf(z, fast_exp2(m - mn), s);               // m = -inf at the first tile: exp2(-inf) = 0
+    m = mn;
+}
+// General form: `vis` bit r set = accumulator r is a visible key.
+__device__ __forceinline__ void online_update_masked(f32x16 acc, uint32_t vis, float scale_log2e, float& m, float& z) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (!((vis >> r) & 1u)) acc[r] = -INFINITY;
+    float bm = acc[0];
+#pragma unroll
+    for (int r = 1; r < 16; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1 < 16 ? r + 1 : r]);
+    const float mn = fmaxf(m, bm * scale_log2e);
+    if (mn > -INFINITY) {
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            s0 += fast_exp2(fmaf(acc[r], scale_log2e, -mn));
+            s1 += fast_exp2(fmaf(acc[r + 1], scale_log2e, -mn));
+        }
+        z = fmaf(z, fast_exp2(m - mn), s0 + s1);
+        m = mn;
+    }
+}
+
+// The compiler's scheduler is asked to issue one MFMA, then a few vector and transcendental
+// instructions, and so on: a wave issues in order, and a chain of dependent MFMAs issued back to back
+// would hold up the independent vector work behind it.
+template <int KS>
+__device__ __forceinline__ void interleave_mfma_valu() {
+#pragma unroll
+    for (int q = 0; q < KS; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 48 / KS, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 16 / KS, 0);
+    }
+}
+
+template <int NBW, int KS>
 __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const uint16_t* __restrict__ q_txt, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len, PrefillDims p, float scale_log2e,
     float2* __restrict__ partial, float* __restrict__ cstat, bf16x8* __restrict__ qfrag)
 {
-    using Tile = OperandTile<KS>;
-    __shared__ __attribute__((aligned(16))) char s_tile[4][Tile::BYTES];
-    __shared__ float s_m[4][32 * NB], s_z[4][32 * NB];
+    using T = LdsRows<KS>;
+    constexpr int TW = 4 / NBW;                       // key tiles per step, one per tile lane
+    constexpr int S = TW == 1 ? 4 : 3;                // LDS slots
+    constexpr int SLOT_ROWS = 32 * TW, SLOT_BYTES = SLOT_ROWS * T::ROWB;
+    constexpr int NLW = SLOT_ROWS / T::RPL / 4;       // load instructions per wave and step
+    constexpr int QBYTES = 4 * 32 * T::ROWB;          // the four waves' query tiles during the prologue
+    constexpr bool EARLY0 = S * SLOT_BYTES >= QBYTES + SLOT_BYTES;   // the last slot is free meanwhile
+    static_assert(S * SLOT_BYTES >= QBYTES, "the query tiles are staged in the K slots");
+    __shared__ __attribute__((aligned(1024))) char s_k[S * SLOT_BYTES];
+    __shared__ float s_m[4][32], s_z[4][32];
     const int lane = lane_id(), wv = wave_id();
-    // Blocks go round-robin over the 8 XCDs in launch order.  With several text groups, the blocks that
-    // read the same K chunk (same chunk and head, different text group) are placed 8 apart in that order:
-    // same XCD, launched together, so the second reader finds the chunk in that XCD's L2.
-    int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y;
-    const int b = blockIdx.z;
-    const int ntg = gridDim.x / p.nch;
-    if (ntg > 1 && (p.nch * p.H) % 8 == 0) {
-        const int lin = blockIdx.x + gridDim.x * blockIdx.y;
-        const int r = lin % (8 * ntg), pair = lin / (8 * ntg) * 8 + r % 8;
-        tg = r / 8;
-        ch = pair % p.nch;
-        h = pair / p.nch;
-    }
-    const int i_base = tg * 32 * NB;                 // first text row of this block's group
-    const long tok_stride = p.kv.token;
+    const int nbw = wv % NBW, tw = wv / NBW;
+    const int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y, b = blockIdx.z;
+    const int nbg = tg * NBW + nbw;                   // 32-row text block of this wave
+    const int i0 = 32 * nbg;
+    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
     const uint16_t* kb = k + (long)b * p.kv.batch + (long)h * p.kv.head;
     const uint16_t* qb = q_txt + (long)b * p.q.batch + (long)h * p.q.head;
     const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
-    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
-    char* tile = s_tile[wv];
+    const __amdgpu_buffer_rsrc_t rk = row_buffer(kb, p.L, p.kv.token, p.d);
+    const uint32_t krow = (uint32_t)(p.kv.token * 2);
 
-    const int c0 = ch * p.chunk;
-    const int c1 = min(c0 + p.chunk, p.L);
-    int j0 = c0 + 32 * wv;
-    u32x4 st[KS];
-    // validity of this lane's key (lane % 32) in the tile that is in flight; fetched with the tile so
-    // that its latency hides behind the previous tile's arithmetic
-    // (kept as the loaded byte until the next iteration: turning it into a lane mask right away would
-    // make the wave wait for the load, and with it for the tile that was requested just before)
-    auto key_valid = [&](int j) -> uint32_t {
-        const int jl = j + (lane & 31);
-        return vb ? (uint32_t)vb[min(jl, p.Mv - 1)] : 1u;
+    const int c0 = ch * p.chunk, c1 = min(c0 + p.chunk, p.L);
+    const int nit = (c1 - c0 + SLOT_ROWS - 1) / SLOT_ROWS;                   // steps of this block
+    // step g's tiles go to slot (g + S - 1) % S: step 0 into the last slot, which the query staging leaves free
+    auto issue_step = [&](int g) {
+        char* slot = s_k + ((g + S - 1) % S) * SLOT_BYTES;
+        const int row0 = c0 + g * SLOT_ROWS;
+#pragma unroll
+        for (int t = 0; t < NLW; ++t) T::issue(rk, krow, row0, (t * 4 + wv) * T::RPL, slot, lane, true);
     };
-    uint32_t v_nxt = 0;
-    const uint32_t lane_off = Tile::lane_offset(tok_stride, lane);
-    if (j0 < c1) {
-        Tile::gload_any(kb, tok_stride, j0, p.L, lane, lane_off, st);
-        v_nxt = key_valid(j0);
-    }
-
-    // text-query fragments of this head: through the same LDS tile, one 32-row block at a time
-    // (all loads are issued before the first LDS pass: the fences below would otherwise serialise them)
-    bf16x8 qf[NB][KS];
-    constexpr int NST = NB < 2 ? NB : 2;             // text blocks staged at a time (32 registers each)
+    // Validity of this lane's key (lane % 32) in the tiles of the steps g0 .. g0+63, one bit per step.
+    // Fetched in batches of 64 steps: a load inside the steady loop would have the compiler wait for
+    // everything in flight, the K tiles included, once per step.
+    auto key_valid_bits = [&](int g0) -> uint64_t {
+        if (!vb) return ~0ull;
+        uint64_t bits = 0;
+        for (int u0 = 0; u0 < 64 && g0 + u0 < nit; u0 += 16) {
+            uint32_t raw[16];
 #pragma unroll
-    for (int nb0 = 0; nb0 < NB; nb0 += NST) {
-        u32x4 sq[NST][KS];
+            for (int u = 0; u < 16; ++u)             // unconditional loads from clamped addresses, 16 in flight
+                raw[u] = vb[min(c0 + ((g0 + u0 + u) * TW + tw) * 32 + (lane & 31), p.Mv - 1)];
 #pragma unroll
-        for (int e = 0; e < NST; ++e)
-            Tile::gload(qb, p.q.token, i_base + 32 * (nb0 + e), tl, lane, sq[e]);   // rows >= txt_len read as zero
-#pragma unroll
-        for (int e = 0; e < NST; ++e) {
-            const int nb = nb0 + e;
-            Tile::to_lds(tile, lane, sq[e]);
-            wave_lds_sync();
-            Tile::frags(tile, lane, qf[nb]);
-            wave_lds_sync();
-            const int nbg = tg * NB + nb;            // 32-row block index within the padded text axis
-            if (ch == 0 && wv == 0 && nbg < p.Npad / 32) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[nb][ks];
-            }
+            for (int u = 0; u < 16; ++u) bits |= (uint64_t)(raw[u] != 0) << (u0 + u);
         }
-    }
+        return bits;
+    };
 
-    float m[NB], z[NB];
+    if (EARLY0 && nit > 0) issue_step(0);
+    bf16x8 qf[KS];
+    load_query_frags<KS>(qb, p.q.token, p.d, i0, tl, s_k + wv * 32 * T::ROWB, lane, qf);
+    if (ch == 0 && tw == 0 && nbg < p.Npad / 32) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) { m[nb] = -INFINITY; z[nb] = 0.f; }
+        for (int ks = 0; ks < KS; ++ks)
+            qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[ks];
+    }
+    uint64_t visbits = key_valid_bits(0);
+    block_sync_lds();                                 // every wave has its query fragments: the slots are free
+    if (!EARLY0 && nit > 0) issue_step(0);
+#pragma unroll
+    for (int g = 1; g < S - 1; ++g)
+        if (g < nit) issue_step(g);
 
-    for (; j0 < c1; j0 += 32 * 4) {
-        Tile::to_lds(tile, lane, st);
-        wave_lds_sync();
+    float m = -INFINITY, z = 0.f;
+    const int i = i0 + (lane & 31);
+    // what the arithmetic of a finished tile needs besides its accumulator
+    struct Pending { bool all; uint32_t vis; };
+    auto visibility = [&](int g) -> Pending {
+        const int j0 = c0 + (g * TW + tw) * 32;
+        const bool v_ok = ((visbits >> (g & 63)) & 1ull) != 0 && j0 + (lane & 31) < p.Mv;
+        const uint32_t vmask = (uint32_t)__ballot(v_ok);     // the tile's 32 keys (vision keys only)
+        Pending pd;
+        pd.all = j0 + 32 <= p.Mv && vmask == 0xFFFFFFFFu;
+        pd.vis = 0xFFFFu;
+        if (!pd.all) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile_row(r, lane), j = j0 + row;
+                const bool vis = j < p.Mv ? ((vmask >> row) & 1u) : (j < c1 && (j - p.Mv) <= i);
+                bits |= (vis ? 1u : 0u) << r;
+            }
+            pd.vis = bits;
+        }
+        return pd;
+    };
+    // Step g: wait for its tiles, refill the slot of step g-1, fragments of this wave's tile.
+    auto fetch = [&](int g, bf16x8 (&kf)[KS]) {
+        if (g + S - 2 < nit) { MD_VM_WAIT((S - 2) * NLW); } else { MD_VM_WAIT(0); }   // this wave's part of step g has landed
+        block_sync_lds();                             // ... and everyone else's; step g-1's slot is free
+        if (g + S - 1 < nit) issue_step(g + S - 1);
+        T::frags(T::frag_base(s_k + ((g + S - 1) % S) * SLOT_BYTES + tw * 32 * T::ROWB, lane), kf);
+    };
+    // The MFMA chain of step g is issued together with the arithmetic on the tile of step g-1.
+    auto step = [&](int g, f32x16& acc_new, const f32x16& acc_old, Pending& pend) {
         bf16x8 kf[KS];
-        Tile::frags(tile, lane, kf);
-        wave_lds_sync();
-        const bool v_ok = v_nxt != 0 && j0 + (lane & 31) < p.Mv;
-        if (j0 + 32 * 4 < c1) {                                                 // prefetch
-            Tile::gload_any(kb, tok_stride, j0 + 32 * 4, p.L, lane, lane_off, st);
-            v_nxt = key_valid(j0 + 32 * 4);
+        fetch(g, kf);
+        if (pend.all) {
+            acc_new = score_tile<KS>(kf, qf);
+            online_update_all(acc_old, scale_log2e, m, z);
+            interleave_mfma_valu<KS>();
+        } else {
+            acc_new = score_tile<KS>(kf, qf);
+            online_update_masked(acc_old, pend.vis, scale_log2e, m, z);
         }
-        // validity of the 32 keys of this tile as a bit mask (vision keys only)
-        const uint32_t vmask = (uint32_t)__ballot(v_ok);
-        // three wave-uniform cases: a vision tile without holes, a vision tile with dropped keys,
-        // and a tile that reaches into the text keys (causal mask, per text row)
-        const bool vision_tile = j0 + 32 <= p.Mv;
-        const bool all_visible = vision_tile && vmask == 0xFFFFFFFFu;
-        const uint32_t mine = vmask >> (4 * (lane >> 5));   // tile_row(r, lane) = 8*(r/4) + 4*(lane/32) + r%4
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            f32x16 acc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[nb][ks], acc, 0, 0, 0);
-            // invisible entries become -inf; the positive scale is applied after the maximum
-            float bm = -INFINITY;
-            if (all_visible) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) bm = fmaxf(bm, acc[r]);
-            } else if (vision_tile) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    if (!((mine >> (8 * (r >> 2) + (r & 3))) & 1u)) acc[r] = -INFINITY;
-                    bm = fmaxf(bm, acc[r]);
-                }
-            } else {
-                const int i = i_base + 32 * nb + (lane & 31);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = tile_row(r, lane);
-                    const int j = j0 + row;
-                    const bool vis = j < p.Mv ? ((vmask >> row) & 1u) : (j < p.L && (j - p.Mv) <= i);
-                    if (!vis) acc[r] = -INFINITY;
-                    bm = fmaxf(bm, acc[r]);
-                }
-            }
-            const float mn = fmaxf(m[nb], bm * scale_log2e);
-            if (mn > -INFINITY) {
-                float s = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(acc[r], scale_log2e, -mn));
-                z[nb] = z[nb] * fast_exp2(m[nb] - mn) + s;
-                m[nb] = mn;
-            }
-        }
+        pend = visibility(g);
+        if ((g & 63) == 63 && g + 1 < nit) visbits = key_valid_bits(g + 1);   // (drains the loads in flight: once per 64 steps)
+    };
+    f32x16 accA, accB;
+    Pending pend{true, 0xFFFFu};
+    if (nit > 0) {
+        bf16x8 kf[KS];
+        fetch(0, kf);
+        accA = score_tile<KS>(kf, qf);
+        pend = visibility(0);
     }
-    // merge the two lane halves (same text row, the other 16 keys), then the four waves
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const float mo = __shfl_xor(m[nb], 32, kWave), zo = __shfl_xor(z[nb], 32, kWave);
-        const float mn = fmaxf(m[nb], mo);
+    int g = 1;
+    for (; g + 1 < nit; g += 2) {
+        step(g, accB, accA, pend);
+        step(g + 1, accA, accB, pend);
+    }
+    if (g < nit) {
+        step(g, accB, accA, pend);
+        if (pend.all) online_update_all(accB, scale_log2e, m, z); else online_update_masked(accB, pend.vis, scale_log2e, m, z);
+    } else if (nit > 0) {
+        if (pend.all) online_update_all(accA, scale_log2e, m, z); else online_update_masked(accA, pend.vis, scale_log2e, m, z);
+    }
+    MD_VM_WAIT(0);
+    // merge the two lane halves (same text row, the other 16 keys), then the tile lanes
+    {
+        const float mo = __shfl_xor(m, 32, kWave), zo = __shfl_xor(z, 32, kWave);
+        const float mn = fmaxf(m, mo);
         float zn = 0.f;
-        if (mn > -INFINITY) zn = z[nb] * fast_exp2(m[nb] - mn) + zo * fast_exp2(mo - mn);
-        if (lane < 32) { s_m[wv][32 * nb + lane] = mn; s_z[wv][32 * nb + lane] = zn; }
+        if (mn > -INFINITY) zn = z * fast_exp2(m - mn) + zo * fast_exp2(mo - mn);
+        if (lane < 32) { s_m[wv][lane] = mn; s_z[wv][lane] = zn; }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < 32 * NB; i += blockDim.x) {
+    if (threadIdx.x < 32 * NBW) {
+        const int nb = threadIdx.x >> 5, r = threadIdx.x & 31;
         float mn = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) mn = fmaxf(mn, s_m[w][i]);
+        for (int t = 0; t < TW; ++t) mn = fmaxf(mn, s_m[t * NBW + nb][r]);
         float zn = 0.f;
         if (mn > -INFINITY) {
 #pragma unroll
-            for (int w = 0; w < 4; ++w) zn += s_z[w][i] * fast_exp2(s_m[w][i] - mn);
+            for (int t = 0; t < TW; ++t) zn += s_z[t * NBW + nb][r] * fast_exp2(s_m[t * NBW + nb][r] - mn);
         }
-        if (i_base + i < p.Npad) {
+        const int ii = 32 * (tg * NBW + nb) + r;
+        if (ii < p.Npad) {
             if (p.nch == 1)     // the only chunk: fold the statistics right away (see fold_stats)
-                cstat[((long)b * p.H + h) * p.Npad + i_base + i] = fold_stats(mn, zn, i_base + i < tl, p.H);
+                cstat[((long)b * p.H + h) * p.Npad + ii] = fold_stats(mn, zn, ii < tl, p.H);
             else
-                partial[(((long)b * p.H + h) * p.nch + ch) * p.Npad + i_base + i] = make_float2(mn, zn);
+                partial[(((long)b * p.H + h) * p.nch + ch) * p.Npad + ii] = make_float2(mn, zn);
         }
     }
 }
@@ -299,155 +386,267 @@ __global__ __launch_bounds__(256) void prefill_cstat_kernel(
     cstat[e] = fold_stats(mn, zn, i < tl, p.H);
 }
 
+// The text-query fragments alone (the caller brought the row statistics, so sweep 1 does not run):
+// one wave per (sample, head, 32-row text block).
+template <int KS>
+__global__ __launch_bounds__(256) void prefill_qpack_kernel(
+    const uint16_t* __restrict__ q_txt, const int32_t* __restrict__ txt_len, const float* __restrict__ row_lse, PrefillDims p,
+    bf16x8* __restrict__ qfrag, float* __restrict__ cstat)
+{
+    using T = LdsRows<KS>;
+    __shared__ __attribute__((aligned(1024))) char s_q[4 * 32 * T::ROWB];
+    const int lane = lane_id(), wv = wave_id();
+    const int nbt = p.Npad / 32;
+    const long item = (long)blockIdx.x * 4 + wv;
+    if (item >= (long)p.B * p.H * nbt) return;
+    const int nbg = (int)(item % nbt), h = (int)(item / nbt % p.H), b = (int)(item / nbt / p.H);
+    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
+    bf16x8 qf[KS];
+    load_query_frags<KS>(q_txt + (long)b * p.q.batch + (long)h * p.q.head, p.q.token, p.d, 32 * nbg, tl,
+                         s_q + wv * 32 * T::ROWB, lane, qf);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qfrag[(item * KS + ks) * kWave + lane] = qf[ks];
+    // the caller's log-sum-exp (natural log, over the keys the row sees) as the folded statistic:
+    // exp(s*scale - lse) / H = exp2(s*scale*log2e + c), c = -lse*log2e - log2(H)
+    if (lane < 32) {
+        const int i = 32 * nbg + lane;
+        const float lse = row_lse[((long)b * p.H + h) * p.N + min(i, p.N - 1)];
+        cstat[((long)b * p.H + h) * p.Npad + i] = i < tl ? -lse * kLog2e - fast_log2((float)p.H) : -INFINITY;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
-// Sweep 2: column scores.  Block = (32 vision keys, sample), NW waves; wave w takes heads w, w+NW, ...
-// K tiles go global -> registers (prefetched one head ahead) -> wave-private LDS -> fragments;
-// text-query fragments come from qfrag with coalesced loads.  The row statistics are folded into one
-// constant per (head, text row): p = exp2(s*scale*log2e + c), c = -m - log2(Z*H), so a probability
-// costs one FMA and one exp2.  NB <= 4 = number of 32-row text blocks of this launch, starting at
-// block nb0: prompts of more than 128 rows take one launch per 128 rows, each writing its own
-// partial column sums and maxima, merged by prefill_merge_groups_kernel.
-template <int NB, int KS, int NW>
-__global__ __launch_bounds__(64 * NW) void prefill_colscore_kernel(
-    const bf16x8* __restrict__ qfrag, const uint16_t* __restrict__ k,
-    const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len,
-    const float* __restrict__ cstat, PrefillDims p, float scale_log2e, int nb0,
+// Sweep 2: head-mean probabilities.  The work is cut into units (128 vision keys of a sample, one head);
+// a persistent grid of P blocks (one or two per CU) takes equal, contiguous runs of units
+// [p*U/P, (p+1)*U/P), ordered (sample, key group, head), whatever the shape: no block count has to
+// match the chip.  A block of 4 waves holds a [128 keys x 32*NBW text rows] tile of a[i][j] in
+// registers (wave w: text block w % NBW, the KT key tiles of tile lane w / NBW) and adds one head's
+// probabilities per unit.  Per unit the 128 K rows go global -> registers -> LDS (two slots; the rows
+// of unit u+2 are requested while unit u is worked on), the wave's text-query fragments come from
+// qfrag (coalesced).  The row statistics are folded into one constant per (head, text row):
+// p = exp2(s*scale*log2e + c), c = -m - log2(Z*H) (cstat: from sweep 1, or from the caller's
+// log-sum-exp), so a probability costs one FMA and one exp2.  The MFMA chain of a key tile is issued together with the exp2 work of the tile before it.
+// Where a run leaves a key group (or ends) the block writes its head-partial sums a[j][i] as one
+// "piece" (fp32, key-major); prefill_colfix_kernel adds a key group's pieces in a fixed order and
+// reduces over the text rows (Eq. 8 / Eq. 10).  Which block holds which piece is a function of the
+// shapes alone, so the result does not depend on timing.
+struct ColPlan { int P; long U; int nkg; int Gmax; };
+
+__host__ __device__ __forceinline__ int unit_block(long u, int P, long U) { return (int)(((u + 1) * P - 1) / U); }
+
+template <int NBW, int KT, int KS>
+__global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
+    const bf16x8* __restrict__ qfrag, const uint16_t* __restrict__ k, const float* __restrict__ cstat,
+    PrefillDims p, ColPlan cp, float scale_log2e, int tgrp, float* __restrict__ apart)
+{
+    constexpr int TW = 4 / NBW;
+    constexpr int KB = 32 * TW * KT;                  // keys per unit (128)
+    constexpr int CH = 2 * KS;                        // 16-byte chunks per row
+    constexpr int PITCH = CH * 16 + 16;               // padded row pitch: conflict-free 128-bit accesses
+    constexpr int SLOT_BYTES = KB * PITCH;
+    constexpr int RPL = kWave / CH;                   // rows per load instruction
+    constexpr int NLW = KB / RPL / 4;                 // load instructions per wave and unit
+    __shared__ __attribute__((aligned(16))) char s_k[2 * SLOT_BYTES];
+    const int lane = lane_id(), wv = wave_id();
+    const int nbw = wv % NBW, tw = wv / NBW;
+    // Blocks go round-robin over the 8 XCDs (each with its own L2): the blocks of one XCD take neighbouring
+    // runs, so a sample's query fragments are fetched into one or two L2s, not all eight.
+    const int P = cp.P;
+    const int pb = (P % 8 == 0) ? (int)(blockIdx.x % 8) * (P / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    const long u0 = (long)pb * cp.U / P, u1 = (long)(pb + 1) * cp.U / P;
+    if (u0 >= u1) return;
+    const int nbt = p.Npad / 32;
+    const int nbg = tgrp * NBW + nbw;                 // 32-row text block of this wave (may lie beyond the prompt)
+    const bool has_rows = nbg < nbt;
+    const int nbc = has_rows ? nbg : 0;
+    const int i = 32 * nbc + (lane & 31);
+    const long tok_stride = p.kv.token;
+
+    // unit u = (tile, head); tile = (sample, key group).  The block walks its run with three cursors (the
+    // unit being worked on, the one whose fragments are requested, the one whose K rows are requested),
+    // each advanced without divisions.
+    struct Unit { int b, kg, h; };
+    auto unit_at = [&](long u) -> Unit {
+        Unit x;
+        const int tile = (int)(u / p.H);
+        x.h = (int)(u - (long)tile * p.H);
+        x.b = tile / cp.nkg;
+        x.kg = tile - x.b * cp.nkg;
+        return x;
+    };
+    auto advance = [&](Unit& x) {
+        if (++x.h == p.H) {
+            x.h = 0;
+            if (++x.kg == cp.nkg) { x.kg = 0; ++x.b; }
+        }
+    };
+    // This wave's share of a unit's K rows: NLW x 1 KiB; rows beyond the last vision key repeat it.
+    // (`live` false, past the end of the run: every lane reads the same 16 bytes -- the loads stay
+    // unconditional, so the compiler can count the loads in flight exactly.)
+    auto load_k = [&](const Unit& x, bool live, u32x4 (&st)[NLW]) {
+        const uint16_t* kb = k + (long)x.b * p.kv.batch + (long)x.h * p.kv.head + (live ? (lane % CH) * 8 : 0);
+#pragma unroll
+        for (int t = 0; t < NLW; ++t) {
+            const int row = live ? min(x.kg * KB + (t * 4 + wv) * RPL + lane / CH, p.Mv - 1) : 0;
+            st[t] = *reinterpret_cast<const u32x4*>(kb + (long)row * tok_stride);
+        }
+    };
+    auto store_k = [&](int slot, const u32x4 (&st)[NLW]) {
+        char* base = s_k + slot * SLOT_BYTES + (lane / CH) * PITCH + (lane % CH) * 16;
+#pragma unroll
+        for (int t = 0; t < NLW; ++t) *reinterpret_cast<u32x4*>(base + (t * 4 + wv) * RPL * PITCH) = st[t];
+    };
+    auto load_q = [&](const Unit& x, bool live, bf16x8 (&qf)[KS]) {
+        const bf16x8* qh = qfrag + (((long)x.b * p.H + x.h) * nbt + nbc) * KS * kWave + (live ? lane : 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = qh[live ? ks * kWave : 0];
+    };
+    // folded row statistic of this lane's text row for the unit's head (-inf beyond txt_len)
+    auto load_c = [&](const Unit& x) -> float {
+        const float c = cstat[((long)x.b * p.H + x.h) * p.Npad + i];
+        return has_rows ? c : -INFINITY;
+    };
+    auto frags = [&](int slot, int kt, bf16x8 (&f)[KS]) {
+        const char* q = s_k + slot * SLOT_BYTES + ((tw * KT + kt) * 32 + (lane & 31)) * PITCH + (lane >> 5) * 16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) f[ks] = *reinterpret_cast<const bf16x8*>(q + ks * 32);
+    };
+    auto add_probs = [&](f32x16& a, const f32x16& acc, float c) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a[r] += fast_exp2(fmaf(acc[r], scale_log2e, c));
+    };
+
+    f32x16 a_acc[KT];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) a_acc[kt][r] = 0.f;
+    };
+    // the piece of key group (x.b, x.kg) this block holds: apart[piece][b][j][i], text rows contiguous
+    auto flush = [&](const Unit& x) {
+        const long tile = (long)x.b * cp.nkg + x.kg;
+        const int piece = pb - unit_block(tile * p.H, P, cp.U);
+        if (has_rows) {
+            float* ap = apart + (((long)piece * p.B + x.b) * p.Mv) * p.Npad + i;
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int j = x.kg * KB + (tw * KT + kt) * 32 + tile_row(r, lane);
+                    if (j < p.Mv) ap[(long)j * p.Npad] = a_acc[kt][r];
+                }
+        }
+    };
+
+    // prologue: unit u0 into slot 0, unit u0+1 in registers, fragments and statistic of unit u0
+    u32x4 st[NLW];
+    bf16x8 qf[KS];
+    Unit xc = unit_at(u0), xq = xc, xk = xc;         // cursors: current unit, fragments, K rows
+    load_k(xk, true, st);
+    load_q(xq, true, qf);
+    float c_cur = load_c(xq), c_nxt = 0.f;
+    store_k(0, st);
+    if (u0 + 1 < u1) advance(xk);
+    load_k(xk, u0 + 1 < u1, st);
+    clear_acc();
+
+    // One unit.  On entry: its K rows are in `slot` (written before the barrier below), the next unit's
+    // rows are in `st`, its fragments in qf.  The fragments of the next unit replace them as soon as the
+    // last MFMA chain of this unit is under way.
+    auto unit_step = [&](long u, int slot) {
+        __syncthreads();                              // slot is complete; the other slot is no longer read
+        store_k(slot ^ 1, st);                        // unit u+1
+        if (u + 2 < u1) advance(xk);
+        load_k(xk, u + 2 < u1, st);                   // unit u+2
+        if (u + 1 < u1) advance(xq);
+        c_nxt = load_c(xq);
+        bf16x8 kfA[KS], kfB[KS];
+        f32x16 accA, accB;
+        frags(slot, 0, kfA);
+        if constexpr (KT > 1) frags(slot, 1, kfB);
+        accA = score_tile<KS>(kfA, qf);
+#pragma unroll
+        for (int kt = 1; kt < KT; ++kt) {
+            // the MFMA chain of tile kt together with the exp2 work of tile kt-1
+            if (kt & 1) {
+                accB = score_tile<KS>(kfB, qf);
+                if (kt + 1 < KT) frags(slot, kt + 1, kfA);
+                add_probs(a_acc[kt - 1], accA, c_cur);
+            } else {
+                accA = score_tile<KS>(kfA, qf);
+                if (kt + 1 < KT) frags(slot, kt + 1, kfB);
+                add_probs(a_acc[kt - 1], accB, c_cur);
+            }
+        }
+        load_q(xq, u + 1 < u1, qf);                   // unit u+1
+        add_probs(a_acc[KT - 1], ((KT - 1) & 1) ? accB : accA, c_cur);
+        c_cur = c_nxt;
+        if (xc.h == p.H - 1 || u + 1 == u1) {         // the run leaves this key group
+            flush(xc);
+            clear_acc();
+        }
+        advance(xc);
+    };
+    long u = u0;
+    for (; u + 1 < u1; u += 2) {
+        unit_step(u, 0);
+        unit_step(u + 1, 1);
+    }
+    if (u < u1) unit_step(u, 0);
+}
+
+// Column statistics (Eq. 8 / Eq. 10): a[i][j] = sum over the pieces of j's key group (fixed order);
+// V_j = sum_i a[i][j], I_j = max_i a[i][j].  A wave takes four neighbouring vision keys at a time (same
+// key group, same pieces), lanes over text rows; all loads of a piece are in flight together.
+constexpr int kFixKeys = 4;
+__global__ __launch_bounds__(256) void prefill_colfix_kernel(
+    const float* __restrict__ apart, const uint8_t* __restrict__ vis_valid, PrefillDims p, ColPlan cp,
     float* __restrict__ Vout, float* __restrict__ Iout)
 {
-    using Tile = OperandTile<KS>;
-    constexpr int PARTS = 2 * NW;
-    constexpr int HALF = NB > 2 ? 2 : NB;            // text blocks dumped per reduction round (8 KiB per wave)
-    static_assert(32 * 32 * HALF * 4 <= Tile::BYTES || KS < 8, "reduction buffer must fit the K tile");
-    constexpr int WBUF = (Tile::BYTES > 32 * 32 * HALF * 4) ? Tile::BYTES : 32 * 32 * HALF * 4;
-    __shared__ __attribute__((aligned(16))) char s_buf[NW][WBUF];   // K tile of each wave; later its a_acc dump
-    __shared__ float s_ps[PARTS][32], s_pm[PARTS][32];
-
-    const int lane = lane_id(), wv = wave_id(), tid = threadIdx.x;
-    // Workgroups go round-robin over the 8 XCDs (each with its own L2).  All key tiles of a sample
-    // share that sample's query fragments, so a sample is pinned to one XCD when the batch allows:
-    // its fragments are then fetched into one L2 instead of eight.
-    const int nt = (p.Mv + 31) / 32;
-    int b, tile_idx;
-    if (p.B % 8 == 0) {
-        const int xcd = blockIdx.x % 8, r = blockIdx.x / 8;
-        b = xcd + 8 * (r / nt);
-        tile_idx = r % nt;
-    } else if (8 % p.B == 0) {                       // small batch: a sample owns 8/B XCDs
-        const int g = 8 / p.B, xcd = blockIdx.x % 8, r = blockIdx.x / 8;
-        b = xcd / g;
-        tile_idx = r * g + xcd % g;
-        if (tile_idx >= nt) return;                  // grid padded to a multiple of 8 (whole block leaves)
-    } else {
-        b = blockIdx.x / nt;
-        tile_idx = blockIdx.x % nt;
-    }
-    const int j0 = tile_idx * 32;
-    const long tok_stride = p.kv.token;
-    const uint8_t* vb = vis_valid ? vis_valid + (long)b * p.Mv : nullptr;
-    const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
-    char* tile = s_buf[wv];
-
-    u32x4 st[KS];
-    const uint16_t* kb = k + (long)b * p.kv.batch;
-    if (wv < p.H) Tile::gload(kb + (long)wv * p.kv.head, tok_stride, j0, p.Mv, lane, st);
-
-    f32x16 a_acc[NB];
+    const int lane = lane_id(), wv = wave_id(), b = blockIdx.y;
+    const long gstride = (long)p.B * p.Mv * p.Npad;
+    const int j0 = (blockIdx.x * 4 + wv) * kFixKeys;
+    if (j0 >= p.Mv) return;
+    const long tile = (long)b * cp.nkg + j0 / kColKeys;
+    const int npieces = unit_block(tile * p.H + p.H - 1, cp.P, cp.U) - unit_block(tile * p.H, cp.P, cp.U) + 1;
+    float s[kFixKeys], mx[kFixKeys];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int q = 0; q < kFixKeys; ++q) { s[q] = 0.f; mx[q] = 0.f; }
+    for (int i0 = 0; i0 < p.Npad; i0 += 2 * kWave) {
+        // two text rows per lane and round (lanes beyond Npad read a valid row and drop it)
+        const int ia = i0 + lane, ib = i0 + kWave + lane;
+        const bool oka = ia < p.Npad, okb = ib < p.Npad;
+        const int ca = oka ? ia : 0, cb = okb ? ib : 0;
+        float a0[kFixKeys], a1[kFixKeys];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) a_acc[nb][r] = 0.f;
-
-    constexpr int TP = (NB + 1) / 2;                 // text blocks are processed in pairs (64 registers of fragments)
-    for (int h = wv; h < p.H; h += NW) {
-        const bf16x8* qh = qfrag + (((long)b * p.H + h) * (p.Npad / 32) + nb0) * KS * kWave + lane;
-        const float* ch = cstat + ((long)b * p.H + h) * p.Npad + 32 * nb0 + (lane & 31);
-        bf16x8 qf[2][KS];
-        float c[2];
-        auto load_pair = [&](int tp) {
+        for (int q = 0; q < kFixKeys; ++q) { a0[q] = 0.f; a1[q] = 0.f; }
+        for (int g = 0; g < npieces; ++g) {
+            float x0[kFixKeys], x1[kFixKeys];
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int nb = 2 * tp + e;
-                if (nb < NB) {
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) qf[e][ks] = qh[(nb * KS + ks) * kWave];
-                    c[e] = ch[32 * nb];
-                }
+            for (int q = 0; q < kFixKeys; ++q) {
+                const float* ap = apart + g * gstride + ((long)b * p.Mv + min(j0 + q, p.Mv - 1)) * p.Npad;
+                x0[q] = ap[ca];
+                x1[q] = ap[cb];
             }
-        };
-        // the first pair's query fragments and folded row statistics are requested before the K tile
-        // goes through LDS, so they are in flight meanwhile
-        load_pair(0);
-        bf16x8 kf[KS];
-        Tile::to_lds(tile, lane, st);
-        wave_lds_sync();
-        Tile::frags(tile, lane, kf);
-        wave_lds_sync();
-        if (h + NW < p.H)                                                      // prefetch the next head's K tile
-            Tile::gload(kb + (long)(h + NW) * p.kv.head, tok_stride, j0, p.Mv, lane, st);
 #pragma unroll
-        for (int tp = 0; tp < TP; ++tp) {
-            if (tp > 0) load_pair(tp);
+            for (int q = 0; q < kFixKeys; ++q) { a0[q] += x0[q]; a1[q] += x1[q]; }
+        }
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int nb = 2 * tp + e;
-                if (nb < NB) {
-                    f32x16 acc;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[e][ks], acc, 0, 0, 0);
-                    // text rows beyond txt_len have zero query fragments and c = -inf: exp2(-inf) = 0 exactly
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        a_acc[nb < NB ? nb : 0][r] += fast_exp2(fmaf(acc[r], scale_log2e, c[e]));
-                }
-            }
+        for (int q = 0; q < kFixKeys; ++q) {
+            const float v0 = oka ? a0[q] : 0.f, v1 = okb ? a1[q] : 0.f;
+            s[q] += v0 + v1;
+            mx[q] = fmaxf(mx[q], fmaxf(v0, v1));
         }
     }
-
-    // Column statistics (Eq. 8 / Eq. 10).  Every wave dumps its accumulators into its own buffer;
-    // the waves' head groups are then summed in wave order while the text rows are reduced
-    // (fixed order -> reproducible bits).
-    float col_s = 0.f, col_m = 0.f;                  // this thread's (key, text-row slice) partial results
-    const int rr = tid & 31, part = tid >> 5;
 #pragma unroll
-    for (int half = 0; half < NB; half += HALF) {
-        __syncthreads();
-        float* mine = reinterpret_cast<float*>(tile);
-#pragma unroll
-        for (int nb = 0; nb < HALF; ++nb) {
-            if (half + nb < NB) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    mine[((nb * 32) + (lane & 31)) * 32 + ((tile_row(r, lane) + (lane & 31)) & 31)] =
-                        a_acc[(half + nb) < NB ? (half + nb) : 0][r];
-            }
-        }
-        __syncthreads();
-        constexpr int per = (32 * HALF + PARTS - 1) / PARTS;
-        for (int ii = part * per; ii < min((part + 1) * per, 32 * HALF); ++ii) {
-            if ((nb0 + half) * 32 + ii >= tl) break;
-            float a = 0.f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w)
-                a += reinterpret_cast<const float*>(s_buf[w])[ii * 32 + ((rr + (ii & 31)) & 31)];
-            col_s += a;
-            col_m = fmaxf(col_m, a);
-        }
-    }
-    s_ps[part][rr] = col_s;
-    s_pm[part][rr] = col_m;
-    __syncthreads();
-    if (tid < 32) {
-        const int j = j0 + tid;
-        if (j < p.Mv) {
-            float s = 0.f, mx = 0.f;
-#pragma unroll
-            for (int q = 0; q < PARTS; ++q) { s += s_ps[q][tid]; mx = fmaxf(mx, s_pm[q][tid]); }
-            const bool ok = !vb || vb[j];
-            Vout[(long)b * p.Mv + j] = ok ? s : 0.f;
-            Iout[(long)b * p.Mv + j] = ok ? mx : 0.f;
+    for (int q = 0; q < kFixKeys; ++q) {
+        const float ss = wave_sum(s[q]), mm = wave_max(mx[q]);
+        const int j = j0 + q;
+        if (lane == 0 && j < p.Mv) {
+            const bool ok = !vis_valid || vis_valid[(long)b * p.Mv + j];
+            Vout[(long)b * p.Mv + j] = ok ? ss : 0.f;
+            Iout[(long)b * p.Mv + j] = ok ? mm : 0.f;
         }
     }
 }
@@ -771,50 +970,60 @@ __global__ __launch_bounds__(256) void prefill_compact_strided_kernel(
     for (int c = threadIdx.x; c < hv; c += blockDim.x) hd[c] = hs[c];
 }
 
-// Prompts of more than 128 text rows: V = sum, I = max over the launches' partial results (group 0 holds the result).
-__global__ __launch_bounds__(256) void prefill_merge_groups_kernel(long n, int groups, float* __restrict__ V, float* __restrict__ I)
-{
-    const long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n) return;
-    float v = V[e], m = I[e];
-    for (int g = 1; g < groups; ++g) { v += V[g * n + e]; m = fmaxf(m, I[g * n + e]); }
-    V[e] = v;
-    I[e] = m;
-}
-
 struct PrefillWorkspace {
-    float2* partial; float* cstat; bf16x8* qfrag; float* V; float* I; float* score; int32_t* src_row;
+    float2* partial; float* cstat; bf16x8* qfrag; float* apart; float* V; float* I; float* score; int32_t* src_row;
     size_t bytes;
 };
 
 #ifndef MD_RS_BLOCKS
-#define MD_RS_BLOCKS 512   // target number of blocks of the row-statistics sweep
-#endif
-#ifndef MD_PF_NW
-#define MD_PF_NW 4      // waves per block in the column-score sweep (measured: 4 beats 8 and 16)
+#define MD_RS_BLOCKS 512   // target number of blocks of the row-statistics sweep (two per CU)
 #endif
 
-int pick_chunks(int B, int H, int L, int ntg) {
-    // enough (sample, head, chunk) blocks to cover the 256 CUs several times; chunks of whole tiles
-    // about two resident blocks per CU (512 in all); at least 4 tiles per chunk so every wave has work
-    const int tiles = (L + 31) / 32;
-    int nch = (MD_RS_BLOCKS + B * H * ntg - 1) / (B * H * ntg);   // ntg: text groups, also spread over blocks
-    if (nch > tiles / 4) nch = tiles / 4;
+
+// Launch shapes of the two sweeps; pure host arithmetic shared by the workspace size and the launch.
+struct ScorePlan { int nbt, nbw, ng, nch, chunk; ColPlan col; int occ; };
+constexpr int kNumCU = 256;                          // MI355X
+
+ScorePlan plan_scores(int B, int Mv, int N, int H) {
+    ScorePlan s;
+    s.nbt = (N + 31) / 32;                            // 32-row text blocks
+    s.nbw = s.nbt == 1 ? 1 : (s.nbt == 2 ? 2 : 4);    // text blocks per block (one per wave or wave pair)
+    s.ng = (s.nbt + s.nbw - 1) / s.nbw;               // text groups: K is read once per group
+    // sweep 1: chunks of whole 128-key units, enough blocks to fill the chip a few times, at least
+    // four units per chunk
+    const int units = (Mv + N + 127) / 128;
+    int nch = (MD_RS_BLOCKS + B * H * s.ng - 1) / (B * H * s.ng);
+    if (nch > units / 4) nch = units / 4;
     if (nch < 1) nch = 1;
-    if (nch > 64) nch = 64;
-    return nch;
+    if (nch > kMaxChunks) nch = kMaxChunks;
+    const int upc = (units + nch - 1) / nch;
+    s.chunk = upc * 128;
+    s.nch = (units + upc - 1) / upc;
+    // sweep 2: a persistent grid; units of (128 keys, one head), at least four per block
+    s.occ = 2;                                        // blocks per CU the kernel's register budget allows
+    ColPlan& c = s.col;
+    c.nkg = (Mv + kColKeys - 1) / kColKeys;
+    c.U = (long)B * c.nkg * H;
+    long P = (c.U + 3) / 4;
+    if (P > kNumCU * s.occ) P = kNumCU * s.occ;
+    if (P < 1) P = 1;
+    c.P = (int)P;
+    c.Gmax = (int)(((long)H * c.P + c.U - 1) / c.U) + 1;   // pieces a key group can be cut into
+    if (c.Gmax > H) c.Gmax = H;
+    return s;
 }
 
 PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap) {
     Carver c(base);
     PrefillWorkspace w;
-    const int Npad = (N + 31) / 32 * 32;
-    w.partial = c.take<float2>((size_t)B * H * 64 * Npad);
+    const ScorePlan s = plan_scores(B, Mv, N, H);
+    const int Npad = s.nbt * 32;
+    w.partial = c.take<float2>((size_t)B * H * s.nch * Npad);
     w.cstat = c.take<float>((size_t)B * H * Npad);
     w.qfrag = c.take<bf16x8>((size_t)B * H * Npad * 16);      // [B][H][NB][KS][64] fragments, d <= 128
-    const int groups = (Npad / 32 + 3) / 4;                    // column-score launches (128 text rows each)
-    w.V = c.take<float>((size_t)groups * B * Mv);
-    w.I = c.take<float>((size_t)groups * B * Mv);
+    w.apart = c.take<float>((size_t)s.col.Gmax * B * Mv * Npad);
+    w.V = c.take<float>((size_t)B * Mv);
+    w.I = c.take<float>((size_t)B * Mv);
     w.score = c.take<float>((size_t)B * Mv);
     w.src_row = c.take<int32_t>((size_t)B * (Rcap + N));
     w.bytes = c.off;
@@ -822,47 +1031,39 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
 }
 
 template <int KS>
-int launch_scores(const PrefillDims& p, const PrefillWorkspace& w, hipStream_t st, const void* q_txt, const void* k,
-                  const uint8_t* vis_valid, const int32_t* txt_len, float scale_log2e) {
-    constexpr int NW = MD_PF_NW;
-    const int nbt = p.Npad / 32;                     // 32-row text blocks in all
-    // sweep 1: a block covers two text blocks (one if there is only one)
-    const int ntg = nbt == 1 ? 1 : (nbt + 1) / 2;
-    dim3 g1(p.nch * ntg, p.H, p.B);
-    if (nbt == 1)
-        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<1, KS>), g1, 256, 0,
-            static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
-            w.partial, w.cstat, w.qfrag);
-    else
-        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<2, KS>), g1, 256, 0,
-            static_cast<const uint16_t*>(q_txt), static_cast<const uint16_t*>(k), vis_valid, txt_len, p, scale_log2e,
-            w.partial, w.cstat, w.qfrag);
-    if (p.nch > 1) {
-        const long n = (long)p.B * p.H * p.Npad;
-        MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel), (unsigned)((n + 255) / 256), 256, 0,
-            w.partial, txt_len, p, w.cstat);
+int launch_scores(const PrefillDims& p, const ScorePlan& s, const PrefillWorkspace& w, hipStream_t st, const void* q_txt,
+                  const void* k, const uint8_t* vis_valid, const int32_t* txt_len, const float* row_lse, float scale_log2e) {
+    const uint16_t* qp = static_cast<const uint16_t*>(q_txt);
+    const uint16_t* kp = static_cast<const uint16_t*>(k);
+    if (!row_lse) {
+        dim3 g1(p.nch * s.ng, p.H, p.B);
+#define MD_ROWSTATS(NBW_)                                                                                      \
+        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW_, KS>), g1, 256, 0,                    \
+            qp, kp, vis_valid, txt_len, p, scale_log2e, w.partial, w.cstat, w.qfrag)
+        if (s.nbw == 1) MD_ROWSTATS(1);
+        else if (s.nbw == 2) MD_ROWSTATS(2);
+        else MD_ROWSTATS(4);
+#undef MD_ROWSTATS
+        if (p.nch > 1) {
+            const long n = (long)p.B * p.H * p.Npad;
+            MD_LAUNCH("prefill_cstat", st, (prefill_cstat_kernel), (unsigned)((n + 255) / 256), 256, 0, w.partial, txt_len, p, w.cstat);
+        }
+    } else {
+        const long items = (long)p.B * p.H * s.nbt;
+        MD_LAUNCH("prefill_qpack", st, (prefill_qpack_kernel<KS>), (unsigned)((items + 3) / 4), 256, 0, qp, txt_len, row_lse, p,
+                  w.qfrag, w.cstat);
     }
-    // sweep 2: one launch per 128 text rows
-    const int nt = (p.Mv + 31) / 32;
-    dim3 g2(p.B % 8 == 0 || 8 % p.B != 0 ? nt * p.B : 8 * ((nt + 8 / p.B - 1) / (8 / p.B)));
-    const long nv = (long)p.B * p.Mv;
-    const int groups = (nbt + 3) / 4;
-    for (int g = 0; g < groups; ++g) {
-        const int nb0 = 4 * g, nbg = nbt - nb0 < 4 ? nbt - nb0 : 4;
-        float* Vg = w.V + g * nv;
-        float* Ig = w.I + g * nv;
-#define MD_COLSCORE(NB_)                                                                                       \
-        MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NB_, KS, NW>), g2, 64 * NW, 0,                  \
-            w.qfrag, static_cast<const uint16_t*>(k), vis_valid, txt_len, w.cstat, p, scale_log2e, nb0, Vg, Ig)
-        if (nbg == 1) MD_COLSCORE(1);
-        else if (nbg == 2) MD_COLSCORE(2);
-        else if (nbg == 3) MD_COLSCORE(3);
-        else MD_COLSCORE(4);
+    for (int tg = 0; tg < s.ng; ++tg) {
+#define MD_COLSCORE(NBW_, KT_)                                                                                 \
+        MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NBW_, KT_, KS>), s.col.P, 256, 0,           \
+            w.qfrag, kp, w.cstat, p, s.col, scale_log2e, tg, w.apart)
+        if (s.nbw == 1) MD_COLSCORE(1, 1);
+        else if (s.nbw == 2) MD_COLSCORE(2, 2);
+        else MD_COLSCORE(4, 4);
 #undef MD_COLSCORE
     }
-    if (groups > 1)
-        MD_LAUNCH("prefill_merge_groups", st, (prefill_merge_groups_kernel), (unsigned)((nv + 255) / 256), 256, 0,
-            nv, groups, w.V, w.I);
+    const int fx = (p.Mv + 4 * kFixKeys - 1) / (4 * kFixKeys);          // four waves of kFixKeys keys per block
+    MD_LAUNCH("prefill_colfix", st, (prefill_colfix_kernel), dim3(fx, p.B), 256, 0, w.apart, vis_valid, p, s.col, w.V, w.I);
     return MD_OK;
 }
 
@@ -881,7 +1082,7 @@ namespace {
 
 int prefill_filter_impl(
     const void* q_txt, const void* k, const void* v, const void* hidden,
-    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key, const float* row_lse,
     int B, int Mv, int N, int H, int d, int C,
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,
@@ -921,6 +1122,9 @@ int prefill_filter_impl(
     if (lrc != MD_OK) return lrc;
     if (lq.token > (1l << 26) || lkv.token > (1l << 26))
         return fail(MD_ESHAPE, "prefill_filter: token stride above 2^26 elements");
+    // the score sweeps address a sample's head slice with 32-bit byte offsets
+    if (((long)L * lkv.token + d) * 2 >= (1l << 31) || ((long)N * lq.token + d) * 2 >= (1l << 31))
+        return fail(MD_ESHAPE, "prefill_filter: one head slice of a sample spans more than 2 GiB");
     const size_t kv_in = layout_extent_bytes(lkv, B, (long)L, H, d), h_in = (size_t)B * L * C * 2;
     const size_t kv_out = layout_extent_bytes(lout, B, (long)Rcap + N, H, d), h_out = (size_t)B * (Rcap + N) * C * 2;
     const void* ins[] = {k, v, hidden, q_txt};
@@ -938,16 +1142,14 @@ int prefill_filter_impl(
     PrefillDims p;
     p.B = B; p.Mv = Mv; p.N = N; p.H = H; p.d = d; p.C = C; p.L = Mv + N; p.Rcap = Rcap;
     p.q = lq; p.kv = lkv;
-    p.Npad = (N + 31) / 32 * 32;
-    p.nch = pick_chunks(B, H, p.L, (p.Npad / 32 + 1) / 2);
-    const int tiles = (p.L + 31) / 32;
-    p.chunk = (tiles + p.nch - 1) / p.nch * 32;
-    p.nch = (p.L + p.chunk - 1) / p.chunk;
+    const ScorePlan sp = plan_scores(B, Mv, N, H);
+    p.Npad = sp.nbt * 32;
+    p.nch = sp.nch; p.chunk = sp.chunk;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float sl2 = softmax_scale * kLog2e;
 
-    int rc = d == 128 ? launch_scores<8>(p, w, st, q_txt, k, vis_valid, txt_len, sl2)
-                      : launch_scores<4>(p, w, st, q_txt, k, vis_valid, txt_len, sl2);
+    int rc = d == 128 ? launch_scores<8>(p, sp, w, st, q_txt, k, vis_valid, txt_len, row_lse, sl2)
+                      : launch_scores<4>(p, sp, w, st, q_txt, k, vis_valid, txt_len, row_lse, sl2);
     if (rc != MD_OK) return rc;
     int32_t* src_row = out_ids ? out_ids : w.src_row;     // the row map doubles as the optional out_ids
     const bool dense_io = is_dense(lkv, (long)L, H, d) && is_dense(lout, (long)Rcap + N, H, d);
@@ -985,7 +1187,7 @@ int prefill_filter_impl(
 
 extern "C" int mustdrop_prefill_filter(
     const void* q_txt, const void* k, const void* v, const void* hidden,
-    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key, const float* row_lse,
     int B, int Mv, int N, int H, int d, int C,
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,
@@ -994,7 +1196,7 @@ extern "C" int mustdrop_prefill_filter(
     float* score_global, float* score_indiv,
     void* workspace, size_t workspace_bytes, void* stream)
 {
-    return prefill_filter_impl(q_txt, k, v, hidden, vis_valid, txt_len, is_key, B, Mv, N, H, d, C, softmax_scale, mode,
+    return prefill_filter_impl(q_txt, k, v, hidden, vis_valid, txt_len, is_key, row_lse, B, Mv, N, H, d, C, softmax_scale, mode,
                                budget, gamma, alpha, Rcap, hidden_out, k_out, v_out, kept_index, kept_count, out_len,
                                out_protect, out_ids, score_global, score_indiv, nullptr, nullptr, nullptr,
                                workspace, workspace_bytes, stream);
@@ -1002,7 +1204,7 @@ extern "C" int mustdrop_prefill_filter(
 
 extern "C" int mustdrop_prefill_filter_strided(
     const void* q_txt, const void* k, const void* v, const void* hidden,
-    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key,
+    const uint8_t* vis_valid, const int32_t* txt_len, const uint8_t* is_key, const float* row_lse,
     int B, int Mv, int N, int H, int d, int C,
     float softmax_scale, md_filter_mode mode, int budget, float gamma, float alpha,
     int Rcap,
@@ -1012,7 +1214,7 @@ extern "C" int mustdrop_prefill_filter_strided(
     const md_kv_layout* q_layout, const md_kv_layout* kv_layout, const md_kv_layout* kv_out_layout,
     void* workspace, size_t workspace_bytes, void* stream)
 {
-    return prefill_filter_impl(q_txt, k, v, hidden, vis_valid, txt_len, is_key, B, Mv, N, H, d, C, softmax_scale, mode,
+    return prefill_filter_impl(q_txt, k, v, hidden, vis_valid, txt_len, is_key, row_lse, B, Mv, N, H, d, C, softmax_scale, mode,
                                budget, gamma, alpha, Rcap, hidden_out, k_out, v_out, kept_index, kept_count, out_len,
                                out_protect, out_ids, score_global, score_indiv, q_layout, kv_layout, kv_out_layout,
                                workspace, workspace_bytes, stream);

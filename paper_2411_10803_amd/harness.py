@@ -53,10 +53,11 @@ def encode_adaptive_on_gpu(x, x_dtype, q_cls, k_cls, qk_dtype, mass_in, valid, T
     return g
 
 
-def prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, mode, budget, gamma, alpha, Rcap=None):
+def prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, mode, budget, gamma, alpha, Rcap=None, row_lse=None):
     out = md.mustdrop_prefill_filter(
         to_dev(t["q_txt"], True), to_dev(t["k"], True), to_dev(t["v"], True), to_dev(t["hidden"], True),
-        to_dev(vis_valid), to_dev(txt_len), to_dev(is_key), Mv, scale, mode, budget, gamma, alpha, Rcap)
+        to_dev(vis_valid), to_dev(txt_len), to_dev(is_key), Mv, scale, mode, budget, gamma, alpha, Rcap,
+        row_lse=to_dev(row_lse))
     return outputs_to_host(out)
 
 

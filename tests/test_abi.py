@@ -85,7 +85,7 @@ def prefill(lib, **kw):
              scale=0.088, mode=0, budget=192, gamma=1 / 576, alpha=2 / 640, Rcap=192,
              ho=P(0x20000000), ko=P(0x28000000), vo=P(0x30000000), ki=X, kc=X, ws=P(0x40000000), wsb=1 << 30)
     a.update(kw)
-    return lib.mustdrop_prefill_filter(a["q"], a["k"], a["v"], a["h"], None, None, None, a["B"], a["Mv"], a["N"], a["H"],
+    return lib.mustdrop_prefill_filter(a["q"], a["k"], a["v"], a["h"], None, None, None, a.get("lse"), a["B"], a["Mv"], a["N"], a["H"],
                                        a["d"], a["C"], F(a["scale"]), a["mode"], a["budget"], F(a["gamma"]), F(a["alpha"]),
                                        a["Rcap"], a["ho"], a["ko"], a["vo"], a["ki"], a["kc"], None, None, None, None, None,
                                        a["ws"], C.c_size_t(a["wsb"]), None)
@@ -187,7 +187,7 @@ def test_layout_argument_errors(lib):
         a.update(kw)
         ref = lambda l: C.byref(l) if l is not None else None
         return lib.mustdrop_prefill_filter_strided(
-            P(0x1000000), a["k"], P(0x8000000), P(0x10000000), None, None, None, 1, 576, 64, 32, 128, 4096,
+            P(0x1000000), a["k"], P(0x8000000), P(0x10000000), None, None, None, None, 1, 576, 64, 32, 128, 4096,
             F(0.088), 0, 192, F(1 / 576), F(2 / 640), 192, P(0x20000000), a["ko"], P(0x30000000), X, X, None, None, None,
             None, None, ref(q), ref(kv), ref(out), P(0x40000000), C.c_size_t(a["wsb"]), None)
 

@@ -125,3 +125,51 @@ def test_determinism():
     for r in runs[1:]:
         for name in ("kept_index", "score_global", "score_indiv", "k_out", "hidden_out"):
             assert np.array_equal(runs[0][name], r[name]), name
+
+
+@pytest.mark.parametrize("which", ["cfg2_slice", "cfg3_one", "ragged_d64", "long_prompt"])
+def test_row_lse_input_skips_the_first_sweep_and_gives_the_same_answer(which):
+    """Sec. 3.4: the text-to-vision scores are a by-product of the layer's attention.  With the attention's row
+    normalisers handed over (here: the oracle's, rounded to fp32) the library reads K once; V, I and the selection
+    must still match the plain oracle result, and the results with and without the normalisers must agree."""
+    from paper_2411_10803_amd import harness
+    rng = np.random.default_rng(17)
+    vis_valid = txt_len = None
+    if which == "cfg2_slice":
+        cfg, samples, R = wl.CONFIGS[2], [0, 3, 9, 15], 128
+    elif which == "cfg3_one":
+        cfg, samples, R = wl.CONFIGS[3], [2], 320
+    elif which == "ragged_d64":
+        cfg, samples, R = wl.tiny(wl.CONFIGS[2], B=3, Hg=7, Wg=11, N=45, H=6, d=64, C=264), None, 20
+        vis_valid = (rng.random((cfg.B, cfg.M)) > 0.3).astype(np.uint8)
+        txt_len = np.array([45, 17, 1], dtype=np.int32)
+    else:
+        cfg, samples, R = wl.tiny(wl.CONFIGS[2], B=2, Hg=9, Wg=13, N=200, H=4, d=128, C=256), None, 40
+        txt_len = np.array([200, 131], dtype=np.int32)
+    t = wl.prefill_inputs(cfg, samples)
+    B = t["k"].shape[0]
+    is_key = wl.random_key_mask(cfg, 8)[:B]
+    if vis_valid is not None:
+        is_key &= vis_valid
+    Mv, N = cfg.M, cfg.N
+    scale, gamma, alpha = 1.0 / np.sqrt(cfg.d), 1.0 / Mv, 2.0 / (Mv + N)
+    o = oracle.prefill_filter(t["q_txt"], t["k"], t["v"], t["hidden"], vis_valid, txt_len, is_key, Mv, scale,
+                              FILTER_BUDGET, R, gamma, alpha, R)
+    lse = o["row_lse"].astype(np.float32)
+    if txt_len is not None:                       # entries of rows beyond txt_len are ignored: poison them
+        for b in range(B):
+            lse[b, :, int(txt_len[b]):] = np.nan
+    g0 = harness.prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, FILTER_BUDGET, R, gamma, alpha, R)
+    g1 = harness.prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, FILTER_BUDGET, R, gamma, alpha, R, row_lse=lse)
+    check_prefill(g0, o, t, Mv, vis_valid, is_key, FILTER_BUDGET, R, gamma, alpha, R)
+    s1 = check_prefill(g1, o, t, Mv, vis_valid, is_key, FILTER_BUDGET, R, gamma, alpha, R)
+    assert s1["max_V_rel"] < 1e-4 and s1["max_I_rel"] < 1e-4
+    ok = np.ones((B, Mv), bool) if vis_valid is None else vis_valid.astype(bool)
+    assert np.allclose(g1["score_global"][ok], g0["score_global"][ok], rtol=1e-5, atol=0)
+    assert np.allclose(g1["score_indiv"][ok], g0["score_indiv"][ok], rtol=1e-5, atol=0)
+    assert np.array_equal(g1["kept_count"], g0["kept_count"])
+    # threshold mode through the same path
+    gth = harness.prefill_on_gpu(t, Mv, vis_valid, txt_len, is_key, scale, FILTER_THRESHOLD, 0, gamma, alpha, Mv, row_lse=lse)
+    oth = oracle.prefill_filter(t["q_txt"], t["k"], t["v"], t["hidden"], vis_valid, txt_len, is_key, Mv, scale,
+                                FILTER_THRESHOLD, 0, gamma, alpha, Mv)
+    check_prefill(gth, oth, t, Mv, vis_valid, is_key, FILTER_THRESHOLD, 0, gamma, alpha, Mv)

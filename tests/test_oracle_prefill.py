@@ -257,3 +257,31 @@ def test_chained_calls_keep_the_key_set_and_shrink_to_the_budgets():
         key, vis, Mv = o["out_protect"][:, :R].copy(), None, R
     for b in range(cfg.B):
         assert keys0[b] <= set(orig[b].tolist())
+
+
+def test_row_normalisers_match_numpy_logsumexp():
+    """The row normalisers the oracle reports (what an attention kernel leaves behind, Sec. 3.4) against a
+    numpy log-sum-exp over the visible keys; rows beyond txt_len report 0."""
+    t = make(B=3, Mv=37, N=9, H=4, d=16, seed=11)
+    rng = np.random.default_rng(5)
+    vis_valid = (rng.random((t["B"], t["Mv"])) > 0.25).astype(np.uint8)
+    txt_len = np.array([9, 4, 0], dtype=np.int32)
+    scale = 0.31
+    o = run(t, budget=10, vis_valid=vis_valid, txt_len=txt_len, scale=scale)
+    q, k = wl.to_f64(t["q"], wl.BF16), wl.to_f64(t["k"], wl.BF16)
+    lg = float(np.float32(scale)) * np.einsum("bihc,bjhc->bhij", q, k)
+    Mv, N = t["Mv"], t["N"]
+    mask = np.ones((t["B"], 1, N, Mv + N), dtype=bool)
+    mask[:, :, :, Mv:] = np.tril(np.ones((N, N), dtype=bool))[None, None]
+    mask[:, :, :, :Mv] &= vis_valid.astype(bool)[:, None, None, :]
+    lg = np.where(mask, lg, -np.inf)
+    mx = lg.max(-1)
+    lse = mx + np.log(np.exp(lg - mx[..., None]).sum(-1))            # [B,H,N]
+    for b in range(t["B"]):
+        tl = int(txt_len[b])
+        assert np.allclose(o["row_lse"][b, :, :tl], lse[b, :, :tl], rtol=1e-13, atol=1e-13)
+        assert np.all(o["row_lse"][b, :, tl:] == 0.0)
+    # they are exactly what turns a logit into the probability the scores are made of
+    b, h, i = 0, 2, 5
+    p = np.exp(lg[b, h, i, :Mv] - o["row_lse"][b, h, i])
+    assert np.isclose(p.sum() + np.exp(lg[b, h, i, Mv:] - o["row_lse"][b, h, i]).sum(), 1.0, rtol=1e-12)
