@@ -1,16 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the MustDrop token-reduction hot path on one MI355X.
 
-One "step" = one pass of the whole path over one batch of the LLaVA-1.5-7B prefill workload
-(batch 16, 576 vision tokens of dim 1024 bf16, 64 text tokens, 32 heads x 128, hidden 4096):
+One "step" = one pass of the whole path over one batch of a synthetic workload:
 
-    mustdrop_encode_merge  ->  mustdrop_prefill_filter (budget 192)  ->  mustdrop_decode_evict
+    mustdrop_encode_merge  ->  mustdrop_prefill_filter (budget mode)  ->  mustdrop_decode_evict
 
 chained on the device (out_valid / out_is_key feed the prefill stage; its compacted K/V, out_len,
 out_protect and out_ids are the decode stage's cache state).  Inputs are seeded synthetic tensors
 resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-decode-loop] [--no-cpu-baseline]
+The headline (`value`, `roofline`, `cpu_baseline`) is the largest prefill workload, the high-resolution
+LLaVA-NeXT shape (batch 8 x 2880 vision tokens, 128 text tokens).  The same line carries one block per
+workload (`workloads`): the single image, the batch-16 LLaVA-1.5 shape, the video shape, and the decode
+loop (batch 64, 4096-entry caches, 256 steps), each with per-stage and per-kernel times, the fraction of
+the HBM roofline on the stage's algorithmic bytes, and the MFMA rate of the score contraction.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads 1,2,3,4,5] [--no-extras]
+                    [--no-cpu-baseline] [--no-parity]
 """
 from __future__ import annotations
 
@@ -29,17 +35,25 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-BENCH_TAU = 0.955          # lands the average merge rate near the paper's Table 3 (about 440 of 576 tokens)
-PREFILL_BUDGET = 192
-DECODE_VISION_BUDGET = 128
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+HEADLINE = 3
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-class Cfg2Pipeline:
-    """Device tensors and the chained three-stage step for the batch-16 LLaVA-1.5 workload."""
+def timed(torch, fn, iters):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / iters
+
+
+class Pipeline:
+    """Device tensors and the chained three-stage step of one prefill workload."""
 
     def __init__(self, cfg, torch, md, harness):
         self.cfg, self.torch, self.md = cfg, torch, md
@@ -49,7 +63,7 @@ class Cfg2Pipeline:
         self.pre_np = wl.prefill_inputs(cfg)
         rng = np.random.default_rng([cfg.seed, 11])
         self.q_dec_np = wl.f32_to_bf16_bits(rng.standard_normal((cfg.B, cfg.H, cfg.d)).astype(np.float32))
-        log(f"[bench] generated inputs in {time.time() - t0:.1f}s")
+        log(f"[bench] {cfg.name}: generated inputs in {time.time() - t0:.1f}s")
         bf = cfg.x_dtype == wl.BF16
         self.x = harness.to_dev(self.enc_np["x"], bf)
         self.q_cls = harness.to_dev(self.enc_np["q_cls"], bf)
@@ -60,9 +74,10 @@ class Cfg2Pipeline:
         self.hidden = harness.to_dev(self.pre_np["hidden"], True)
         self.q_dec = harness.to_dev(self.q_dec_np, True)
         B, M, N, H, d = cfg.B, cfg.M, cfg.N, cfg.H, cfg.d
-        self.R = PREFILL_BUDGET
+        self.tau = cfg.bench_tau
+        self.R = cfg.budgets[0]
         self.Lcap = self.R + N
-        self.decode_budget = DECODE_VISION_BUDGET + N
+        self.decode_budget = self.R * 2 // 3 + N          # the decode stage evicts a third of the kept vision entries
         i32, u8, f32 = torch.int32, torch.uint8, torch.float32
         z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=dev)
         self.enc_out = {
@@ -82,17 +97,19 @@ class Cfg2Pipeline:
         self.dec_ws = md.decode_workspace(B, self.Lcap, H)
         self.scale = 1.0 / float(np.sqrt(d))
         self.gamma, self.alpha = 1.0 / M, 2.0 / (M + N)
+        self.row_lse = None
 
     def encode(self):
         c = self.cfg
         self.md.mustdrop_encode_merge(self.x, self.q_cls, self.k_cls, None, None, c.T, c.Hg, c.Wg, c.kt, c.kh, c.kw,
-                                      BENCH_TAU, c.key_budget, out=self.enc_out, workspace=self.enc_ws)
+                                      self.tau, c.key_budget, out=self.enc_out, workspace=self.enc_ws)
 
-    def prefill(self):
+    def prefill(self, with_lse=False):
         c = self.cfg
         self.md.mustdrop_prefill_filter(self.q_txt, self.k, self.v, self.hidden, self.enc_out["out_valid"], None,
                                         self.enc_out["out_is_key"], c.M, self.scale, self.md.FILTER_BUDGET, self.R,
-                                        self.gamma, self.alpha, Rcap=self.R, out=self.pre_out, workspace=self.pre_ws)
+                                        self.gamma, self.alpha, Rcap=self.R, out=self.pre_out, workspace=self.pre_ws,
+                                        row_lse=self.row_lse if with_lse else None)
 
     def decode(self):
         # decay 0: the running score is overwritten, so the step is idempotent across benchmark iterations
@@ -105,65 +122,199 @@ class Cfg2Pipeline:
         self.prefill()
         self.decode()
 
+    def make_row_lse(self):
+        """What the layer's attention kernel would hand over (Sec. 3.4): per head and text row, the natural-log
+        sum of exp(scale * q.k) over the valid vision keys and the text keys 0..i.  Plain torch: an INPUT of the
+        benchmark's with-LSE variant, made once outside every timed region."""
+        torch, c = self.torch, self.cfg
+        valid = self.enc_out["out_valid"].bool()                             # [B, M]
+        causal = torch.ones((c.N, c.N), dtype=torch.bool, device="cuda").tril()
+        out = torch.empty((c.B, c.H, c.N), dtype=torch.float32, device="cuda")
+        for b in range(c.B):                                                 # one sample at a time: [H, N, L] fp32
+            lg = torch.einsum("ihc,jhc->hij", self.q_txt[b].float(), self.k[b].float()) * self.scale
+            mask = torch.cat([valid[b][None, :].expand(c.N, c.M), causal], dim=1)
+            out[b] = torch.logsumexp(lg.masked_fill(~mask[None], float("-inf")), dim=-1)
+        self.row_lse = out
 
-def timed(torch, fn, iters):
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(iters):
-        fn()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / iters
 
-
-# HBM bytes per launch on the benchmark workload, from two rocprofv3 --pmc runs of this script
+# HBM bytes per launch of the headline workload's kernels, from two rocprofv3 --pmc runs of this script
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same counters show for a plain
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
-# The runs and the raw figures are in profiles/hbm_traffic_cfg2_llava15_b16.txt.
-MEASURED_HBM_TRAFFIC_BYTES = {
-    "prefill_compact": int((36690.0 * 2.0 + 73152.0) * 1024),
-    "prefill_select": int((12443.1 * 2.0 + 24609.0) * 1024),
-    "prefill_rowstats": int((45197.4 * 2.0 + 8320.0) * 1024),
-    "prefill_colscore": int((41248.8 * 2.0 + 72.0) * 1024),
-    "encode_scores": int((18683.6 * 2.0 + 854.2) * 1024),
-    "encode_emit": int((9330.5 * 2.0 + 14287.5) * 1024),
-    "decode_logits": int((16837.0 * 2.0 + 765.0) * 1024),
-    "decode_move": int((8105.0 * 2.0 + 16000.0) * 1024),
-}
+# The runs and the raw figures are in profiles/hbm_traffic_cfg3_llavanext_b8.txt.
+MEASURED_HBM_TRAFFIC_BYTES = {}
 
 
-def kernel_bytes(cfg, pipe, counts):
-    """Algorithmic bytes per launch of every kernel of the step (what the method itself must move)."""
+def stage_bytes(cfg, pipe, counts):
+    """Algorithmic bytes per stage and per kernel (what the method itself must move), one step."""
     B, M, N, H, d, C, D = cfg.B, cfg.M, cfg.N, cfg.H, cfg.d, cfg.C, cfg.D
     e = 2 if cfg.x_dtype == wl.BF16 else 4
     L = M + N
-    surv = counts["encode_survivors"]
-    rows = counts["prefill_rows"]
-    dec_len = counts["decode_entries"]
-    moves = counts["decode_moves"]
-    return {
+    vrows = counts["encode_survivors"]               # valid vision rows entering the prefill stage (the rest is padding)
+    surv, rows, text_rows = counts["encode_survivors"], counts["prefill_rows"], counts["prefill_text_rows"]
+    dec_len, moves = counts["decode_entries"], counts["decode_moves"]
+    row48 = (C + 2 * H * d) * 2
+    kb = {
         "encode_scores": B * M * D * e + B * (M + 1) * D * e + B * (M + 1) * cfg.Hc * 4,
         "encode_decide": B * (M + 1) * cfg.Hc * 4 + B * M * 16,
         "encode_emit": B * M * D * e + surv * D * e,
-        "prefill_rowstats": B * (L + N) * H * d * 2,
+        "prefill_rowstats": (vrows + 2 * B * N) * H * d * 2,
         "prefill_cstat": B * H * N * 12,
-        "prefill_colscore": B * (M + N) * H * d * 2,
+        "prefill_qpack": 2 * B * N * H * d * 2,
+        "prefill_colscore": (vrows + B * N) * H * d * 2,
+        "prefill_colfix": vrows * N * 4,
         # budget mode on dense layouts: the text rows are copied by further blocks of the selection launch,
         # the compaction kernel moves the kept vision rows only
-        "prefill_select": B * M * 16 + 2 * counts["prefill_text_rows"] * (C + 2 * H * d) * 2,
-        "prefill_compact": 2 * (rows - counts["prefill_text_rows"]) * (C + 2 * H * d) * 2,
+        "prefill_select": B * M * 16 + 2 * text_rows * row48,
+        "prefill_compact": 2 * (rows - text_rows) * row48,
         "decode_logits": dec_len * H * d * 2 + dec_len * H * 4,
         "decode_select": 3 * dec_len * H * 4,
         "decode_move": 2 * moves * 2 * H * d * 2,
     }
+    st = {
+        # x once + k_cls once + the survivors written + index / mass / flag per token
+        "encode": B * M * D * e + B * (M + 1) * D * e + surv * D * e + B * M * 13,
+        # K (valid vision rows and the text rows) and Q_txt once per sample
+        "prefill_score": (vrows + 2 * B * N) * H * d * 2,
+        "prefill_select": B * M * 8,
+        "prefill_compact": 2 * rows * row48,
+        # the live cache's K rows once + the rows moved (read and written)
+        "decode": dec_len * H * d * 2 + 2 * moves * 2 * H * d * 2,
+    }
+    st["prefill"] = st["prefill_score"] + st["prefill_select"] + st["prefill_compact"]
+    flops = {"prefill_rowstats": 2.0 * H * N * (vrows + B * N) * d, "prefill_colscore": 2.0 * H * N * vrows * d}
+    return kb, st, flops
 
 
-def decode_loop_cfg5(torch, md, harness, steps):
+def profile_steps(binding, fn, iters):
+    binding.profile_start()
+    for _ in range(iters):
+        fn()
+    prof = binding.profile_stop()
+    return {n: r["ms"] * 1e3 / max(r["calls"], 1) for n, r in prof.items()}, {n: r["calls"] for n, r in prof.items()}
+
+
+def copy_ceiling(torch, nbytes, reps=24, pairs=4):
+    """What a plain device-to-device copy of the same size reaches on this box (bytes read + written per
+    second), rotating over several source / destination pairs so that no call finds its data in the
+    256 MB Infinity Cache."""
+    half = max(nbytes // 2, 1 << 20)
+    bufs = [(torch.empty(half, dtype=torch.uint8, device="cuda"), torch.empty(half, dtype=torch.uint8, device="cuda"))
+            for _ in range(pairs)]
+    state = {"i": 0}
+
+    def one():
+        src, dst = bufs[state["i"] % pairs]
+        state["i"] += 1
+        dst.copy_(src)
+
+    for _ in range(pairs):
+        one()
+    ms = timed(torch, one, reps)
+    del bufs
+    return 2 * half / (ms * 1e-3) / 1e9
+
+
+def frac(nbytes, us):
+    return round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None
+
+
+def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceiling=False):
+    """One prefill workload: the chained step, its stages, its kernels, the with-LSE variant, cold inputs."""
+    pipe = Pipeline(cfg, torch, md, harness)
+    for _ in range(warmup):
+        pipe.step()
+    step_ms = timed(torch, pipe.step, steps)
+    enc_ms = timed(torch, pipe.encode, steps)
+    pre_ms = timed(torch, pipe.prefill, steps)
+    pipe.prefill()
+    dec_ms = timed(torch, lambda: (pipe.prefill(), pipe.decode()), steps) - pre_ms
+    k_us, k_calls = profile_steps(binding, pipe.step, steps)
+    torch.cuda.synchronize()
+
+    out_count = pipe.enc_out["out_count"].cpu().numpy()
+    kept = np.minimum(pipe.pre_out["kept_count"].cpu().numpy(), pipe.R)
+    pipe.prefill()
+    torch.cuda.synchronize()
+    dec_len = pipe.pre_out["out_len"].cpu().numpy().copy()
+    kept_index = pipe.pre_out["kept_index"].clone()
+    pipe.decode()
+    torch.cuda.synchronize()
+    dec_after = pipe.pre_out["out_len"].cpu().numpy()
+    counts = {"encode_survivors": int(out_count.sum()), "prefill_rows": int((kept + cfg.N).sum()),
+              "prefill_text_rows": int(cfg.B * cfg.N), "decode_entries": int(dec_len.sum()),
+              "decode_moves": int(np.minimum(dec_after, dec_len - dec_after).sum())}
+    kb, sb, flops = stage_bytes(cfg, pipe, counts)
+
+    # the same prefill call with the attention kernel's row normalisers handed over (one sweep over K)
+    pipe.make_row_lse()
+    pipe.prefill(with_lse=True)
+    torch.cuda.synchronize()
+    same = bool((pipe.pre_out["kept_index"] == kept_index).all())
+    lse_ms = timed(torch, lambda: pipe.prefill(with_lse=True), steps)
+    lse_us, _ = profile_steps(binding, lambda: pipe.prefill(with_lse=True), steps)
+    torch.cuda.synchronize()
+    pipe.prefill()
+
+    kernels = {}
+    for name, us in k_us.items():
+        nb = kb.get(name, 0)
+        kernels[name] = {"avg_us": round(us, 2), "calls": k_calls[name], "algorithmic_MB": round(nb / 1e6, 3),
+                         "GBps": round(nb / (us * 1e-6) / 1e9, 1) if us > 0 else 0.0, "frac_of_hbm_peak": frac(nb, us)}
+        if name in flops:
+            kernels[name]["mfma_frac"] = round(flops[name] / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+    score_names = ("prefill_rowstats", "prefill_cstat", "prefill_colscore", "prefill_colfix")
+    score_us = sum(k_us.get(n, 0.0) for n in score_names)
+    lse_score_us = sum(lse_us.get(n, 0.0) for n in ("prefill_qpack", "prefill_colscore", "prefill_colfix"))
+    tokens = cfg.B * cfg.M
+    tps = lambda ms: tokens / (ms * 1e-3)
+    stages = {
+        "encode": {"us": round(enc_ms * 1e3, 2), "vision_tokens_per_s": tps(enc_ms),
+                   "algorithmic_MB": round(sb["encode"] / 1e6, 2), "frac_of_hbm_peak": frac(sb["encode"], enc_ms * 1e3)},
+        "prefill": {"us": round(pre_ms * 1e3, 2), "vision_tokens_per_s": tps(pre_ms),
+                    "algorithmic_MB": round(sb["prefill"] / 1e6, 2), "frac_of_hbm_peak": frac(sb["prefill"], pre_ms * 1e3),
+                    "score_us": round(score_us, 2), "score_algorithmic_MB": round(sb["prefill_score"] / 1e6, 2),
+                    "score_frac_of_hbm_peak": frac(sb["prefill_score"], score_us),
+                    "score_mfma_frac": round(sum(flops.values()) / (score_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "select_us": round(k_us.get("prefill_select", 0.0), 2),
+                    "compact_us": round(k_us.get("prefill_compact", 0.0), 2)},
+        "decode": {"us": round(dec_ms * 1e3, 2), "vision_tokens_per_s": tps(dec_ms),
+                   "algorithmic_MB": round(sb["decode"] / 1e6, 2), "frac_of_hbm_peak": frac(sb["decode"], dec_ms * 1e3)},
+    }
+    step_bytes = sb["encode"] + sb["prefill"] + sb["decode"]
+    dominant = max(kernels, key=lambda n: kernels[n]["avg_us"])
+    traffic = MEASURED_HBM_TRAFFIC_BYTES.get(dominant) if cfg.number == HEADLINE else None
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"], "traffic": traffic,
+                "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
+                "algorithmic_bytes": kb.get(dominant, 0), "avg_us": kernels[dominant]["avg_us"]}
+    if "mfma_frac" in kernels[dominant]:
+        roofline["mfma_frac"] = kernels[dominant]["mfma_frac"]
+    if with_ceiling and kb.get(dominant, 0) > 0:
+        ceiling = copy_ceiling(torch, kb[dominant])
+        roofline["plain_copy_same_size_GBps"] = round(ceiling, 1)
+        roofline["frac_of_plain_copy"] = round(roofline["achieved"] / ceiling, 4)
+    block = {
+        "workload": cfg.name, "batch": cfg.B, "vision_tokens": cfg.M, "text_tokens": cfg.N,
+        "window": f"{cfg.kt}x{cfg.kh}x{cfg.kw}", "tau": pipe.tau, "key_budget": cfg.key_budget,
+        "prefill_budget": pipe.R, "decode_budget": pipe.decode_budget,
+        "us_per_step": round(step_ms * 1e3, 2), "vision_tokens_per_s": tps(step_ms),
+        "step_algorithmic_MB": round(step_bytes / 1e6, 2), "step_frac_of_hbm_peak": frac(step_bytes, step_ms * 1e3),
+        "stages": stages, "counts": counts, "kernels": kernels, "roofline": roofline,
+        "prefill_with_lse": {"us": round(lse_ms * 1e3, 2), "score_us": round(lse_score_us, 2),
+                             "score_frac_of_hbm_peak": frac(sb["prefill_score"], lse_score_us),
+                             "kernels_us": {n: round(u, 2) for n, u in lse_us.items()},
+                             "same_selection_as_without": same},
+    }
+    return pipe, block, step_ms
+
+
+def decode_loop_cfg5(torch, md, binding, harness, steps):
     """Decode-stage workload proper: batch 64, 4096-entry cache, 256 steps, budget 1024."""
     cfg = wl.CONFIGS[5]
     steps = min(steps, cfg.steps)
     t0 = time.time()
     t = wl.decode_inputs(cfg, steps=steps)
-    log(f"[bench] generated decode workload in {time.time() - t0:.1f}s")
+    log(f"[bench] {cfg.name}: generated decode workload in {time.time() - t0:.1f}s")
     B, Lcap, H, d = cfg.B, t["Lcap"], cfg.H, cfg.d
     kc, vc = harness.to_dev(t["k_cache"], True), harness.to_dev(t["v_cache"], True)
     qs, kn, vn = (harness.to_dev(t[n], True) for n in ("q_steps", "k_new", "v_new"))
@@ -184,22 +335,41 @@ def decode_loop_cfg5(torch, md, harness, steps):
     ev[0].record()
     md.mustdrop_decode_evict(qs[0], kc, vc, acc, ids, protect, length, scale, 1.0, cfg.decode_budget, workspace=ws)
     ev[1].record()
+    half = max(steps // 2, 1)
     for s in range(1, steps):
+        if s == half:
+            torch.cuda.synchronize()
+            binding.profile_start()                   # per-kernel durations over the second half of the loop
         md.mustdrop_decode_append(kn[s], vn[s], kc, vc, acc, ids, protect, length, cfg.L0 + s, 1)
         md.mustdrop_decode_evict(qs[s], kc, vc, acc, ids, protect, length, scale, 1.0, cfg.decode_budget, workspace=ws)
+    prof = binding.profile_stop() if steps > half else {}
     ev[2].record()
     torch.cuda.synchronize()
     total_ms = (time.perf_counter() - t0) * 1e3
     first_ms = ev[0].elapsed_time(ev[1])
-    steady_ms = ev[1].elapsed_time(ev[2]) / max(steps - 1, 1)
-    entries = B * cfg.L0 + (steps - 1) * B * (cfg.decode_budget + 1)
     assert int(length.min()) == cfg.decode_budget and int(length.max()) == cfg.decode_budget
-    steady_bytes = B * (cfg.decode_budget + 1) * H * d * 2
+    # steady state timed on its own (the profiled half above carries the event overhead)
+    def steady():
+        s = steps - 1
+        md.mustdrop_decode_append(kn[s], vn[s], kc, vc, acc, ids, protect, length, cfg.L0 + steps, 1)
+        md.mustdrop_decode_evict(qs[s], kc, vc, acc, ids, protect, length, scale, 1.0, cfg.decode_budget, workspace=ws)
+    steady_ms = timed(torch, steady, 64)
+    entries = B * cfg.L0 + (steps - 1) * B * (cfg.decode_budget + 1)
+    steady_bytes = B * (cfg.decode_budget + 1) * H * d * 2 + 2 * B * 2 * H * d * 2
+    k_us = {n: round(r["ms"] * 1e3 / max(r["calls"], 1), 2) for n, r in prof.items()}
+    logits_bytes = B * (cfg.decode_budget + 1) * (H * d * 2 + H * 4)
+    roof = None
+    if "decode_logits" in k_us:
+        roof = {"bound": "hbm", "kernel": "decode_logits", "avg_us": k_us["decode_logits"], "algorithmic_bytes": logits_bytes,
+                "achieved": round(logits_bytes / (k_us["decode_logits"] * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": frac(logits_bytes, k_us["decode_logits"])}
     return {
-        "workload": cfg.name, "steps": steps, "entries_scored_per_s": entries / (total_ms * 1e-3),
-        "total_ms": total_ms, "first_step_ms": first_ms, "steady_us_per_step": steady_ms * 1e3,
-        "steady_k_read_GBps": steady_bytes / (steady_ms * 1e-3) / 1e9,
-        "first_step_k_read_GBps": B * cfg.L0 * H * d * 2 / (first_ms * 1e-3) / 1e9,
+        "workload": cfg.name, "batch": B, "initial_entries": cfg.L0, "budget": cfg.decode_budget, "steps": steps,
+        "entries_scored_per_s": entries / (total_ms * 1e-3), "total_ms": round(total_ms, 3),
+        "first_step_ms": round(first_ms, 4), "first_step_k_read_GBps": round(B * cfg.L0 * H * d * 2 / (first_ms * 1e-3) / 1e9, 1),
+        "first_step_frac_of_hbm_peak": round(B * cfg.L0 * H * d * 2 / (first_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "steady_us_per_step": round(steady_ms * 1e3, 2), "steady_algorithmic_MB": round(steady_bytes / 1e6, 2),
+        "steady_frac_of_hbm_peak": frac(steady_bytes, steady_ms * 1e3), "kernels_us": k_us, "roofline": roof,
     }
 
 
@@ -241,7 +411,7 @@ def progressive_prefill(torch, md, harness, cfg, pipe, iters=100):
     per_call = [timed(torch, lambda l=l: call(l), iters) for l in range(len(budgets))]
     kept = [int(o["kept_count"].min()) for o in outs]
     assert kept == budgets, kept
-    return {"workload": cfg.name, "vision_tokens": [cfg.M] + budgets, "us_per_chain": total * 1e3,
+    return {"workload": cfg.name, "vision_tokens": [cfg.M] + budgets, "us_per_chain": round(total * 1e3, 2),
             "us_per_call": [round(x * 1e3, 2) for x in per_call],
             "vision_tokens_per_s": B * cfg.M / (total * 1e-3)}
 
@@ -286,73 +456,33 @@ def static_handoff(torch, md, binding, cfg, layers=32, kept_vision=64, reps=10, 
             "move_GBps": round(move_bytes / (us.get("decode_move", 1e9) * 1e-6) / 1e9, 1)}
 
 
-def copy_ceiling(torch, nbytes, reps=24, pairs=4):
-    """What a plain device-to-device copy of the same size reaches on this box (bytes read + written per
-    second), rotating over several source / destination pairs so that no call finds its data in the
-    256 MB Infinity Cache."""
-    half = nbytes // 2
-    bufs = [(torch.empty(half, dtype=torch.uint8, device="cuda"), torch.empty(half, dtype=torch.uint8, device="cuda"))
-            for _ in range(pairs)]
-    state = {"i": 0}
-
-    def one():
-        src, dst = bufs[state["i"] % pairs]
-        state["i"] += 1
-        dst.copy_(src)
-
-    for _ in range(pairs):
-        one()
-    ms = timed(torch, one, reps)
-    del bufs
-    return 2 * half / (ms * 1e-3) / 1e9
-
-
-def cold_vs_warm(torch, pipe, iters=64, sets=16):
-    """Stage times with the inputs rotating over `sets` distinct copies (more than the 256 MB Infinity Cache
+def cold_vs_warm(torch, pipe, iters=48):
+    """Stage times with the inputs rotating over several distinct copies (more than the 256 MB Infinity Cache
     in total: every call finds its inputs in HBM) against the same call repeated on one set."""
     out = {}
-    names = ("x", "q_cls", "k_cls")
-    orig = {n: getattr(pipe, n) for n in names}
-    copies = [{n: t.clone() for n, t in orig.items()} for _ in range(sets)]
     state = {"i": 0}
+    for stage, names, fn in (("encode", ("x", "q_cls", "k_cls"), pipe.encode), ("prefill", ("q_txt", "k", "v", "hidden"), pipe.prefill)):
+        orig = {n: getattr(pipe, n) for n in names}
+        mb = sum(t.numel() * t.element_size() for t in orig.values()) / 1e6
+        sets = int(min(16, max(2, np.ceil(600.0 / mb))))
+        copies = [orig] + [{n: t.clone() for n, t in orig.items()} for _ in range(sets - 1)]
 
-    def rotating():
-        for n, t in copies[state["i"] % sets].items():
+        def rotating():
+            for n, t in copies[state["i"] % sets].items():
+                setattr(pipe, n, t)
+            state["i"] += 1
+            fn()
+
+        for _ in range(sets):
+            rotating()
+        cold = timed(torch, rotating, iters)
+        for n, t in orig.items():
             setattr(pipe, n, t)
-        state["i"] += 1
-        pipe.encode()
-
-    for _ in range(sets):
-        rotating()
-    cold = timed(torch, rotating, iters)
-    for n, t in orig.items():
-        setattr(pipe, n, t)
-    pipe.encode()
-    warm = timed(torch, pipe.encode, iters)
-    mb = sum(t.numel() * t.element_size() for t in orig.values()) / 1e6
-    out["encode"] = {"warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2), "input_MB_per_set": round(mb, 1),
-                     "sets": sets}
-    del copies
-    names = ("q_txt", "k", "v", "hidden")
-    orig = {n: getattr(pipe, n) for n in names}
-    copies = [orig, {n: t.clone() for n, t in orig.items()}]
-
-    def rotating2():
-        for n, t in copies[state["i"] % 2].items():
-            setattr(pipe, n, t)
-        state["i"] += 1
-        pipe.prefill()
-
-    for _ in range(4):
-        rotating2()
-    cold = timed(torch, rotating2, iters)
-    for n, t in orig.items():
-        setattr(pipe, n, t)
-    pipe.prefill()
-    warm = timed(torch, pipe.prefill, iters)
-    mb = sum(t.numel() * t.element_size() for t in orig.values()) / 1e6
-    out["prefill"] = {"warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2), "input_MB_per_set": round(mb, 1),
-                      "sets": 2}
+        fn()
+        warm = timed(torch, fn, iters)
+        out[stage] = {"warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2), "input_MB_per_set": round(mb, 1),
+                      "sets": sets}
+        del copies
     return out
 
 
@@ -369,7 +499,7 @@ def variable_length(torch, md, cfg, pipe):
            "out_is_key": z((B, M), u8), "out_valid": z((B, M), u8), "out_count": z((B,), i32),
            "key_index": z((B, M), i32), "key_count": z((B,), i32), "a_cls": None, "window_sim": None}
     md.mustdrop_encode_merge_adaptive(pipe.x, pipe.q_cls, pipe.k_cls, None, None, c.T, c.Hg, c.Wg, c.kt, c.kh, c.kw,
-                                      BENCH_TAU, lam, M, out=enc, workspace=pipe.enc_ws)
+                                      pipe.tau, lam, M, out=enc, workspace=pipe.enc_ws)
     ws = md.prefill_workspace(B, M, N, H, M)
     pre = None
 
@@ -395,25 +525,10 @@ def variable_length(torch, md, cfg, pipe):
     us = timed(torch, lambda: call(s), 50) * 1e3
     oc, kc, kk = (t.cpu().numpy() for t in (enc["out_count"], enc["key_count"], pre["kept_count"]))
     d3 = lambda a: {"mean": round(float(a.mean()), 1), "min": int(a.min()), "max": int(a.max())}
-    return {"encode_survivors": d3(oc), "adaptive_keys": dict(d3(kc), key_lambda=lam), "prefill_threshold_kept": d3(kk),
-            "gamma": pipe.gamma * s, "alpha": pipe.alpha * s, "prefill_threshold_us": round(us, 2),
+    return {"workload": cfg.name, "encode_survivors": d3(oc), "adaptive_keys": dict(d3(kc), key_lambda=lam),
+            "prefill_threshold_kept": d3(kk), "gamma": pipe.gamma * s, "alpha": pipe.alpha * s,
+            "prefill_threshold_us": round(us, 2),
             "paper_table3_average_tokens": {"encode": 440, "prefill": 64, "decode": 45}}
-
-
-def single_image_latency(torch, md, harness, iters=300):
-    """The latency workload: one image (1 x 24 x 24 fp32 patch tokens, 32 text tokens) through the same
-    chained three-stage step; microseconds per stage and per step."""
-    cfg = wl.CONFIGS[1]
-    pipe = Cfg2Pipeline(cfg, torch, md, harness)
-    for _ in range(10):
-        pipe.step()
-    step = timed(torch, pipe.step, iters)
-    enc = timed(torch, pipe.encode, iters)
-    pre = timed(torch, pipe.prefill, iters)
-    pipe.prefill()
-    dec = timed(torch, lambda: (pipe.prefill(), pipe.decode()), iters) - pre
-    return {"workload": cfg.name, "us_per_step": round(step * 1e3, 2), "encode_us": round(enc * 1e3, 2),
-            "prefill_us": round(pre * 1e3, 2), "decode_us": round(dec * 1e3, 2)}
 
 
 def cpu_info():
@@ -429,82 +544,87 @@ def cpu_info():
     return {"cpu_model": model, "nproc": os.cpu_count()}
 
 
+def oracle_step(cfg, pipe, b):
+    """One sample of the chained step through the oracle."""
+    import oracle
+    e = {k: v[b:b + 1] for k, v in pipe.enc_np.items() if k != "ell"}
+    p = {k: v[b:b + 1] for k, v in pipe.pre_np.items()}
+    o1 = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
+                             cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, pipe.tau, cfg.key_budget)
+    o2 = oracle.prefill_filter(p["q_txt"], p["k"], p["v"], p["hidden"], o1["out_valid"], None, o1["out_is_key"],
+                               cfg.M, pipe.scale, oracle.FILTER_BUDGET, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
+    acc = np.zeros((1, pipe.Lcap), np.float32)
+    oracle.decode_evict(pipe.q_dec_np[b:b + 1], o2["k_out"], o2["v_out"], acc, o2["out_ids"], o2["out_protect"],
+                        o2["out_len"], pipe.scale, 0.0, pipe.decode_budget)
+    return o1, o2
+
+
 def cpu_baseline(cfg, pipe, min_seconds=10.0):
-    """The oracle, as it stands, on this host: the same chained step on the full batch of 16."""
+    """The oracle, as it stands, on this host: the same chained step, one thread per sample of the batch."""
     import oracle
     from concurrent.futures import ThreadPoolExecutor
     cores = min(os.cpu_count() or 1, 16, cfg.B)
-
-    def one(b):
-        e = {k: v[b:b + 1] for k, v in pipe.enc_np.items() if k != "ell"}
-        p = {k: v[b:b + 1] for k, v in pipe.pre_np.items()}
-        o1 = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
-                                 cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU, cfg.key_budget)
-        o2 = oracle.prefill_filter(p["q_txt"], p["k"], p["v"], p["hidden"], o1["out_valid"], None, o1["out_is_key"],
-                                   cfg.M, pipe.scale, oracle.FILTER_BUDGET, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
-        acc = np.zeros((1, pipe.Lcap), np.float32)
-        oracle.decode_evict(pipe.q_dec_np[b:b + 1], o2["k_out"], o2["v_out"], acc, o2["out_ids"], o2["out_protect"],
-                            o2["out_len"], pipe.scale, 0.0, pipe.decode_budget)
-        return o1, o2
-
     oracle.lib()
-    t0, n1 = time.perf_counter(), 0
-    while n1 < cfg.B and (n1 == 0 or time.perf_counter() - t0 < 2.0):       # one thread, about two seconds of samples
-        one(n1)
-        n1 += 1
-    single = n1 * cfg.M / (time.perf_counter() - t0)
+    t0 = time.perf_counter()
+    oracle_step(cfg, pipe, 0)                       # one thread, one sample
+    single = cfg.M / (time.perf_counter() - t0)
     reps, t0 = 0, time.perf_counter()
-    with ThreadPoolExecutor(cores) as ex:        # ctypes releases the GIL: samples run in parallel
+    with ThreadPoolExecutor(cores) as ex:           # ctypes releases the GIL: samples run in parallel
         while True:
-            list(ex.map(one, range(cfg.B)))
+            list(ex.map(lambda b: oracle_step(cfg, pipe, b), range(cfg.B)))
             reps += 1
             dt = time.perf_counter() - t0
             if dt >= min_seconds or reps >= 500:
                 break
     return {"value": reps * cfg.B * cfg.M / dt, "unit": "vision tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"the full batch of {cfg.B} samples through all three oracle stages, {reps} repetitions, "
-                      f"{dt:.1f}s, one thread per sample",
-            "single_thread": {"value": single, "unit": "vision tokens/s", "sample": f"{n1} samples of the batch"},
+            "sample": f"the full batch of {cfg.B} samples of {cfg.name} through all three oracle stages, {reps} "
+                      f"repetition(s), {dt:.1f}s, one thread per sample",
+            "single_thread": {"value": single, "unit": "vision tokens/s", "sample": "one sample of the batch"},
             **cpu_info()}
 
 
 def parity_check(cfg, pipe, harness):
     """Last step's GPU outputs against the oracle on the full batch (same rules as the GPU tests)."""
     import oracle
+    from concurrent.futures import ThreadPoolExecutor
     from parity import check_encode, check_prefill
     g1 = harness.outputs_to_host(pipe.enc_out)
     e = pipe.enc_np
-    o1 = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
-                             cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU, cfg.key_budget)
+    args = (cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, pipe.tau, cfg.key_budget)
+    o1 = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None, *args)
     # the timed step does not ask for the optional score outputs: rerun once with them for the margin rule
-    gs = harness.encode_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None,
-                               cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU, cfg.key_budget)
+    gs = harness.encode_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, None, *args)
     assert np.array_equal(gs["out_count"], g1["out_count"]) and np.array_equal(gs["key_index"], g1["key_index"])
     for b in range(cfg.B):                      # rows beyond out_count are never written: compare the live part
         n = int(g1["out_count"][b])
         for name in ("out_index", "out_is_key", "out_x"):
             assert np.array_equal(gs[name][b, :n], g1[name][b, :n]), f"timed step and checked step differ in {name}"
-    s1 = check_encode(gs, o1, e["x"], cfg.x_dtype, None, cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, BENCH_TAU,
-                      cfg.key_budget)
+    s1 = check_encode(gs, o1, e["x"], cfg.x_dtype, None, *args)
     p = pipe.pre_np
     vv, kk = g1["out_valid"], g1["out_is_key"]
     gp = harness.prefill_on_gpu(p, cfg.M, vv, None, kk, pipe.scale, 0, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
-    o2 = oracle.prefill_filter(p["q_txt"], p["k"], p["v"], p["hidden"], vv, None, kk, cfg.M, pipe.scale, 0, pipe.R,
-                               pipe.gamma, pipe.alpha, pipe.R)
+
+    def one(b):
+        return oracle.prefill_filter(p["q_txt"][b:b + 1], p["k"][b:b + 1], p["v"][b:b + 1], p["hidden"][b:b + 1],
+                                     vv[b:b + 1], None, kk[b:b + 1], cfg.M, pipe.scale, 0, pipe.R, pipe.gamma,
+                                     pipe.alpha, pipe.R)
+    with ThreadPoolExecutor(min(os.cpu_count() or 1, 16, cfg.B)) as ex:
+        parts = list(ex.map(one, range(cfg.B)))
+    o2 = {k: np.concatenate([q[k] for q in parts], axis=0) for k in parts[0]}
     s2 = check_prefill(gp, o2, p, cfg.M, vv, kk, 0, pipe.R, pipe.gamma, pipe.alpha, pipe.R)
-    return {"encode": s1, "prefill": s2, "status": "pass"}
+    return {"workload": cfg.name, "encode": s1, "prefill": s2, "status": "pass"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-decode-loop", action="store_true")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workloads", default="1,2,3,4,5", help="which workload blocks to measure besides the headline")
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
-    ap.add_argument("--no-progressive", action="store_true", help="skip the chained-prefill and hand-off extras")
+    ap.add_argument("--no-extras", action="store_true", help="skip the chained-prefill, hand-off, cold-input and threshold extras")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) to scale rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -519,8 +639,7 @@ def main():
     import paper_2411_10803_amd as md
     from paper_2411_10803_amd import binding, harness
     md.library()
-    cfg = wl.CONFIGS[2]
-    pipe = Cfg2Pipeline(cfg, torch, md, harness)
+    want = sorted({int(x) for x in args.workloads.split(",") if x} | {HEADLINE})
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -529,81 +648,55 @@ def main():
             dst.copy_(src)          # plain copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        pipe.step()
-    ms_per_step = timed(torch, pipe.step, args.steps)
-    stage_ms = {"encode": timed(torch, pipe.encode, args.steps), "prefill": timed(torch, pipe.prefill, args.steps)}
-    pipe.prefill()
-    stage_ms["decode"] = timed(torch, lambda: (pipe.prefill(), pipe.decode()), args.steps) - stage_ms["prefill"]
 
-    # per-kernel durations with HIP events on the launch stream, over the same steps
-    binding.profile_start()
-    for _ in range(args.steps):
-        pipe.step()
-    prof = binding.profile_stop()
-    torch.cuda.synchronize()
-
-    out_count = pipe.enc_out["out_count"].cpu().numpy()
-    kept = np.minimum(pipe.pre_out["kept_count"].cpu().numpy(), pipe.R)
-    pipe.prefill()
-    torch.cuda.synchronize()
-    dec_len = pipe.pre_out["out_len"].cpu().numpy().copy()
-    pipe.decode()
-    torch.cuda.synchronize()
-    dec_after = pipe.pre_out["out_len"].cpu().numpy()
-    counts = {"encode_survivors": int(out_count.sum()), "prefill_rows": int((kept + cfg.N).sum()),
-              "prefill_text_rows": int(cfg.B * cfg.N),
-              "decode_entries": int(dec_len.sum()), "decode_moves": int(np.minimum(dec_after, dec_len - dec_after).sum())}
-    kb = kernel_bytes(cfg, pipe, counts)
-    kernels = {}
-    for name, r in prof.items():
-        us = r["ms"] * 1e3 / max(r["calls"], 1)
-        gbs = kb.get(name, 0) / (us * 1e-6) / 1e9 if us > 0 else 0.0
-        kernels[name] = {"avg_us": round(us, 2), "calls": r["calls"], "algorithmic_MB": round(kb.get(name, 0) / 1e6, 3),
-                         "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
-    dominant = max(kernels, key=lambda n: kernels[n]["avg_us"])
-    traffic = MEASURED_HBM_TRAFFIC_BYTES.get(dominant) if cfg.name == "cfg2_llava15_b16" else None
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": kernels[dominant]["GBps"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": kernels[dominant]["frac_of_hbm_peak"], "traffic": traffic,
-                "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
-                "algorithmic_bytes": kb.get(dominant, 0), "avg_us": kernels[dominant]["avg_us"]}
-
-    ceiling = copy_ceiling(torch, kb.get(dominant, 0)) if kb.get(dominant, 0) > 0 else None
-    if ceiling:
-        roofline["plain_copy_same_size_GBps"] = round(ceiling, 1)
-        roofline["frac_of_plain_copy"] = round(roofline["achieved"] / ceiling, 4)
-
-    tokens = cfg.B * cfg.M
+    # the headline first: its K timed steps after W warm-up steps are the figures of the contract
+    cfg = wl.CONFIGS[HEADLINE]
+    pipe, head, ms_per_step = measure_workload(torch, md, binding, harness, cfg, args.steps, args.warmup, with_ceiling=True)
+    blocks = {cfg.name: head}
     result = {
         "metric": "vision tokens processed/sec per pipeline stage; achieved % of HBM/MFMA roofline",
-        "value": tokens / (ms_per_step * 1e-3), "unit": "vision tokens/s",
+        "value": cfg.B * cfg.M / (ms_per_step * 1e-3), "unit": "vision tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.B, "vision_tokens": cfg.M, "text_tokens": cfg.N,
-                   "vision_dim": cfg.D, "heads": cfg.H, "head_dim": cfg.d, "hidden": cfg.C, "window": "1x2x2",
-                   "tau": BENCH_TAU, "key_budget": cfg.key_budget, "prefill_budget": pipe.R,
-                   "decode_budget": pipe.decode_budget, "step": "encode_merge -> prefill_filter -> decode_evict"},
-        "stages": {s: {"ms": round(m, 4), "vision_tokens_per_s": tokens / (m * 1e-3)} for s, m in stage_ms.items()},
-        "counts": counts,
-        "roofline": roofline,
-        "kernels": kernels,
+                   "vision_dim": cfg.D, "heads": cfg.H, "head_dim": cfg.d, "hidden": cfg.C,
+                   "window": f"{cfg.kt}x{cfg.kh}x{cfg.kw}", "tau": pipe.tau, "key_budget": cfg.key_budget,
+                   "prefill_budget": pipe.R, "decode_budget": pipe.decode_budget,
+                   "step": "encode_merge -> prefill_filter -> decode_evict"},
+        "stages": head["stages"], "counts": head["counts"], "roofline": head["roofline"], "kernels": head["kernels"],
     }
-    if not args.no_decode_loop:
-        result["decode_loop"] = decode_loop_cfg5(torch, md, harness, args.decode_steps)
-    if not args.no_progressive:
-        result["progressive_prefill"] = progressive_prefill(torch, md, harness, cfg, pipe)
-    if not args.no_progressive:
-        result["static_handoff"] = static_handoff(torch, md, binding, cfg)
-        result["static_handoff_video"] = static_handoff(torch, md, binding, cfg, B=8, M=2048, kept_vision=1024, reps=5,
-                                                        name="video_8x256_keep_half")
-        result["single_image_latency"] = single_image_latency(torch, md, harness)
-        result["cold_vs_warm"] = cold_vs_warm(torch, pipe)
-        result["variable_length"] = variable_length(torch, md, cfg, pipe)
+    if not args.no_extras:
+        head["cold_vs_warm"] = cold_vs_warm(torch, pipe)
     if not args.no_parity:
         result["parity"] = parity_check(cfg, pipe, harness)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, pipe)
         result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
+    del pipe
+    torch.cuda.empty_cache()
+
+    steps_other = max(20, args.steps // 2)
+    for n in want:
+        if n == HEADLINE:
+            continue
+        if n == 5:
+            blocks[wl.CONFIGS[5].name] = decode_loop_cfg5(torch, md, binding, harness, args.decode_steps)
+            torch.cuda.empty_cache()
+            continue
+        c = wl.CONFIGS[n]
+        p2, blk, _ = measure_workload(torch, md, binding, harness, c, steps_other, args.warmup)
+        if not args.no_extras:
+            blk["cold_vs_warm"] = cold_vs_warm(torch, p2)
+            if n == 2:                                   # the extras that are defined on the batch-16 LLaVA-1.5 shape
+                blk["progressive_prefill"] = progressive_prefill(torch, md, harness, c, p2)
+                blk["variable_length"] = variable_length(torch, md, c, p2)
+                blk["static_handoff"] = static_handoff(torch, md, binding, c)
+                blk["static_handoff_video"] = static_handoff(torch, md, binding, c, B=8, M=2048, kept_vision=1024,
+                                                             reps=5, name="video_8x256_keep_half")
+        blocks[c.name] = blk
+        del p2
+        torch.cuda.empty_cache()
+    result["workloads"] = blocks
     print(json.dumps(result))
 
 

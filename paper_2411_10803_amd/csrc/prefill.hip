@@ -107,6 +107,36 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_buffer(const uint16_t* bas
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)bytes, 0x00020000);
 }
 
+// Vision rows that matter.  Vision tokens arrive with a validity mask; after the vision-encoder stage
+// merged tokens away the valid ones of a sample are a prefix and the rest of its Mv slots is padding.
+// Both sweeps skip the slots behind the last valid one: eff = min(Mv, round_up32(last valid + 1))
+// (0 when no slot is valid).  Any other pattern of invalid slots is still handled key by key.
+// Per-thread part: the largest index this thread saw set among [0, n), or -1.
+__device__ __forceinline__ int last_set_partial(const uint8_t* v, int n, int tid, int nthreads) {
+    int last = -1;
+    const int head = min(n, (int)((16 - ((uintptr_t)v & 15)) & 15));     // bytes before 16-byte alignment
+    if (tid < head && v[tid]) last = tid;
+    const int nvec = (n - head) / 16;
+    const uint4* pv = reinterpret_cast<const uint4*>(v + head);
+    for (int q = tid; q < nvec; q += nthreads) {
+        const uint4 w = pv[q];
+        const int base = head + q * 16;
+        if (w.x) last = base + ((31 - __clz((int)w.x)) >> 3);
+        if (w.y) last = base + 4 + ((31 - __clz((int)w.y)) >> 3);
+        if (w.z) last = base + 8 + ((31 - __clz((int)w.z)) >> 3);
+        if (w.w) last = base + 12 + ((31 - __clz((int)w.w)) >> 3);
+    }
+    for (int j = head + nvec * 16 + tid; j < n; j += nthreads)
+        if (v[j]) last = j;
+    return last;
+}
+__device__ __forceinline__ int wave_max_int(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ int effective_rows(int last, int Mv) { return last < 0 ? 0 : min(Mv, (last + 32) & ~31); }
+
 // Row statistics folded into one constant: a probability of the head mean is
 // exp2(s*scale*log2e + c) with c = -m - log2(Z) - log2(H); text rows beyond txt_len get -inf (-> 0).
 __device__ __forceinline__ float fold_stats(float m, float z, bool row_ok, int H) {
@@ -116,18 +146,27 @@ __device__ __forceinline__ float fold_stats(float m, float z, bool row_ok, int H
 // The 32 text-query rows i0.. of head slice `qb` as MFMA fragments: global -> this wave's LDS tile ->
 // registers.  Rows at or beyond `tl` come out as zero rows.
 template <int KS>
-__device__ __forceinline__ void load_query_frags(const uint16_t* qb, long tok_stride, int d, int i0, int tl, char* tile,
-                                                 int lane, bf16x8 (&qf)[KS]) {
+__device__ __forceinline__ void issue_query_rows(const uint16_t* qb, long tok_stride, int d, int i0, int tl, char* tile, int lane) {
     using T = LdsRows<KS>;
     const __amdgpu_buffer_rsrc_t rq = row_buffer(qb, tl, tok_stride, d);
 #pragma unroll
     for (int t = 0; t < 32 / T::RPL; ++t) T::issue(rq, (uint32_t)(tok_stride * 2), i0, t * T::RPL, tile, lane, true);
+}
+template <int KS>
+__device__ __forceinline__ void read_query_frags(int i0, int tl, const char* tile, int lane, bf16x8 (&qf)[KS]) {
+    using T = LdsRows<KS>;
     MD_VM_WAIT(0);
     T::frags(T::frag_base(tile, lane), qf);
     const bool row_ok = i0 + (lane & 31) < tl;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
         if (!row_ok) qf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+}
+template <int KS>
+__device__ __forceinline__ void load_query_frags(const uint16_t* qb, long tok_stride, int d, int i0, int tl, char* tile,
+                                                 int lane, bf16x8 (&qf)[KS]) {
+    issue_query_rows<KS>(qb, tok_stride, d, i0, tl, tile, lane);
+    read_query_frags<KS>(i0, tl, tile, lane, qf);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -206,7 +245,7 @@ template <int NBW, int KS>
 __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const uint16_t* __restrict__ q_txt, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len, PrefillDims p, float scale_log2e,
-    float2* __restrict__ partial, float* __restrict__ cstat, bf16x8* __restrict__ qfrag)
+    float2* __restrict__ partial, float* __restrict__ cstat, bf16x8* __restrict__ qfrag, int32_t* __restrict__ mv_eff)
 {
     using T = LdsRows<KS>;
     constexpr int TW = 4 / NBW;                       // key tiles per step, one per tile lane
@@ -218,6 +257,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     static_assert(S * SLOT_BYTES >= QBYTES, "the query tiles are staged in the K slots");
     __shared__ __attribute__((aligned(1024))) char s_k[S * SLOT_BYTES];
     __shared__ float s_m[4][32], s_z[4][32];
+    __shared__ int s_last[4];
     const int lane = lane_id(), wv = wave_id();
     const int nbw = wv % NBW, tw = wv / NBW;
     const int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y, b = blockIdx.z;
@@ -230,14 +270,26 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     const __amdgpu_buffer_rsrc_t rk = row_buffer(kb, p.L, p.kv.token, p.d);
     const uint32_t krow = (uint32_t)(p.kv.token * 2);
 
-    const int c0 = ch * p.chunk, c1 = min(c0 + p.chunk, p.L);
-    const int nit = (c1 - c0 + SLOT_ROWS - 1) / SLOT_ROWS;                   // steps of this block
+    // The sweep runs over "effective" key positions e: the Me vision rows that matter (see
+    // effective_rows), then the N text rows; e >= Me is row e + jump of K.  Me is a multiple of 32 (or
+    // Mv itself), so a 32-key tile never straddles the jump.  The chunks cut [0, Me + N) evenly.
+    int Me = p.Mv, jump = 0, c0 = 0, c1 = 0, nit = 0;
+    auto plan = [&]() {
+        jump = p.Mv - Me;
+        const int units = (Me + p.N + 127) / 128, upc = (units + p.nch - 1) / p.nch;
+        c0 = ch * upc * 128;
+        c1 = min(c0 + upc * 128, Me + p.N);
+        nit = c1 > c0 ? (c1 - c0 + SLOT_ROWS - 1) / SLOT_ROWS : 0;         // steps of this block
+    };
     // step g's tiles go to slot (g + S - 1) % S: step 0 into the last slot, which the query staging leaves free
     auto issue_step = [&](int g) {
         char* slot = s_k + ((g + S - 1) % S) * SLOT_BYTES;
         const int row0 = c0 + g * SLOT_ROWS;
 #pragma unroll
-        for (int t = 0; t < NLW; ++t) T::issue(rk, krow, row0, (t * 4 + wv) * T::RPL, slot, lane, true);
+        for (int t = 0; t < NLW; ++t) {
+            const int sr = (t * 4 + wv) * T::RPL;
+            T::issue(rk, krow, row0 + (row0 + sr >= Me ? jump : 0), sr, slot, lane, true);
+        }
     };
     // Validity of this lane's key (lane % 32) in the tiles of the steps g0 .. g0+63, one bit per step.
     // Fetched in batches of 64 steps: a load inside the steady loop would have the compiler wait for
@@ -256,38 +308,54 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         return bits;
     };
 
-    if (EARLY0 && nit > 0) issue_step(0);
+    if (!vb) {
+        plan();
+        if (EARLY0 && nit > 0) issue_step(0);
+    }
+    char* qtile = s_k + wv * 32 * T::ROWB;
+    issue_query_rows<KS>(qb, p.q.token, p.d, i0, tl, qtile, lane);
+    if (vb) {                                         // the mask scan shares the wait with the query rows
+        const int last = wave_max_int(last_set_partial(vb, p.Mv, threadIdx.x, 256));
+        if (lane == 0) s_last[wv] = last;
+    }
     bf16x8 qf[KS];
-    load_query_frags<KS>(qb, p.q.token, p.d, i0, tl, s_k + wv * 32 * T::ROWB, lane, qf);
+    read_query_frags<KS>(i0, tl, qtile, lane, qf);
     if (ch == 0 && tw == 0 && nbg < p.Npad / 32) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[ks];
     }
-    uint64_t visbits = key_valid_bits(0);
     block_sync_lds();                                 // every wave has its query fragments: the slots are free
-    if (!EARLY0 && nit > 0) issue_step(0);
+    if (vb) {
+        Me = effective_rows(max(max(s_last[0], s_last[1]), max(s_last[2], s_last[3])), p.Mv);
+        plan();
+        if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) mv_eff[b] = Me;   // for the second sweep
+    } else if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) {
+        mv_eff[b] = p.Mv;
+    }
+    if ((!EARLY0 || vb) && nit > 0) issue_step(0);
 #pragma unroll
     for (int g = 1; g < S - 1; ++g)
         if (g < nit) issue_step(g);
+    uint64_t visbits = key_valid_bits(0);
 
     float m = -INFINITY, z = 0.f;
     const int i = i0 + (lane & 31);
     // what the arithmetic of a finished tile needs besides its accumulator
     struct Pending { bool all; uint32_t vis; };
     auto visibility = [&](int g) -> Pending {
-        const int j0 = c0 + (g * TW + tw) * 32;
-        const bool v_ok = ((visbits >> (g & 63)) & 1ull) != 0 && j0 + (lane & 31) < p.Mv;
+        const int j0 = c0 + (g * TW + tw) * 32;       // effective position of the tile's first key
+        const bool v_ok = ((visbits >> (g & 63)) & 1ull) != 0 && j0 + (lane & 31) < Me;
         const uint32_t vmask = (uint32_t)__ballot(v_ok);     // the tile's 32 keys (vision keys only)
         Pending pd;
-        pd.all = j0 + 32 <= p.Mv && vmask == 0xFFFFFFFFu;
+        pd.all = j0 + 32 <= Me && vmask == 0xFFFFFFFFu;
         pd.vis = 0xFFFFu;
         if (!pd.all) {
             uint32_t bits = 0;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = tile_row(r, lane), j = j0 + row;
-                const bool vis = j < p.Mv ? ((vmask >> row) & 1u) : (j < c1 && (j - p.Mv) <= i);
+                const bool vis = j < Me ? ((vmask >> row) & 1u) : (j < c1 && (j - Me) <= i);
                 bits |= (vis ? 1u : 0u) << r;
             }
             pd.vis = bits;
@@ -390,15 +458,31 @@ __global__ __launch_bounds__(256) void prefill_cstat_kernel(
 // one wave per (sample, head, 32-row text block).
 template <int KS>
 __global__ __launch_bounds__(256) void prefill_qpack_kernel(
-    const uint16_t* __restrict__ q_txt, const int32_t* __restrict__ txt_len, const float* __restrict__ row_lse, PrefillDims p,
-    bf16x8* __restrict__ qfrag, float* __restrict__ cstat)
+    const uint16_t* __restrict__ q_txt, const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len,
+    const float* __restrict__ row_lse, PrefillDims p, bf16x8* __restrict__ qfrag, float* __restrict__ cstat,
+    int32_t* __restrict__ mv_eff)
 {
     using T = LdsRows<KS>;
     __shared__ __attribute__((aligned(1024))) char s_q[4 * 32 * T::ROWB];
+    __shared__ int s_last[4];
     const int lane = lane_id(), wv = wave_id();
     const int nbt = p.Npad / 32;
+    const long items = (long)p.B * p.H * nbt;
+    const long item_blocks = (items + 3) / 4;
+    if ((long)blockIdx.x >= item_blocks) {            // the last B blocks: the vision rows that matter, per sample
+        const int b = (int)(blockIdx.x - item_blocks);
+        int last = p.Mv - 1;
+        if (vis_valid) {
+            last = wave_max_int(last_set_partial(vis_valid + (long)b * p.Mv, p.Mv, threadIdx.x, 256));
+            if (lane == 0) s_last[wv] = last;
+            __syncthreads();
+            last = max(max(s_last[0], s_last[1]), max(s_last[2], s_last[3]));
+        }
+        if (threadIdx.x == 0) mv_eff[b] = effective_rows(last, p.Mv);
+        return;
+    }
     const long item = (long)blockIdx.x * 4 + wv;
-    if (item >= (long)p.B * p.H * nbt) return;
+    if (item >= items) return;
     const int nbg = (int)(item % nbt), h = (int)(item / nbt % p.H), b = (int)(item / nbt / p.H);
     const int tl = txt_len ? min(max(txt_len[b], 0), p.N) : p.N;
     bf16x8 qf[KS];
@@ -434,10 +518,35 @@ struct ColPlan { int P; long U; int nkg; int Gmax; };
 
 __host__ __device__ __forceinline__ int unit_block(long u, int P, long U) { return (int)(((u + 1) * P - 1) / U); }
 
+// The same decomposition over the key groups that matter (mv_eff, one entry per sample; written by the
+// kernel before this sweep): sample b owns the tiles [tile0(b), tile0(b) + ceil(mv_eff[b] / 128)).
+// Fewer units than the host planned for means fewer blocks at work only where a key group would
+// otherwise be cut into more pieces than the workspace holds (Gmax).
+struct ColRun { long U; int P; int tile0; int nk; };
+__device__ __forceinline__ int key_groups(int rows) { return (rows + kColKeys - 1) / kColKeys; }
+__device__ __forceinline__ ColRun effective_run(const int32_t* __restrict__ mv_eff, int B, int H, ColPlan cp, int bq) {
+    int tiles = 0, tile0 = 0, nk = 0;
+    for (int b = 0; b < B; ++b) {
+        const int n = key_groups(mv_eff[b]);
+        if (b == bq) { tile0 = tiles; nk = n; }
+        tiles += n;
+    }
+    ColRun r;
+    r.U = (long)tiles * H;
+    long P = (long)(cp.Gmax - 1) * tiles;             // pieces per key group <= ceil(H*P/U) + 1 <= Gmax
+    if (cp.Gmax >= H || P > cp.P) P = cp.P;
+    if (P >= 8) P &= ~7L;                             // whole rounds over the 8 XCDs
+    if (P < 1) P = 1;
+    r.P = (int)P;
+    r.tile0 = tile0;
+    r.nk = nk;
+    return r;
+}
+
 template <int NBW, int KT, int KS>
 __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
     const bf16x8* __restrict__ qfrag, const uint16_t* __restrict__ k, const float* __restrict__ cstat,
-    PrefillDims p, ColPlan cp, float scale_log2e, int tgrp, float* __restrict__ apart)
+    const int32_t* __restrict__ mv_eff, PrefillDims p, ColPlan cp, float scale_log2e, int tgrp, float* __restrict__ apart)
 {
     constexpr int TW = 4 / NBW;
     constexpr int KB = 32 * TW * KT;                  // keys per unit (128)
@@ -451,9 +560,12 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
     const int nbw = wv % NBW, tw = wv / NBW;
     // Blocks go round-robin over the 8 XCDs (each with its own L2): the blocks of one XCD take neighbouring
     // runs, so a sample's query fragments are fetched into one or two L2s, not all eight.
-    const int P = cp.P;
+    const ColRun run = effective_run(mv_eff, p.B, p.H, cp, -1);
+    const int P = run.P;
+    const long U = run.U;
+    if ((int)blockIdx.x >= P) return;
     const int pb = (P % 8 == 0) ? (int)(blockIdx.x % 8) * (P / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
-    const long u0 = (long)pb * cp.U / P, u1 = (long)(pb + 1) * cp.U / P;
+    const long u0 = (long)pb * U / P, u1 = (long)(pb + 1) * U / P;
     if (u0 >= u1) return;
     const int nbt = p.Npad / 32;
     const int nbg = tgrp * NBW + nbw;                 // 32-row text block of this wave (may lie beyond the prompt)
@@ -462,22 +574,31 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
     const int i = 32 * nbc + (lane & 31);
     const long tok_stride = p.kv.token;
 
-    // unit u = (tile, head); tile = (sample, key group).  The block walks its run with three cursors (the
-    // unit being worked on, the one whose fragments are requested, the one whose K rows are requested),
-    // each advanced without divisions.
-    struct Unit { int b, kg, h; };
+    // unit u = (tile, head); tile = (sample, key group), counted over the key groups that matter.  The
+    // block walks its run with three cursors (the unit being worked on, the one whose fragments are
+    // requested, the one whose K rows are requested), each advanced without divisions.
+    struct Unit { int b, kg, h, nk, t; };             // nk: key groups of sample b; t: tile index
     auto unit_at = [&](long u) -> Unit {
         Unit x;
-        const int tile = (int)(u / p.H);
-        x.h = (int)(u - (long)tile * p.H);
-        x.b = tile / cp.nkg;
-        x.kg = tile - x.b * cp.nkg;
+        x.t = (int)(u / p.H);
+        x.h = (int)(u - (long)x.t * p.H);
+        int first = 0;
+        x.b = 0; x.kg = 0; x.nk = 1;
+        for (int b = 0; b < p.B; ++b) {
+            const int n = key_groups(mv_eff[b]);
+            if (x.t >= first && x.t < first + n) { x.b = b; x.kg = x.t - first; x.nk = n; }
+            first += n;
+        }
         return x;
     };
     auto advance = [&](Unit& x) {
         if (++x.h == p.H) {
             x.h = 0;
-            if (++x.kg == cp.nkg) { x.kg = 0; ++x.b; }
+            ++x.t;
+            if (++x.kg == x.nk) {
+                x.kg = 0;
+                do { ++x.b; x.nk = x.b < p.B ? key_groups(mv_eff[x.b]) : 1; } while (x.nk == 0);
+            }
         }
     };
     // This wave's share of a unit's K rows: NLW x 1 KiB; rows beyond the last vision key repeat it.
@@ -525,8 +646,7 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
     };
     // the piece of key group (x.b, x.kg) this block holds: apart[piece][b][j][i], text rows contiguous
     auto flush = [&](const Unit& x) {
-        const long tile = (long)x.b * cp.nkg + x.kg;
-        const int piece = pb - unit_block(tile * p.H, P, cp.U);
+        const int piece = pb - unit_block((long)x.t * p.H, P, U);
         if (has_rows) {
             float* ap = apart + (((long)piece * p.B + x.b) * p.Mv) * p.Npad + i;
 #pragma unroll
@@ -601,15 +721,18 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
 // key group, same pieces), lanes over text rows; all loads of a piece are in flight together.
 constexpr int kFixKeys = 4;
 __global__ __launch_bounds__(256) void prefill_colfix_kernel(
-    const float* __restrict__ apart, const uint8_t* __restrict__ vis_valid, PrefillDims p, ColPlan cp,
-    float* __restrict__ Vout, float* __restrict__ Iout)
+    const float* __restrict__ apart, const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ mv_eff,
+    PrefillDims p, ColPlan cp, float* __restrict__ Vout, float* __restrict__ Iout)
 {
     const int lane = lane_id(), wv = wave_id(), b = blockIdx.y;
     const long gstride = (long)p.B * p.Mv * p.Npad;
     const int j0 = (blockIdx.x * 4 + wv) * kFixKeys;
     if (j0 >= p.Mv) return;
-    const long tile = (long)b * cp.nkg + j0 / kColKeys;
-    const int npieces = unit_block(tile * p.H + p.H - 1, cp.P, cp.U) - unit_block(tile * p.H, cp.P, cp.U) + 1;
+    const ColRun run = effective_run(mv_eff, p.B, p.H, cp, b);
+    // keys behind the rows that matter: no pieces were written, their scores are zero
+    const bool skipped = j0 / kColKeys >= run.nk;
+    const long tile = run.tile0 + j0 / kColKeys;
+    const int npieces = skipped ? 0 : unit_block(tile * p.H + p.H - 1, run.P, run.U) - unit_block(tile * p.H, run.P, run.U) + 1;
     float s[kFixKeys], mx[kFixKeys];
 #pragma unroll
     for (int q = 0; q < kFixKeys; ++q) { s[q] = 0.f; mx[q] = 0.f; }
@@ -972,6 +1095,7 @@ __global__ __launch_bounds__(256) void prefill_compact_strided_kernel(
 
 struct PrefillWorkspace {
     float2* partial; float* cstat; bf16x8* qfrag; float* apart; float* V; float* I; float* score; int32_t* src_row;
+    int32_t* mv_eff;
     size_t bytes;
 };
 
@@ -1008,7 +1132,9 @@ ScorePlan plan_scores(int B, int Mv, int N, int H) {
     if (P > kNumCU * s.occ) P = kNumCU * s.occ;
     if (P < 1) P = 1;
     c.P = (int)P;
-    c.Gmax = (int)(((long)H * c.P + c.U - 1) / c.U) + 1;   // pieces a key group can be cut into
+    // pieces a key group can be cut into; sized for half the planned units (samples whose valid vision rows
+    // are a prefix of their slots bring fewer key groups), beyond that fewer blocks work
+    c.Gmax = (int)((2L * H * c.P + c.U - 1) / c.U) + 1;
     if (c.Gmax > H) c.Gmax = H;
     return s;
 }
@@ -1026,6 +1152,7 @@ PrefillWorkspace carve_prefill(void* base, int B, int Mv, int N, int H, int Rcap
     w.I = c.take<float>((size_t)B * Mv);
     w.score = c.take<float>((size_t)B * Mv);
     w.src_row = c.take<int32_t>((size_t)B * (Rcap + N));
+    w.mv_eff = c.take<int32_t>((size_t)B);
     w.bytes = c.off;
     return w;
 }
@@ -1039,7 +1166,7 @@ int launch_scores(const PrefillDims& p, const ScorePlan& s, const PrefillWorkspa
         dim3 g1(p.nch * s.ng, p.H, p.B);
 #define MD_ROWSTATS(NBW_)                                                                                      \
         MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW_, KS>), g1, 256, 0,                    \
-            qp, kp, vis_valid, txt_len, p, scale_log2e, w.partial, w.cstat, w.qfrag)
+            qp, kp, vis_valid, txt_len, p, scale_log2e, w.partial, w.cstat, w.qfrag, w.mv_eff)
         if (s.nbw == 1) MD_ROWSTATS(1);
         else if (s.nbw == 2) MD_ROWSTATS(2);
         else MD_ROWSTATS(4);
@@ -1050,20 +1177,20 @@ int launch_scores(const PrefillDims& p, const ScorePlan& s, const PrefillWorkspa
         }
     } else {
         const long items = (long)p.B * p.H * s.nbt;
-        MD_LAUNCH("prefill_qpack", st, (prefill_qpack_kernel<KS>), (unsigned)((items + 3) / 4), 256, 0, qp, txt_len, row_lse, p,
-                  w.qfrag, w.cstat);
+        MD_LAUNCH("prefill_qpack", st, (prefill_qpack_kernel<KS>), (unsigned)((items + 3) / 4 + p.B), 256, 0, qp, vis_valid, txt_len,
+                  row_lse, p, w.qfrag, w.cstat, w.mv_eff);
     }
     for (int tg = 0; tg < s.ng; ++tg) {
 #define MD_COLSCORE(NBW_, KT_)                                                                                 \
         MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NBW_, KT_, KS>), s.col.P, 256, 0,           \
-            w.qfrag, kp, w.cstat, p, s.col, scale_log2e, tg, w.apart)
+            w.qfrag, kp, w.cstat, w.mv_eff, p, s.col, scale_log2e, tg, w.apart)
         if (s.nbw == 1) MD_COLSCORE(1, 1);
         else if (s.nbw == 2) MD_COLSCORE(2, 2);
         else MD_COLSCORE(4, 4);
 #undef MD_COLSCORE
     }
     const int fx = (p.Mv + 4 * kFixKeys - 1) / (4 * kFixKeys);          // four waves of kFixKeys keys per block
-    MD_LAUNCH("prefill_colfix", st, (prefill_colfix_kernel), dim3(fx, p.B), 256, 0, w.apart, vis_valid, p, s.col, w.V, w.I);
+    MD_LAUNCH("prefill_colfix", st, (prefill_colfix_kernel), dim3(fx, p.B), 256, 0, w.apart, vis_valid, w.mv_eff, p, s.col, w.V, w.I);
     return MD_OK;
 }
 

@@ -77,6 +77,43 @@ def test_ragged_padding_and_odd_shapes():
     assert np.array_equal(g["kept_count"], vis_valid.sum(1))
 
 
+def test_padding_tails_of_different_lengths_are_skipped_not_scored():
+    # After the vision-encoder stage the valid slots of a sample are a prefix and the rest is padding: the
+    # sweeps stop at the last valid slot.  Samples whose last valid slot falls on and off the 32-key and
+    # 128-key boundaries, holes before it, one sample with no valid slot at all, NaN in every invalid row.
+    # Two shapes: 128 text rows with several key chunks, and d = 64 with a vision length off the tile grid.
+    for cfg, lasts in ((wl.tiny(wl.CONFIGS[3], B=6, T=2, H=8, C=256), (1151, 640, 127, 333, 31, None)),
+                       (wl.tiny(wl.CONFIGS[2], B=5, Hg=9, Wg=13, N=45, H=6, d=64, C=264), (116, 95, 64, 0, None))):
+        Mv = cfg.M
+        t = wl.prefill_inputs(cfg)
+        rng = np.random.default_rng(17)
+        vis_valid = np.zeros((cfg.B, Mv), np.uint8)
+        for b, last in enumerate(lasts):
+            if last is None:
+                continue
+            vis_valid[b, :last + 1] = rng.random(last + 1) > (0.0 if b == 0 else 0.25)   # sample 0: a plain prefix
+            vis_valid[b, last] = 1
+        bad = vis_valid == 0
+        t["k"][:, :Mv][bad] = 0x7FC0
+        t["v"][:, :Mv][bad] = 0x7F80
+        t["hidden"][:, :Mv][bad] = 0xFFFF
+        is_key = wl.random_key_mask(cfg, 6, valid=vis_valid)
+        for R in (8, 48):
+            g, o, s = run(t, Mv, R, vis_valid=vis_valid, is_key=is_key)
+            assert np.array_equal(g["kept_count"], np.minimum(np.maximum(R, is_key.sum(1)), vis_valid.sum(1)))
+            assert np.all(g["score_global"][bad] == 0) and np.all(g["score_indiv"][bad] == 0)
+        g, o, s = run(t, Mv, 0, mode=FILTER_THRESHOLD, vis_valid=vis_valid, is_key=is_key, gamma=1.0 / Mv, alpha=1.5 / Mv)
+        assert g["kept_count"][len(lasts) - 1] == 0
+        # the same mask and the caller's row normalisers: one sweep, same selection
+        from paper_2411_10803_amd import harness
+        scale = 1.0 / np.sqrt(cfg.d)
+        o = oracle.prefill_filter(t["q_txt"], t["k"], t["v"], t["hidden"], vis_valid, None, is_key, Mv, scale, FILTER_BUDGET,
+                                  48, 1.0 / Mv, 2.0 / cfg.L, 48)
+        g2 = harness.prefill_on_gpu(t, Mv, vis_valid, None, is_key, scale, FILTER_BUDGET, 48, 1.0 / Mv, 2.0 / cfg.L, 48,
+                                    row_lse=o["row_lse"].astype(np.float32))
+        check_prefill(g2, o, t, Mv, vis_valid, is_key, FILTER_BUDGET, 48, 1.0 / Mv, 2.0 / cfg.L, 48)
+
+
 def test_long_prompts_more_than_128_text_rows():
     # the column scores of a long prompt come from several launches (128 text rows each) that are merged
     cfg = wl.tiny(wl.CONFIGS[2], B=2, Hg=9, Wg=13, N=300, H=4, d=128, C=64)
