@@ -104,24 +104,30 @@ template <> struct Vec<true> {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 6 numerator: logit[b][h][j] = q_cls[b][h] . k_cls[b][j][h] / sqrt(dc), j = 0..M.
-// One wave per kClsRows consecutive key rows of a sample (their loads are in flight together).  A
-// head covers vph = dc/VEC consecutive 16-byte vectors (a power of two), so the per-head sums are
+// Eq. 6, the part that needs no global view.  With x[h][j] = log2(e) * q_cls[b][h] . k_cls[b][j][h] / sqrt(dc),
+// j = 0..M, one wave takes kClsRows consecutive key rows of a sample (their loads are in flight
+// together) and leaves, per head h and for its group g of rows,
+//     part[b][h][g] = (m, z):  m = max of x over the rows that count (the CLS row and the valid tokens),
+//                              z = sum of exp2(x - m) over them,
+//     num[b][h][j]  = exp2(x[h][j] - m)   for each of those rows,
+// so that the decision kernel gets a probability as num * exp2(m - m_h) / Z_h with one factor per
+// (head, group): no exponential per (head, token) on the one CU that decides for a sample.
+// A head covers vph = dc/VEC consecutive 16-byte vectors (a power of two), so the per-head sums are
 // segmented butterflies over vph lanes (or whole-wave sums if vph >= 64).
-constexpr int kClsRows = 4;
+constexpr int kClsRows = 8;
 __host__ __device__ __forceinline__ int cls_groups(int M) { return (M + 1 + kClsRows - 1) / kClsRows; }
 
 template <bool BF>
 __device__ __forceinline__ void cls_logits_rows(
     long item, const void* __restrict__ q_cls, const void* __restrict__ k_cls, const uint8_t* __restrict__ valid,
-    const EncodeDims& p, float* __restrict__ logits)
+    const EncodeDims& p, float* __restrict__ logits, float2* __restrict__ part)
 {
     constexpr int VEC = Vec<BF>::N;
     constexpr int R = kClsRows;
     const int lane = lane_id();
     const int gps = cls_groups(p.M);
     if (item >= (long)p.B * gps) return;
-    const int b = (int)(item / gps), j0 = (int)(item % gps) * R;
+    const int b = (int)(item / gps), g = (int)(item % gps), j0 = g * R;
     // wave-uniform.  Loads are never guarded one by one (a guarded load waits for the one before it):
     // addresses are clamped into the sample instead and what was read for an inactive row is ignored.
     bool act[R];
@@ -144,6 +150,22 @@ __device__ __forceinline__ void cls_logits_rows(
     const int nvec = p.D / VEC, vph = p.dc / VEC;
     const float scale = 1.0f / sqrtf((float)p.dc);
     float* out = logits + (size_t)b * p.Hc * (p.M + 1) + j0;
+    float2* pout = part + (size_t)b * p.Hc * gps + g;
+    // the R logits of one head -> numerators (in place) and their statistics (every lane that holds
+    // them computes the same values)
+    auto finish = [&](float (&lg)[R]) -> float2 {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (act[r]) mx = fmaxf(mx, lg[r] * kLog2eE);
+        float z = 0.f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            lg[r] = act[r] ? fast_exp2(fmaf(lg[r], kLog2eE, -mx)) : 0.f;
+            z += lg[r];
+        }
+        return make_float2(mx, z);
+    };
 
     float acc[R];
 #pragma unroll
@@ -151,37 +173,47 @@ __device__ __forceinline__ void cls_logits_rows(
     const int iters = (nvec + kWave - 1) / kWave;
     for (int it = 0; it < iters; ++it) {
         const int idx = it * kWave + lane;
-        float part[R];
+        float part_r[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) part[r] = 0.f;
-        if (idx < nvec) {
+        for (int r = 0; r < R; ++r) part_r[r] = 0.f;
+        {
+            const int ic = min(idx, nvec - 1);       // lanes beyond the row repeat its last vector and drop it
             float qv[VEC], kv[R][VEC];
-            Vec<BF>::load(qrow, idx * VEC, qv);
+            Vec<BF>::load(qrow, ic * VEC, qv);
 #pragma unroll
-            for (int r = 0; r < R; ++r) Vec<BF>::load(krow[r], idx * VEC, kv[r]);
+            for (int r = 0; r < R; ++r) Vec<BF>::load(krow[r], ic * VEC, kv[r]);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                if (!act[r]) continue;
+                if (!act[r] || idx >= nvec) continue;
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) part[r] = fmaf(qv[e], kv[r][e], part[r]);
+                for (int e = 0; e < VEC; ++e) part_r[r] = fmaf(qv[e], kv[r][e], part_r[r]);
             }
         }
         if (vph < kWave) {
+            float lg[R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (!act[r]) continue;
-                const float tot = group_sum_rt(part[r], vph);
-                if (idx < nvec && (lane & (vph - 1)) == 0) out[(size_t)(idx / vph) * (p.M + 1) + r] = tot * scale;
+            for (int r = 0; r < R; ++r) lg[r] = group_sum_rt(part_r[r], vph) * scale;
+            if (idx < nvec && (lane & (vph - 1)) == 0) {
+                const int h = idx / vph;
+                pout[(size_t)h * gps] = finish(lg);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    if (act[r]) out[(size_t)h * (p.M + 1) + r] = lg[r];
             }
         } else {
             const int per_head = vph / kWave;                 // iterations per head
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                acc[r] += part[r];
-                if ((it + 1) % per_head == 0) {
-                    const float tot = wave_sum(acc[r]);
-                    if (act[r] && lane == 0) out[(size_t)(it / per_head) * (p.M + 1) + r] = tot * scale;
-                    acc[r] = 0.f;
+            for (int r = 0; r < R; ++r) acc[r] += part_r[r];
+            if ((it + 1) % per_head == 0) {
+                float lg[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) { lg[r] = wave_sum(acc[r]) * scale; acc[r] = 0.f; }
+                if (lane == 0) {
+                    const int h = it / per_head;
+                    pout[(size_t)h * gps] = finish(lg);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        if (act[r]) out[(size_t)h * (p.M + 1) + r] = lg[r];
                 }
             }
         }
@@ -286,20 +318,21 @@ __device__ __forceinline__ void window_sim_item(
 template <int WSM, bool XBF, bool QKBF>
 __global__ __launch_bounds__(256) void encode_scores_kernel(
     const void* __restrict__ x, const void* __restrict__ q_cls, const void* __restrict__ k_cls,
-    const uint8_t* __restrict__ valid, EncodeDims p, int with_cls, float* __restrict__ sim, float* __restrict__ logits)
+    const uint8_t* __restrict__ valid, EncodeDims p, int with_cls, float* __restrict__ sim, float* __restrict__ logits,
+    float2* __restrict__ cls_part)
 {
     const long item = (long)blockIdx.x * (blockDim.x >> 6) + wave_id();
     const long n_win = (long)p.B * p.W;
     if (item < n_win) window_sim_item<WSM, XBF>(item, x, valid, p, sim);
-    else if (with_cls) cls_logits_rows<QKBF>(item - n_win, q_cls, k_cls, valid, p, logits);
+    else if (with_cls) cls_logits_rows<QKBF>(item - n_win, q_cls, k_cls, valid, p, logits, cls_part);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Per-sample decisions.  One block per sample.
 __global__ __launch_bounds__(1024) void encode_decide_kernel(
     EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
-    const float* __restrict__ logits, const float* __restrict__ sim, float tau, int key_budget,
-    int key_adaptive, float key_lambda, int32_t* __restrict__ key_count,
+    const float* __restrict__ logits, const float2* __restrict__ cls_part, const float* __restrict__ sim, float tau,
+    int key_budget, int key_adaptive, float key_lambda, int32_t* __restrict__ key_count,
     float* __restrict__ acls, uint8_t* __restrict__ iskey, uint8_t* __restrict__ wmerged,
     int32_t* __restrict__ dstpos,
     int32_t* __restrict__ out_index, float* __restrict__ out_mass, uint8_t* __restrict__ out_is_key,
@@ -321,16 +354,19 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
 
     // ---- Key Retaining
     if (key_budget > 0 || key_adaptive) {
-        const float* lg = logits + (size_t)b * p.Hc * (M + 1);
+        const float* lg = logits + (size_t)b * p.Hc * (M + 1);       // numerators, see cls_logits_rows
+        const int gps = cls_groups(M);
+        const float2* pb = cls_part + (size_t)b * p.Hc * gps;
         for (int h = wv; h < p.Hc; h += nw) {
-            const float* l = lg + (size_t)h * (M + 1);
+            const float2* pp = pb + (size_t)h * gps;
             float mx = -INFINITY;
-            for (int j = lane; j <= M; j += kWave)
-                if (j == 0 || !vb || vb[j - 1]) mx = fmaxf(mx, l[j]);
+            for (int g = lane; g < gps; g += kWave) mx = fmaxf(mx, pp[g].x);
             mx = wave_max(mx);
             float z = 0.f;
-            for (int j = lane; j <= M; j += kWave)
-                if (j == 0 || !vb || vb[j - 1]) z += fast_exp2(kLog2eE * (l[j] - mx));
+            for (int g = lane; g < gps; g += kWave) {
+                const float2 v = pp[g];
+                if (v.x > -INFINITY) z = fmaf(v.y, fast_exp2(v.x - mx), z);
+            }
             z = wave_sum(z);
             if (lane == 0) { s_max[h] = mx; s_inv[h] = 1.0f / (z * (float)p.Hc); }
         }
@@ -339,7 +375,9 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
             float a = -INFINITY;
             if (!vb || vb[j]) {
                 a = 0.f;
-                for (int h = 0; h < p.Hc; ++h) a += fast_exp2(kLog2eE * (lg[(size_t)h * (M + 1) + j + 1] - s_max[h])) * s_inv[h];
+                const int g = (j + 1) / kClsRows;
+                for (int h = 0; h < p.Hc; ++h)
+                    a = fmaf(lg[(size_t)h * (M + 1) + j + 1], fast_exp2(pb[(size_t)h * gps + g].x - s_max[h]) * s_inv[h], a);
             }
             acls_b[j] = a;
             if (a_cls_out) a_cls_out[(size_t)b * M + j] = a;
@@ -445,25 +483,40 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same decisions for M <= 1024*IPT with a sample's tokens in registers (thread t owns tokens
-// t, t+1024, ...): loads are issued in batches, the radix passes and prefix sums touch no memory,
-// key and merge flags are shared through LDS.
+// The same decisions for M <= 1024*IPT with a sample's tokens in registers (thread t owns the IPT
+// consecutive tokens t*IPT ..): the kernel is a chain of dependent steps on one CU per sample, so it
+// is built to be short rather than wide.
+//   - the softmax denominators come from the per-wave statistics the score kernel left (a few
+//     hundred pairs per head), while the own tokens' logits are already on their way;
+//   - the top-k radix select starts below the bits that all scores share;
+//   - key ranks and survivor ranks come from ONE block scan of a packed pair of counts.
+#ifdef MD_DECIDE_TICKS
+#define MD_DTICK(k) do { if (threadIdx.x == 0 && blockIdx.x == 0) ticks[k] = __builtin_readcyclecounter(); } while (0)
+#else
+#define MD_DTICK(k) do { } while (0)
+#endif
 template <int IPT>
 __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
-    const float* __restrict__ logits, const float* __restrict__ sim, float tau, int key_budget,
-    int key_adaptive, float key_lambda, int32_t* __restrict__ key_count,
+    const float* __restrict__ logits, const float2* __restrict__ cls_part, const float* __restrict__ sim,
+    float tau, int key_budget, int key_adaptive, float key_lambda, int32_t* __restrict__ key_count,
     uint8_t* __restrict__ wmerged, int32_t* __restrict__ dstpos,
     int32_t* __restrict__ out_index, float* __restrict__ out_mass, uint8_t* __restrict__ out_is_key,
     uint8_t* __restrict__ out_valid, int32_t* __restrict__ out_count, int32_t* __restrict__ key_index,
     float* __restrict__ a_cls_out, float* __restrict__ window_sim_out)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];   // [M] merged-window mass (float), [M] key flags, [M] token state
-    __shared__ float s_max[kMaxClsHeads], s_inv[kMaxClsHeads];
+    // [M] merged-window mass / scores (float), then [M] key flags and [M] token states, which take the place of
+    // the [groups][16] factors of Eq. 6 (see decide_fast_lds_bytes)
+    extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
     __shared__ int s_hist[256];
     __shared__ int s_red[16];
+    __shared__ uint32_t s_lo[16], s_hi[16];
     __shared__ float s_redf[16];
     __shared__ int s_moff[kMaxWindow];               // member_offset(m): integer divisions done once per block
+#ifdef MD_DECIDE_TICKS
+    __shared__ long long ticks[8];
+#endif
+    MD_DTICK(0);
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
     const int M = p.M, W = p.W;
     if (tid < p.ws) s_moff[tid] = member_offset(p, tid);    // read after later barriers
@@ -472,114 +525,135 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     uint8_t* s_state = s_key + M;                    // 0: not in a merged window, 1: first valid member, 2: merged away
     const uint8_t* vb = valid ? valid + (size_t)b * M : nullptr;
     const float* mb = mass_in ? mass_in + (size_t)b * M : nullptr;
+    const int j0 = tid * IPT;                        // first own token (and first own window)
+    const bool with_keys = key_budget > 0 || key_adaptive;
+    const float* lg = logits + (size_t)b * p.Hc * (M + 1);
 
-    // own tokens' state and own windows' similarity: requested first
-    // (clamped addresses, no guarded loads: a guarded load would wait for the one before it)
+    // ---- everything that depends on nothing is requested first (clamped or range-checked addresses, no
+    // guarded loads: a guarded load would wait for the one before it)
+    // Eq. 6: wave h owns head h (Hc <= 16 = waves of the block; waves beyond Hc contribute zeros).  Its
+    // lanes take the head's per-group statistics (group = kClsRows rows, see cls_logits_rows).
+    constexpr int PRE = 16;                          // heads
+    constexpr int NPB = 2 * IPT + 1;                 // groups per lane: 64 * NPB >= cls_groups(1024 * IPT)
+    constexpr int PT = IPT < 4 ? IPT : 4;            // tokens per batch of numerators
+    constexpr bool EARLY = IPT <= 4;                 // registers allow the first batch to be requested up front
+    const int gps = cls_groups(M);
+    float2 pv[NPB];
+    if (with_keys) {
+        const float2* pp = cls_part + ((size_t)b * p.Hc + min(wv, p.Hc - 1)) * gps;
+#pragma unroll
+        for (int u = 0; u < NPB; ++u) pv[u] = pp[min(lane + u * kWave, gps - 1)];
+    }
+    // numerators of the tokens tid + 1024*t, all heads: one buffer load each (the token's offset in a
+    // vector register, the head's in a scalar one; tokens beyond M repeat the last one and are dropped).
+    // The scores change hands through LDS afterwards.
+    const __amdgpu_buffer_rsrc_t rnum =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lg + 1), 0, (max(p.Hc, 1) * (M + 1) - 1) * 4, 0x00020000);
+    float xl[PT][PRE];
+    auto request_numerators = [&](int t0) {
+#pragma unroll
+        for (int t = 0; t < PT; ++t) {
+            const int voff = min(tid + 1024 * (t0 + t), M - 1) * 4;
+#pragma unroll
+            for (int u = 0; u < PRE; ++u)
+                xl[t][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                    rnum, voff, min(u, p.Hc - 1) * (M + 1) * 4, 0));
+        }
+    };
     bool ok[IPT];
     float mass[IPT], simv[IPT];
     {
         uint32_t vbyte[IPT];
 #pragma unroll
-        for (int t = 0; t < IPT; ++t) vbyte[t] = vb ? vb[min(tid + t * 1024, M - 1)] : 1u;
+        for (int t = 0; t < IPT; ++t) vbyte[t] = vb ? vb[min(j0 + t, M - 1)] : 1u;
 #pragma unroll
-        for (int t = 0; t < IPT; ++t) mass[t] = mb ? mb[min(tid + t * 1024, M - 1)] : 1.0f;
+        for (int t = 0; t < IPT; ++t) mass[t] = mb ? mb[min(j0 + t, M - 1)] : 1.0f;
 #pragma unroll
-        for (int t = 0; t < IPT; ++t) simv[t] = sim[(size_t)b * W + min(tid + t * 1024, W - 1)];
+        for (int t = 0; t < IPT; ++t) simv[t] = sim[(size_t)b * W + min(tid + 1024 * t, W - 1)];
+        if (EARLY && with_keys) request_numerators(0);
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
-            const int j = tid + t * 1024;
+            const int j = j0 + t;
             ok[t] = j < M && vbyte[t] != 0;
             if (j >= M) mass[t] = 1.0f;
-            if (j >= W) simv[t] = 0.f;
         }
     }
     bool sel[IPT];
 #pragma unroll
     for (int t = 0; t < IPT; ++t) sel[t] = false;
 
-    if (key_budget > 0 || key_adaptive) {
-        const float* lg = logits + (size_t)b * p.Hc * (M + 1);
-        // one token per thread and few heads: the own token's logits are requested before the
-        // denominators are computed, so that the two passes over the logits cost one round trip
-        constexpr int PRE = 16;
-        const bool pre = IPT == 1 && p.Hc <= PRE;    // block-uniform
-        float xl[PRE];
-        if (pre) {
+    if (with_keys) {
+        // head statistics (m_h, Z_h) and the factor of every group: f[g][h] = exp2(m_g - m_h) / (Z_h * Hc)
+        float* s_f = reinterpret_cast<float*>(s_dyn + ((4 * (size_t)M + 15) & ~(size_t)15));   // [gps][PRE], gone before the key flags are written
+        {
+            float mx = -INFINITY;
 #pragma unroll
-            for (int u = 0; u < PRE; ++u) xl[u] = (u < p.Hc && tid < M) ? lg[(size_t)u * (M + 1) + tid + 1] : 0.f;
-        }
-        // Eq. 6 denominators: one wave per head, (max, sum) in the log2 domain, 16 loads in flight
-        for (int h = wv; h < p.Hc; h += nw) {
-            const float* l = lg + (size_t)h * (M + 1);
-            float mx = -INFINITY, z = 0.f;
-            for (int j0 = lane; j0 <= M; j0 += 16 * kWave) {
-                // all 16 logits (and validity bytes) are requested before any is used: clamped
-                // addresses instead of guarded loads, which would each wait for the one before
-                float x[16];
-                uint32_t vv[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) x[u] = l[min(j0 + u * kWave, M)];
-                if (vb) {
-#pragma unroll
-                    for (int u = 0; u < 16; ++u) vv[u] = vb[min(max(j0 + u * kWave - 1, 0), M - 1)];
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 16; ++u) vv[u] = 1u;
-                }
-                float bm = -INFINITY;
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int j = j0 + u * kWave;
-                    x[u] = (j <= M && (j == 0 || vv[u] != 0)) ? x[u] * kLog2eE : -INFINITY;
-                    bm = fmaxf(bm, x[u]);
-                }
-                const float mn = fmaxf(mx, bm);
-                if (mn > -INFINITY) {
-                    float sacc = 0.f;
-#pragma unroll
-                    for (int u = 0; u < 16; ++u) sacc += fast_exp2(x[u] - mn);
-                    z = z * fast_exp2(mx - mn) + sacc;
-                }
-                mx = mn;
+            for (int u = 0; u < NPB; ++u) {
+                if (lane + u * kWave >= gps) pv[u] = make_float2(-INFINITY, 0.f);
+                mx = fmaxf(mx, pv[u].x);
             }
             const float gm = wave_max(mx);
-            const float zs = wave_sum(gm > -INFINITY ? z * fast_exp2(mx - gm) : 0.f);
-            if (lane == 0) { s_max[h] = gm; s_inv[h] = 1.0f / (zs * (float)p.Hc); }
+            float z = 0.f;
+#pragma unroll
+            for (int u = 0; u < NPB; ++u) {
+                pv[u].x = fast_exp2(pv[u].x - gm);   // (gm is finite: the CLS row always counts)
+                z = fmaf(pv[u].y, pv[u].x, z);
+            }
+            const float inv = wv < p.Hc ? 1.0f / (wave_sum(z) * (float)p.Hc) : 0.f;
+#pragma unroll
+            for (int u = 0; u < NPB; ++u)
+                if (lane + u * kWave < gps) s_f[(lane + u * kWave) * PRE + wv] = pv[u].x * inv;
+        }
+        if (!EARLY) request_numerators(0);
+        __syncthreads();
+        MD_DTICK(1);
+        // a_cls (head mean of the probabilities) of the tokens tid + 1024*t
+        float* s_a = s_tmass;                        // free until the merge decisions
+#pragma unroll
+        for (int t0 = 0; t0 < IPT; t0 += PT) {
+            if (t0 > 0) request_numerators(t0);
+#pragma unroll
+            for (int t = 0; t < PT; ++t) {
+                const int j = tid + 1024 * (t0 + t);
+                const f32x4* fr = reinterpret_cast<const f32x4*>(s_f + (size_t)(min(j, M - 1) + 1) / kClsRows * PRE);
+                float a = 0.f;
+#pragma unroll
+                for (int q = 0; q < PRE / 4; ++q) {
+                    const f32x4 f = fr[q];
+                    a = fmaf(xl[t][4 * q], f.x, a);
+                    a = fmaf(xl[t][4 * q + 1], f.y, a);
+                    a = fmaf(xl[t][4 * q + 2], f.z, a);
+                    a = fmaf(xl[t][4 * q + 3], f.w, a);
+                }
+                if (j < M) s_a[j] = a;
+            }
         }
         __syncthreads();
-        // a_cls of the own tokens (head mean of the probabilities), eight loads in flight
+        MD_DTICK(2);
         uint64_t rk[IPT];
+        float av[IPT];
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
-            const int j = tid + t * 1024;
-            float a = -INFINITY;
-            if (pre) {
-                if (ok[t]) {
-                    a = 0.f;
-#pragma unroll
-                    for (int u = 0; u < PRE; ++u)
-                        if (u < p.Hc) a += fast_exp2(fmaf(xl[u], kLog2eE, -s_max[u])) * s_inv[u];
-                }
-            } else {
-                // unguarded loads at a clamped token, eight heads in flight; the sum of a token that is
-                // not there is dropped afterwards
-                const int jc = min(j, M - 1);
-                float acc = 0.f;
-                for (int h0 = 0; h0 < p.Hc; h0 += 8) {
-                    float x[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) x[u] = lg[(size_t)min(h0 + u, p.Hc - 1) * (M + 1) + jc + 1];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (h0 + u < p.Hc) acc += fast_exp2(fmaf(x[u], kLog2eE, -s_max[h0 + u])) * s_inv[h0 + u];
-                }
-                if (ok[t]) a = acc;
-            }
+            const int j = j0 + t;
+            av[t] = s_a[min(j, M - 1)];
+            const float a = ok[t] ? av[t] : -INFINITY;
             if (j < M && a_cls_out) a_cls_out[(size_t)b * M + j] = a;
             rk[t] = ok[t] ? rank_key(a, j) : 0ull;
         }
         if (!key_adaptive) {                         // Eq. 7, budget form: the key_budget largest scores
-            const SelectBound sb = block_radix_select_reg<IPT>(rk, key_budget, s_hist);
+            // the scores' bit patterns share their leading bits: start the radix passes below them
+            uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+            for (int t = 0; t < IPT; ++t)
+                if (rk[t] != 0) { lo = min(lo, (uint32_t)(rk[t] >> 32)); hi = max(hi, (uint32_t)(rk[t] >> 32)); }
+            lo = wave_min_u32(lo);
+            hi = ~wave_min_u32(~hi);
+            if (lane == 0) { s_lo[wv] = lo; s_hi[wv] = hi; }
+            __syncthreads();
+            lo = wave_min_u32(lane < nw ? s_lo[lane] : 0xFFFFFFFFu);
+            hi = ~wave_min_u32(lane < nw ? ~s_hi[lane] : 0xFFFFFFFFu);
+            const int common = lo <= hi ? (lo == hi ? 32 : __clz((int)(lo ^ hi))) : 0;     // leading bits all present keys share
+            const SelectBound sb = block_radix_select_reg<IPT>(rk, key_budget, s_hist, common, (uint64_t)hi << 32);
 #pragma unroll
             for (int t = 0; t < IPT; ++t) sel[t] = rk[t] != 0 && (rk[t] >> sb.shift) >= sb.bound;
         } else {                                     // Eq. 7 as printed: a_cls > mu, mu = mean + lambda * std
@@ -587,47 +661,37 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
             int cnt = 0;
 #pragma unroll
             for (int t = 0; t < IPT; ++t)
-                if (ok[t]) { s1 += __uint_as_float((uint32_t)(rk[t] >> 32)); ++cnt; }
+                if (ok[t]) { s1 += av[t]; ++cnt; }
             s1 = block_sum(s1, s_redf);
             cnt = block_sum_i(cnt, s_red);
             const float mean = cnt > 0 ? s1 / (float)cnt : 0.f;
             float s2 = 0.f;
 #pragma unroll
             for (int t = 0; t < IPT; ++t)
-                if (ok[t]) { const float dlt = __uint_as_float((uint32_t)(rk[t] >> 32)) - mean; s2 = fmaf(dlt, dlt, s2); }
+                if (ok[t]) { const float dlt = av[t] - mean; s2 = fmaf(dlt, dlt, s2); }
             s2 = block_sum(s2, s_redf);
             const float mu = mean + key_lambda * sqrtf(cnt > 0 ? s2 / (float)cnt : 0.f);
 #pragma unroll
-            for (int t = 0; t < IPT; ++t) sel[t] = ok[t] && __uint_as_float((uint32_t)(rk[t] >> 32)) > mu;
+            for (int t = 0; t < IPT; ++t) sel[t] = ok[t] && av[t] > mu;
         }
-        int running = 0;                             // keys so far; key_budget is the capacity of key_index
+    } else if (a_cls_out) {
 #pragma unroll
-        for (int t = 0; t < IPT; ++t) {
-            if (t * 1024 >= M) continue;             // block-uniform
-            const int j = tid + t * 1024;
-            if (j < M) { s_key[j] = sel[t]; s_state[j] = 0; }
-            int total;
-            const int r = block_rank(sel[t], s_red, total);
-            if (sel[t] && running + r < key_budget) key_index[(size_t)b * key_budget + running + r] = j;
-            running += total;
-        }
-        for (int r = running + tid; r < key_budget; r += blockDim.x) key_index[(size_t)b * key_budget + r] = -1;
-        if (key_count && tid == 0) key_count[b] = running;
-    } else {
-#pragma unroll
-        for (int t = 0; t < IPT; ++t) {
-            const int j = tid + t * 1024;
-            if (j < M) { s_key[j] = 0; s_state[j] = 0; if (a_cls_out) a_cls_out[(size_t)b * M + j] = 0.f; }
-        }
+        for (int t = 0; t < IPT; ++t)
+            if (j0 + t < M) a_cls_out[(size_t)b * M + j0 + t] = 0.f;
     }
+    MD_DTICK(3);
+#pragma unroll
+    for (int t = 0; t < IPT; ++t)
+        if (j0 + t < M) { s_key[j0 + t] = sel[t]; s_state[j0 + t] = 0; }
     __syncthreads();
+    MD_DTICK(4);
 
     // ---- merge decision per window: S > tau, >= 2 valid members, no key member.  The window's thread
     // leaves each member's fate (and the merged mass at the first valid member) in LDS, so that the
-    // per-token pass below needs no index arithmetic (the states were cleared with the key flags).
+    // per-token pass below needs no index arithmetic.
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-        const int w = tid + t * 1024;
+        const int w = tid + 1024 * t;                // windows go round the threads: there are fewer than tokens
         if (w >= W) continue;
         int n = 0, first = -1;
         bool has_key = false;
@@ -674,35 +738,60 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
         if (window_sim_out) window_sim_out[(size_t)b * W + w] = simv[t];
     }
     __syncthreads();
+    MD_DTICK(5);
 
-    // ---- survivors in ascending token index: prefix sum of the survivor flags, one round per 1024 tokens
-    int running = 0;
+    // ---- keys and survivors in ascending token index: one block scan of (keys << 16 | survivors) per thread
+    bool surv[IPT], merged[IPT];
+    int packed = 0;
 #pragma unroll
     for (int t = 0; t < IPT; ++t) {
-        if (t * 1024 >= M) continue;                 // block-uniform
-        const int j = tid + t * 1024;
-        bool surv = false, merged = false;
-        float ms = 0.f;
+        surv[t] = false; merged[t] = false;
         if (ok[t]) {
-            const int stt = s_state[j];
-            merged = stt != 0;
-            surv = stt != 2;
-            ms = stt == 1 ? s_tmass[j] : mass[t];
+            const int stt = s_state[j0 + t];
+            merged[t] = stt != 0;
+            surv[t] = stt != 2;
+            if (stt == 1) mass[t] = s_tmass[j0 + t];
         }
-        int total;
-        const int r = block_rank(surv, s_red, total);
-        if (j < M) dstpos[(size_t)b * M + j] = surv ? running + r : -1;
-        if (surv) {
-            const size_t o = (size_t)b * M + running + r;
-            out_index[o] = j;
-            out_mass[o] = ms;
-            out_is_key[o] = merged ? 0 : (sel[t] ? 1 : 0);
-        }
-        running += total;
+        packed += (sel[t] ? 0x10000 : 0) + (surv[t] ? 1 : 0);
     }
-    if (tid == 0) out_count[b] = running;
+    const int incl = wave_incl_scan_i(packed);
+    if (lane == kWave - 1) s_red[wv] = incl;
+    __syncthreads();
+    MD_DTICK(6);
+    int total;
+    int excl = wave_prefix_of_totals(s_red, total) + incl - packed;
+    int kpos = excl >> 16, spos = excl & 0xFFFF;
+    const int nkeys = total >> 16, nsurv = total & 0xFFFF;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t) {
+        const int j = j0 + t;
+        if (sel[t]) {
+            if (kpos < key_budget) key_index[(size_t)b * key_budget + kpos] = j;
+            ++kpos;
+        }
+        if (j < M) dstpos[(size_t)b * M + j] = surv[t] ? spos : -1;
+        if (surv[t]) {
+            const size_t o = (size_t)b * M + spos;
+            out_index[o] = j;
+            out_mass[o] = mass[t];
+            out_is_key[o] = merged[t] ? 0 : (sel[t] ? 1 : 0);
+            ++spos;
+        }
+    }
+    if (with_keys) {
+        for (int r = nkeys + tid; r < key_budget; r += blockDim.x) key_index[(size_t)b * key_budget + r] = -1;
+        if (key_count && tid == 0) key_count[b] = nkeys;
+    }
+    if (tid == 0) out_count[b] = nsurv;
     if (out_valid)
-        for (int s2 = tid; s2 < M; s2 += blockDim.x) out_valid[(size_t)b * M + s2] = s2 < running;
+        for (int s2 = tid; s2 < M; s2 += blockDim.x) out_valid[(size_t)b * M + s2] = s2 < nsurv;
+#ifdef MD_DECIDE_TICKS
+    MD_DTICK(7);
+    if (threadIdx.x == 0 && blockIdx.x == 0)
+        printf("decide ticks: denom %lld acls %lld select %lld keyflags %lld windows %lld scan %lld writes %lld total %lld\n",
+               ticks[1] - ticks[0], ticks[2] - ticks[1], ticks[3] - ticks[2], ticks[4] - ticks[3], ticks[5] - ticks[4],
+               ticks[6] - ticks[5], ticks[7] - ticks[6], ticks[7] - ticks[0]);
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -794,7 +883,7 @@ __global__ __launch_bounds__(256) void encode_emit_kernel(
 }
 
 struct EncodeWorkspace {
-    float* logits; float* acls; float* sim; uint8_t* iskey; uint8_t* wmerged; int32_t* dstpos;
+    float* logits; float2* cls_part; float* acls; float* sim; uint8_t* iskey; uint8_t* wmerged; int32_t* dstpos;
     size_t bytes;
 };
 
@@ -802,6 +891,7 @@ EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
     Carver c(base);
     EncodeWorkspace ws;
     ws.logits = c.take<float>((size_t)B * (Hc > 0 ? Hc : 1) * (M + 1));
+    ws.cls_part = c.take<float2>((size_t)B * (Hc > 0 ? Hc : 1) * cls_groups(M));
     ws.acls = c.take<float>((size_t)B * M);
     ws.sim = c.take<float>((size_t)B * W);
     ws.iskey = c.take<uint8_t>((size_t)B * M);
@@ -811,13 +901,28 @@ EncodeWorkspace carve_encode(void* base, int B, int M, int W, int Hc) {
     return ws;
 }
 
+// Dynamic LDS of the fast decision kernel: [M] floats, then the larger of ([M] + [M] flag bytes) and the
+// [groups][16] factors (16-byte aligned).
+size_t decide_fast_lds_bytes(int M) {
+    const size_t head = (4 * (size_t)M + 15) & ~(size_t)15;
+    const size_t factors = (size_t)cls_groups(M) * 16 * 4, flags = 2 * (size_t)M + 16;
+    return head + (factors > flags ? factors : flags);
+}
+// More than 64 KiB of dynamic LDS has to be asked for (only the 8-tokens-per-thread form needs it).
+bool decide_fast_lds_ready(int M, size_t bytes) {
+    if (bytes <= 64 * 1024) return true;
+    if (M <= 4096) return false;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_decide_fast_kernel<8>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+}
+
 template <int WSM>
 void launch_scores(dim3 grid, hipStream_t st, bool xbf, bool qkbf, const void* x, const void* q_cls, const void* k_cls,
-                   const uint8_t* valid, const EncodeDims& p, int with_cls, float* sim, float* logits) {
-    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
-    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
-    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
-    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits);
+                   const uint8_t* valid, const EncodeDims& p, int with_cls, float* sim, float* logits, float2* cls_part) {
+    if (xbf && qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, true>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits, cls_part);
+    else if (xbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, true, false>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits, cls_part);
+    else if (qkbf) MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, true>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits, cls_part);
+    else MD_LAUNCH("encode_scores", st, (encode_scores_kernel<WSM, false, false>), grid, 64 * kEncWaves, 0, x, q_cls, k_cls, valid, p, with_cls, sim, logits, cls_part);
 }
 
 }  // namespace
@@ -900,23 +1005,25 @@ int encode_merge_impl(
     dim3 sgrid((unsigned)((items + kEncWaves - 1) / kEncWaves));
     const bool xbf = x_dtype == MD_BF16, qkbf = qk_dtype == MD_BF16;
     const int with_cls = with_keys;
-    if (ws <= 2) launch_scores<2>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
-    else if (ws <= 4) launch_scores<4>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
-    else if (ws <= 8) launch_scores<8>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
-    else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits);
+    if (ws <= 2) launch_scores<2>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits, wsp.cls_part);
+    else if (ws <= 4) launch_scores<4>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits, wsp.cls_part);
+    else if (ws <= 8) launch_scores<8>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits, wsp.cls_part);
+    else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits, wsp.cls_part);
     dim3 wgrid((unsigned)(((long)B * W + kEncWaves - 1) / kEncWaves));
+    const size_t dlds = decide_fast_lds_bytes(M);
+    const bool fast_ok = M <= 8192 && (!with_keys || Hc <= 16) && decide_fast_lds_ready(M, dlds);
 #define MD_DECIDE_FAST(IPT_)                                                                                  \
-    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_>), B, 1024, 6 * (size_t)M,              \
-        p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,              \
+    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_>), B, 1024, dlds,                       \
+        p, valid, mass_in, wsp.logits, wsp.cls_part, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,  \
         wsp.wmerged, wsp.dstpos,                                                                                   \
         out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)
-    if (M <= 1024) MD_DECIDE_FAST(1);
-    else if (M <= 2048) MD_DECIDE_FAST(2);
-    else if (M <= 4096) MD_DECIDE_FAST(4);
-    else if (M <= 8192) MD_DECIDE_FAST(8);
+    if (fast_ok && M <= 1024) MD_DECIDE_FAST(1);
+    else if (fast_ok && M <= 2048) MD_DECIDE_FAST(2);
+    else if (fast_ok && M <= 4096) MD_DECIDE_FAST(4);
+    else if (fast_ok) MD_DECIDE_FAST(8);
     else
         MD_LAUNCH("encode_decide", st, (encode_decide_kernel), B, 1024, 0,
-            p, valid, mass_in, wsp.logits, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,
+            p, valid, mass_in, wsp.logits, wsp.cls_part, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,
             wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
             out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out);
 #undef MD_DECIDE_FAST

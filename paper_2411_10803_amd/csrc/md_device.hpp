@@ -222,17 +222,19 @@ __device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int 
 // as long as the tie value is below 2^31 - 1): no memory traffic inside the passes.  The wave that
 // scans the histogram also clears it, so a pass costs two barriers.
 template <int IPT>
-__device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&key)[IPT], int k, int* hist) {
+__device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&key)[IPT], int k, int* hist,
+                                                               int skip = 0, uint64_t top = 0ull) {
     __shared__ int s_digit, s_k, s_done;
     if (k <= 0) return SelectBound{~0ull, 0};               // nothing selected
     const int lane = lane_id();
     __syncthreads();                                        // earlier readers of the shared words are done
     for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
     __syncthreads();
-    int sh = 56, shift = 64;
-    uint64_t prefix = 0ull;
+    // `skip` leading bits (0..56) are the same in every present key (those of `top`): the passes start below them
+    int sh = 56 - skip, shift = 64 - skip;
+    uint64_t prefix = skip > 0 ? top >> shift : 0ull;
     int kk = k;
-    bool first = true;
+    bool first = skip == 0;
     for (;;) {
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
