@@ -198,9 +198,10 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
     float* s_at = reinterpret_cast<float*>(s_holes + p.Lcap);
     __shared__ float s_cm[1024], s_cz[1024];         // per head: max (log2 domain), 1 / (Z * H)
     __shared__ int s_red[16];
-    __shared__ int s_hist[256];
+    __shared__ int s_hist[kSelectHistInts];
     __shared__ uint64_t s_red64[16];
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id();
+    if (tid < 256) s_hist[tid] = 0;                  // for block_select_topk, after later barriers
     const int H = p.H;
     const float* lb = logits + (long)b * p.Lcap * H;
     float* ab = acc + (long)b * p.Lcap;
@@ -363,7 +364,7 @@ __global__ __launch_bounds__(1024) void decode_select_fast_kernel(
         return;
     }
 
-    const SelectBound sb = block_radix_select_reg<IPT>(key, extra, s_hist);
+    const SelectBound sb = block_select_topk<IPT>(key, extra, s_hist);
     bool keep[IPT];
 #pragma unroll
     for (int t = 0; t < IPT; ++t)

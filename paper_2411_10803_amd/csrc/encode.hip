@@ -17,7 +17,7 @@ namespace md {
 namespace {
 
 constexpr float kLog2eE = 1.4426950408889634f;
-constexpr int kMaxWindow = 16;
+constexpr int kMaxWindow = 16;                   // = the length of EncodeDims::moff
 #ifndef MD_ENC_WAVES
 #define MD_ENC_WAVES 4
 #endif
@@ -29,6 +29,7 @@ struct EncodeDims {
     int kt, kh, kw;
     int M, W, ws, nwx, nwy, nwt;
     int clipped;      // the window does not divide the grid: windows at the far border hold fewer tokens
+    int moff[16];     // member_offset(m), m < ws: filled by the host so that kernels get them as scalars
 };
 
 // Token of member m of window w; -1 for a member that a clipped border window does not have.
@@ -47,7 +48,7 @@ __device__ __forceinline__ int window_base(const EncodeDims& p, int w) {
     const int wx = w % p.nwx, wy = (w / p.nwx) % p.nwy, wt = w / (p.nwx * p.nwy);
     return (wt * p.kt * p.Hg + wy * p.kh) * p.Wg + wx * p.kw;
 }
-__device__ __forceinline__ int member_offset(const EncodeDims& p, int m) {
+__host__ __device__ __forceinline__ int member_offset(const EncodeDims& p, int m) {
     const int dx = m % p.kw, dy = (m / p.kw) % p.kh, dt = m / (p.kw * p.kh);
     return (dt * p.Hg + dy) * p.Wg + dx;
 }
@@ -109,7 +110,7 @@ template <> struct Vec<true> {
 // together) and leaves, per head h and for its group g of rows,
 //     part[b][h][g] = (m, z):  m = max of x over the rows that count (the CLS row and the valid tokens),
 //                              z = sum of exp2(x - m) over them,
-//     num[b][h][j]  = exp2(x[h][j] - m)   for each of those rows,
+//     num[b][j][h]  = exp2(x[h][j] - m)   for each of those rows (heads contiguous),
 // so that the decision kernel gets a probability as num * exp2(m - m_h) / Z_h with one factor per
 // (head, group): no exponential per (head, token) on the one CU that decides for a sample.
 // A head covers vph = dc/VEC consecutive 16-byte vectors (a power of two), so the per-head sums are
@@ -149,7 +150,7 @@ __device__ __forceinline__ void cls_logits_rows(
     for (int r = 0; r < R; ++r) krow[r] = kb0 + (size_t)min(j0 + r, p.M) * rowb;
     const int nvec = p.D / VEC, vph = p.dc / VEC;
     const float scale = 1.0f / sqrtf((float)p.dc);
-    float* out = logits + (size_t)b * p.Hc * (p.M + 1) + j0;
+    float* out = logits + ((size_t)b * (p.M + 1) + j0) * p.Hc;
     float2* pout = part + (size_t)b * p.Hc * gps + g;
     // the R logits of one head -> numerators (in place) and their statistics (every lane that holds
     // them computes the same values)
@@ -198,7 +199,7 @@ __device__ __forceinline__ void cls_logits_rows(
                 pout[(size_t)h * gps] = finish(lg);
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    if (act[r]) out[(size_t)h * (p.M + 1) + r] = lg[r];
+                    if (act[r]) out[(size_t)r * p.Hc + h] = lg[r];
             }
         } else {
             const int per_head = vph / kWave;                 // iterations per head
@@ -213,7 +214,7 @@ __device__ __forceinline__ void cls_logits_rows(
                     pout[(size_t)h * gps] = finish(lg);
 #pragma unroll
                     for (int r = 0; r < R; ++r)
-                        if (act[r]) out[(size_t)h * (p.M + 1) + r] = lg[r];
+                        if (act[r]) out[(size_t)r * p.Hc + h] = lg[r];
                 }
             }
         }
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
 
     // ---- Key Retaining
     if (key_budget > 0 || key_adaptive) {
-        const float* lg = logits + (size_t)b * p.Hc * (M + 1);       // numerators, see cls_logits_rows
+        const float* lg = logits + (size_t)b * (M + 1) * p.Hc;       // numerators [row][head], see cls_logits_rows
         const int gps = cls_groups(M);
         const float2* pb = cls_part + (size_t)b * p.Hc * gps;
         for (int h = wv; h < p.Hc; h += nw) {
@@ -377,7 +378,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
                 a = 0.f;
                 const int g = (j + 1) / kClsRows;
                 for (int h = 0; h < p.Hc; ++h)
-                    a = fmaf(lg[(size_t)h * (M + 1) + j + 1], fast_exp2(pb[(size_t)h * gps + g].x - s_max[h]) * s_inv[h], a);
+                    a = fmaf(lg[(size_t)(j + 1) * p.Hc + h], fast_exp2(pb[(size_t)h * gps + g].x - s_max[h]) * s_inv[h], a);
             }
             acls_b[j] = a;
             if (a_cls_out) a_cls_out[(size_t)b * M + j] = a;
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(1024) void encode_decide_kernel(
 #else
 #define MD_DTICK(k) do { } while (0)
 #endif
-template <int IPT>
+template <int IPT, int WS>
 __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     EncodeDims p, const uint8_t* __restrict__ valid, const float* __restrict__ mass_in,
     const float* __restrict__ logits, const float2* __restrict__ cls_part, const float* __restrict__ sim,
@@ -508,18 +509,16 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     // [M] merged-window mass / scores (float), then [M] key flags and [M] token states, which take the place of
     // the [groups][16] factors of Eq. 6 (see decide_fast_lds_bytes)
     extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
-    __shared__ int s_hist[256];
+    __shared__ int s_hist[kSelectHistInts];
     __shared__ int s_red[16];
-    __shared__ uint32_t s_lo[16], s_hi[16];
     __shared__ float s_redf[16];
-    __shared__ int s_moff[kMaxWindow];               // member_offset(m): integer divisions done once per block
 #ifdef MD_DECIDE_TICKS
-    __shared__ long long ticks[8];
+    __shared__ long long ticks[12];
 #endif
     MD_DTICK(0);
-    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wv = wave_id();
     const int M = p.M, W = p.W;
-    if (tid < p.ws) s_moff[tid] = member_offset(p, tid);    // read after later barriers
+    if (tid < 256) s_hist[tid] = 0;                         // for block_select_topk, after later barriers
     float* s_tmass = reinterpret_cast<float*>(s_dyn);
     uint8_t* s_key = s_dyn + 4 * (size_t)M;
     uint8_t* s_state = s_key + M;                    // 0: not in a merged window, 1: first valid member, 2: merged away
@@ -527,7 +526,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     const float* mb = mass_in ? mass_in + (size_t)b * M : nullptr;
     const int j0 = tid * IPT;                        // first own token (and first own window)
     const bool with_keys = key_budget > 0 || key_adaptive;
-    const float* lg = logits + (size_t)b * p.Hc * (M + 1);
+    const float* lg = logits + (size_t)b * (M + 1) * p.Hc;           // numerators [row][head], row 0 = CLS
 
     // ---- everything that depends on nothing is requested first (clamped or range-checked addresses, no
     // guarded loads: a guarded load would wait for the one before it)
@@ -535,7 +534,6 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     // lanes take the head's per-group statistics (group = kClsRows rows, see cls_logits_rows).
     constexpr int PRE = 16;                          // heads
     constexpr int NPB = 2 * IPT + 1;                 // groups per lane: 64 * NPB >= cls_groups(1024 * IPT)
-    constexpr int PT = IPT < 4 ? IPT : 4;            // tokens per batch of numerators
     constexpr bool EARLY = IPT <= 4;                 // registers allow the first batch to be requested up front
     const int gps = cls_groups(M);
     float2 pv[NPB];
@@ -544,21 +542,21 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
 #pragma unroll
         for (int u = 0; u < NPB; ++u) pv[u] = pp[min(lane + u * kWave, gps - 1)];
     }
-    // numerators of the tokens tid + 1024*t, all heads: one buffer load each (the token's offset in a
-    // vector register, the head's in a scalar one; tokens beyond M repeat the last one and are dropped).
-    // The scores change hands through LDS afterwards.
-    const __amdgpu_buffer_rsrc_t rnum =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lg + 1), 0, (max(p.Hc, 1) * (M + 1) - 1) * 4, 0x00020000);
-    float xl[PT][PRE];
+    // Numerators of the tokens tid + 1024*t: the 16 heads of a token are 64 consecutive bytes, four
+    // 16-byte buffer loads (the token's offset in a vector register, the quarter's and the batch's in the
+    // instruction and a scalar; tokens beyond M and heads beyond Hc fall outside the buffer's range and
+    // read as zero).  The scores change hands through LDS afterwards.
+    constexpr int PT = IPT < 4 ? IPT : 4;            // tokens per batch
+    const int nrec = M * p.Hc * 4;
+    const __amdgpu_buffer_rsrc_t rnum = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lg + p.Hc), 0, nrec, 0x00020000);
+    f32x4 xl[PT][4];
     auto request_numerators = [&](int t0) {
 #pragma unroll
-        for (int t = 0; t < PT; ++t) {
-            const int voff = min(tid + 1024 * (t0 + t), M - 1) * 4;
+        for (int t = 0; t < PT; ++t)
 #pragma unroll
-            for (int u = 0; u < PRE; ++u)
-                xl[t][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                    rnum, voff, min(u, p.Hc - 1) * (M + 1) * 4, 0));
-        }
+            for (int q = 0; q < 4; ++q)
+                xl[t][q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                    rnum, 4 * q < p.Hc ? tid * p.Hc * 4 + 16 * q : nrec, (t0 + t) * 1024 * p.Hc * 4, 0));
     };
     bool ok[IPT];
     float mass[IPT], simv[IPT];
@@ -581,6 +579,41 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     bool sel[IPT];
 #pragma unroll
     for (int t = 0; t < IPT; ++t) sel[t] = false;
+    // What a window's decision needs besides the key flags, worked out while the loads above are on
+    // their way: its first token, which members are valid, their count, first one and total mass.
+    struct WinInfo { int base, first, n; uint32_t vmask; float total; };
+    auto analyse = [&](int w) -> WinInfo {
+        WinInfo wi;
+        wi.base = window_base(p, w); wi.first = -1; wi.n = 0; wi.vmask = 0u; wi.total = 0.f;
+#pragma unroll
+        for (int m0 = 0; m0 < WS; m0 += 4) {         // four members' flags and masses in flight (WS >= ws)
+            if (m0 >= p.ws) break;
+            uint32_t vv[4];
+            float mm[4];
+            int tk[4];
+            bool inb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                inb[u] = m0 + u < p.ws && member_in_grid(p, w, m0 + u);
+                tk[u] = inb[u] ? wi.base + p.moff[m0 + u] : wi.base;     // the window's first token is always there
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vv[u] = vb ? vb[tk[u]] : 1u;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) mm[u] = mb ? mb[tk[u]] : 1.0f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (!inb[u] || vv[u] == 0) continue;
+                wi.vmask |= 1u << (m0 + u);
+                ++wi.n;
+                if (wi.first < 0) wi.first = tk[u];
+                wi.total += mm[u];
+            }
+        }
+        return wi;
+    };
+    WinInfo win0 = analyse(min(tid, W - 1));         // nearly always the thread's only window (W <= 1024)
+    MD_DTICK(8);
 
     if (with_keys) {
         // head statistics (m_h, Z_h) and the factor of every group: f[g][h] = exp2(m_g - m_h) / (Z_h * Hc)
@@ -593,6 +626,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
                 mx = fmaxf(mx, pv[u].x);
             }
             const float gm = wave_max(mx);
+            MD_DTICK(9);
             float z = 0.f;
 #pragma unroll
             for (int u = 0; u < NPB; ++u) {
@@ -605,6 +639,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
                 if (lane + u * kWave < gps) s_f[(lane + u * kWave) * PRE + wv] = pv[u].x * inv;
         }
         if (!EARLY) request_numerators(0);
+        MD_DTICK(10);
         __syncthreads();
         MD_DTICK(1);
         // a_cls (head mean of the probabilities) of the tokens tid + 1024*t
@@ -618,12 +653,12 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
                 const f32x4* fr = reinterpret_cast<const f32x4*>(s_f + (size_t)(min(j, M - 1) + 1) / kClsRows * PRE);
                 float a = 0.f;
 #pragma unroll
-                for (int q = 0; q < PRE / 4; ++q) {
+                for (int q = 0; q < 4; ++q) {
                     const f32x4 f = fr[q];
-                    a = fmaf(xl[t][4 * q], f.x, a);
-                    a = fmaf(xl[t][4 * q + 1], f.y, a);
-                    a = fmaf(xl[t][4 * q + 2], f.z, a);
-                    a = fmaf(xl[t][4 * q + 3], f.w, a);
+                    a = fmaf(xl[t][q].x, f.x, a);
+                    a = fmaf(xl[t][q].y, f.y, a);
+                    a = fmaf(xl[t][q].z, f.z, a);
+                    a = fmaf(xl[t][q].w, f.w, a);
                 }
                 if (j < M) s_a[j] = a;
             }
@@ -641,19 +676,7 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
             rk[t] = ok[t] ? rank_key(a, j) : 0ull;
         }
         if (!key_adaptive) {                         // Eq. 7, budget form: the key_budget largest scores
-            // the scores' bit patterns share their leading bits: start the radix passes below them
-            uint32_t lo = 0xFFFFFFFFu, hi = 0u;
-#pragma unroll
-            for (int t = 0; t < IPT; ++t)
-                if (rk[t] != 0) { lo = min(lo, (uint32_t)(rk[t] >> 32)); hi = max(hi, (uint32_t)(rk[t] >> 32)); }
-            lo = wave_min_u32(lo);
-            hi = ~wave_min_u32(~hi);
-            if (lane == 0) { s_lo[wv] = lo; s_hi[wv] = hi; }
-            __syncthreads();
-            lo = wave_min_u32(lane < nw ? s_lo[lane] : 0xFFFFFFFFu);
-            hi = ~wave_min_u32(lane < nw ? ~s_hi[lane] : 0xFFFFFFFFu);
-            const int common = lo <= hi ? (lo == hi ? 32 : __clz((int)(lo ^ hi))) : 0;     // leading bits all present keys share
-            const SelectBound sb = block_radix_select_reg<IPT>(rk, key_budget, s_hist, common, (uint64_t)hi << 32);
+            const SelectBound sb = block_select_topk<IPT>(rk, key_budget, s_hist);
 #pragma unroll
             for (int t = 0; t < IPT; ++t) sel[t] = rk[t] != 0 && (rk[t] >> sb.shift) >= sb.bound;
         } else {                                     // Eq. 7 as printed: a_cls > mu, mu = mean + lambda * std
@@ -693,46 +716,20 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
     for (int t = 0; t < IPT; ++t) {
         const int w = tid + 1024 * t;                // windows go round the threads: there are fewer than tokens
         if (w >= W) continue;
-        int n = 0, first = -1;
+        const WinInfo wi = t == 0 ? win0 : analyse(w);
         bool has_key = false;
-        float total = 0.f;
-        const int base = window_base(p, w);
-        uint32_t vmask = 0;                          // bit m: member m is valid
-        for (int m0 = 0; m0 < p.ws; m0 += 4) {       // four members' flags and masses in flight
-            uint32_t vv[4];
-            float mm[4];
-            int tk[4];
-            bool inb[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int m = min(m0 + u, p.ws - 1);
-                inb[u] = member_in_grid(p, w, m);
-                tk[u] = inb[u] ? base + s_moff[m] : base;        // the window's first token is always there
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) vv[u] = vb ? vb[tk[u]] : 1u;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) if (!inb[u]) vv[u] = 0u;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) mm[u] = mb ? mb[tk[u]] : 1.0f;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (m0 + u >= p.ws || vv[u] == 0) continue;
-                vmask |= 1u << (m0 + u);
-                ++n;
-                if (first < 0) first = tk[u];
-                has_key |= s_key[tk[u]] != 0;
-                total += mm[u];
-            }
-        }
-        const bool mg = n >= 2 && !has_key && simv[t] > tau;
+        for (int m = 0; m < WS; ++m)
+            if (m < p.ws && ((wi.vmask >> m) & 1u)) has_key |= s_key[wi.base + p.moff[m]] != 0;
+        const bool mg = wi.n >= 2 && !has_key && simv[t] > tau;
         if (mg) {
-            for (int m = 0; m < p.ws; ++m) {
-                if (!((vmask >> m) & 1u)) continue;
-                const int tok = base + s_moff[m];
-                s_state[tok] = tok == first ? 1 : 2;
+#pragma unroll
+            for (int m = 0; m < WS; ++m) {
+                if (m >= p.ws || !((wi.vmask >> m) & 1u)) continue;
+                const int tok = wi.base + p.moff[m];
+                s_state[tok] = tok == wi.first ? 1 : 2;
             }
-            s_tmass[first] = total;
+            s_tmass[wi.first] = wi.total;
         }
         wmerged[(size_t)b * W + w] = mg;
         if (window_sim_out) window_sim_out[(size_t)b * W + w] = simv[t];
@@ -788,9 +785,10 @@ __global__ __launch_bounds__(1024) void encode_decide_fast_kernel(
 #ifdef MD_DECIDE_TICKS
     MD_DTICK(7);
     if (threadIdx.x == 0 && blockIdx.x == 0)
-        printf("decide ticks: denom %lld acls %lld select %lld keyflags %lld windows %lld scan %lld writes %lld total %lld\n",
-               ticks[1] - ticks[0], ticks[2] - ticks[1], ticks[3] - ticks[2], ticks[4] - ticks[3], ticks[5] - ticks[4],
-               ticks[6] - ticks[5], ticks[7] - ticks[6], ticks[7] - ticks[0]);
+        printf("issue %d gm %d f %d bar %d | acls %d select %d keyflags %d windows %d scan %d writes %d total %d\n",
+               (int)(ticks[8] - ticks[0]), (int)(ticks[9] - ticks[8]), (int)(ticks[10] - ticks[9]), (int)(ticks[1] - ticks[10]),
+               (int)(ticks[2] - ticks[1]), (int)(ticks[3] - ticks[2]), (int)(ticks[4] - ticks[3]), (int)(ticks[5] - ticks[4]),
+               (int)(ticks[6] - ticks[5]), (int)(ticks[7] - ticks[6]), (int)(ticks[7] - ticks[0]));
 #endif
 }
 
@@ -912,8 +910,11 @@ size_t decide_fast_lds_bytes(int M) {
 bool decide_fast_lds_ready(int M, size_t bytes) {
     if (bytes <= 64 * 1024) return true;
     if (M <= 4096) return false;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_decide_fast_kernel<8>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    bool ok = true;
+    ok &= hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_decide_fast_kernel<8, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    ok &= hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_decide_fast_kernel<8, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    ok &= hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_decide_fast_kernel<8, 16>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    return ok;
 }
 
 template <int WSM>
@@ -999,6 +1000,7 @@ int encode_merge_impl(
     p.kt = kt; p.kh = kh; p.kw = kw; p.M = M; p.W = W; p.ws = ws;
     p.nwx = nwx; p.nwy = nwy; p.nwt = nwt;
     p.clipped = (T % kt || Hg % kh || Wg % kw) ? 1 : 0;
+    for (int m = 0; m < kMaxWindow; ++m) p.moff[m] = m < ws ? member_offset(p, m) : 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     const long items = (long)B * W + (with_keys ? (long)B * cls_groups(M) : 0);
@@ -1011,21 +1013,24 @@ int encode_merge_impl(
     else launch_scores<16>(sgrid, st, xbf, qkbf, x, q_cls, k_cls, valid, p, with_cls, wsp.sim, wsp.logits, wsp.cls_part);
     dim3 wgrid((unsigned)(((long)B * W + kEncWaves - 1) / kEncWaves));
     const size_t dlds = decide_fast_lds_bytes(M);
-    const bool fast_ok = M <= 8192 && (!with_keys || Hc <= 16) && decide_fast_lds_ready(M, dlds);
-#define MD_DECIDE_FAST(IPT_)                                                                                  \
-    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_>), B, 1024, dlds,                       \
+    const bool fast_ok = M <= 8192 && (!with_keys || (Hc <= 16 && Hc % 4 == 0)) && decide_fast_lds_ready(M, dlds);
+#define MD_DECIDE_FAST(IPT_, WS_)                                                                             \
+    MD_LAUNCH("encode_decide", st, (encode_decide_fast_kernel<IPT_, WS_>), B, 1024, dlds,                  \
         p, valid, mass_in, wsp.logits, wsp.cls_part, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,  \
         wsp.wmerged, wsp.dstpos,                                                                                   \
         out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out)
-    if (fast_ok && M <= 1024) MD_DECIDE_FAST(1);
-    else if (fast_ok && M <= 2048) MD_DECIDE_FAST(2);
-    else if (fast_ok && M <= 4096) MD_DECIDE_FAST(4);
-    else if (fast_ok) MD_DECIDE_FAST(8);
+#define MD_DECIDE_FAST_WS(IPT_)                                                                               \
+    do { if (ws <= 4) MD_DECIDE_FAST(IPT_, 4); else if (ws <= 8) MD_DECIDE_FAST(IPT_, 8); else MD_DECIDE_FAST(IPT_, 16); } while (0)
+    if (fast_ok && M <= 1024) MD_DECIDE_FAST_WS(1);
+    else if (fast_ok && M <= 2048) MD_DECIDE_FAST_WS(2);
+    else if (fast_ok && M <= 4096) MD_DECIDE_FAST_WS(4);
+    else if (fast_ok) MD_DECIDE_FAST_WS(8);
     else
         MD_LAUNCH("encode_decide", st, (encode_decide_kernel), B, 1024, 0,
             p, valid, mass_in, wsp.logits, wsp.cls_part, wsp.sim, tau, key_budget, key_adaptive, key_lambda, key_count,
             wsp.acls, wsp.iskey, wsp.wmerged, wsp.dstpos,
             out_index, out_mass, out_is_key, out_valid, out_count, key_index, a_cls_out, window_sim_out);
+#undef MD_DECIDE_FAST_WS
 #undef MD_DECIDE_FAST
     if (x_dtype == MD_BF16) MD_LAUNCH("encode_emit", st, (encode_emit_kernel<true>), wgrid, 64 * kEncWaves, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);
     else MD_LAUNCH("encode_emit", st, (encode_emit_kernel<false>), wgrid, 64 * kEncWaves, 0, x, valid, mass_in, p, wsp.wmerged, wsp.dstpos, out_x);

@@ -219,63 +219,72 @@ __device__ __forceinline__ SelectBound block_radix_select(KeyFn key, int n, int 
 }
 
 // Same selection with the keys held in registers (IPT per thread, 0 = absent; real keys are never 0
-// as long as the tie value is below 2^31 - 1): no memory traffic inside the passes.  The wave that
-// scans the histogram also clears it, so a pass costs two barriers.
+// as long as the tie value is below 2^31 - 1), built for a short chain of dependent steps:
+//   - the scores of one sample share their leading bits (sign, most of the exponent): the block's
+//     smallest and largest score are found first and the passes start below the bits they share, so
+//     the first histogram is spread over its bins instead of piling onto two or three of them;
+//   - three histograms take turns (pass p counts into hist[p % 3] and clears hist[(p + 1) % 3], which
+//     nobody reads between the two barriers around it), and every wave scans the finished histogram
+//     itself: one barrier per pass and no hand-over of the result through LDS.
+// `hist`: 768 ints of shared memory whose first 256 the caller has zeroed, with a block barrier
+// between the zeroing and this call.  All threads of the block (at most 16 waves) must call it.
+constexpr int kSelectHistInts = 768;
 template <int IPT>
-__device__ __forceinline__ SelectBound block_radix_select_reg(const uint64_t (&key)[IPT], int k, int* hist,
-                                                               int skip = 0, uint64_t top = 0ull) {
-    __shared__ int s_digit, s_k, s_done;
+__device__ __forceinline__ SelectBound block_select_topk(const uint64_t (&key)[IPT], int k, int* hist) {
     if (k <= 0) return SelectBound{~0ull, 0};               // nothing selected
-    const int lane = lane_id();
-    __syncthreads();                                        // earlier readers of the shared words are done
-    for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+    const int lane = lane_id(), wv = wave_id(), nw = blockDim.x >> 6;
+    // leading bits common to every present key's score
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int t = 0; t < IPT; ++t)
+        if (key[t] != 0) { lo = min(lo, (uint32_t)(key[t] >> 32)); hi = max(hi, (uint32_t)(key[t] >> 32)); }
+    lo = wave_min_u32(lo);
+    hi = ~wave_min_u32(~hi);
+    if (lane == 0) { hist[512 + wv] = (int)lo; hist[528 + wv] = (int)hi; }     // hist[2] is not in use before pass 1
     __syncthreads();
-    // `skip` leading bits (0..56) are the same in every present key (those of `top`): the passes start below them
+    lo = wave_min_u32(lane < nw ? (uint32_t)hist[512 + lane] : 0xFFFFFFFFu);
+    hi = ~wave_min_u32(lane < nw ? ~(uint32_t)hist[528 + lane] : 0xFFFFFFFFu);
+    if (lo > hi) return SelectBound{0ull, 63};              // no key present: "select everything" selects nothing
+    const int skip = lo == hi ? 32 : __clz((int)(lo ^ hi));
     int sh = 56 - skip, shift = 64 - skip;
-    uint64_t prefix = skip > 0 ? top >> shift : 0ull;
+    uint64_t prefix = skip > 0 ? ((uint64_t)hi << 32) >> shift : 0ull;
     int kk = k;
     bool first = skip == 0;
-    for (;;) {
+    for (int pass = 0;; ++pass) {
+        int* h = hist + (pass % 3) * 256;
+        int* hn = hist + ((pass + 1) % 3) * 256;
 #pragma unroll
         for (int t = 0; t < IPT; ++t) {
             const uint64_t kv = key[t];
-            if (kv != 0 && (first || (kv >> shift) == prefix)) atomicAdd(&hist[(kv >> sh) & 0xFF], 1);
+            if (kv != 0 && (first || (kv >> shift) == prefix)) atomicAdd(&h[(kv >> sh) & 0xFF], 1);
         }
+        if (threadIdx.x < 256) hn[threadIdx.x] = 0;
         __syncthreads();
-        if (threadIdx.x < kWave) {
-            // digits 255..0 handled 4 per lane, high digits in low lanes
-            int c[4], s = 0;
+        // digits 255..0, four per lane, high digits in low lanes; every wave does the same scan
+        int c[4], s = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { c[t] = h[255 - (lane * 4 + t)]; s += c[t]; }
+        const int incl = wave_incl_scan_i(s);
+        const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+        if (total < kk) return SelectBound{0ull, 63};       // fewer than k items: select everything (keys < 2^63)
+        int run = incl - s;                                 // items in strictly higher digits
+        const bool mine = run < kk && incl >= kk;           // the lane whose four digits hold the k-th item
+        int packed = 0;
+        if (mine) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                c[t] = hist[255 - (lane * 4 + t)];
-                hist[255 - (lane * 4 + t)] = 0;
-                s += c[t];
-            }
-            const int incl = wave_incl_scan_i(s);
-            int run = incl - s;                             // items in strictly higher digits
-            const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
-            if (lane == 0 && total < kk) { s_digit = 0; s_k = kk; s_done = 2; }   // fewer than k items
-            if (total >= kk) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    if (run < kk && run + c[t] >= kk) {
-                        s_digit = 255 - (lane * 4 + t);
-                        s_k = kk - run;
-                        s_done = (run + c[t] == kk) ? 1 : 0;
-                    }
-                    run += c[t];
-                }
+                if (run < kk && run + c[t] >= kk)
+                    packed = (255 - (lane * 4 + t)) | ((run + c[t] == kk ? 1 : 0) << 8) | ((kk - run) << 9);
+                run += c[t];
             }
         }
-        __syncthreads();
-        const int done = s_done;
-        if (done == 2) return SelectBound{0ull, 63};        // select everything (keys < 2^63)
+        packed = __builtin_amdgcn_readlane(packed, __builtin_ctzll(__ballot(mine)));
         const int width = shift - sh;                       // 8, less when the last digit overlaps its predecessor
-        prefix = (prefix << width) | ((uint64_t)s_digit & ((1ull << width) - 1ull));
+        prefix = (prefix << width) | ((uint64_t)(packed & 0xFF) & ((1ull << width) - 1ull));
         shift = sh;
-        kk = s_k;
+        kk = packed >> 9;
         first = false;
-        if (done == 1 || sh == 0) break;
+        if (((packed >> 8) & 1) || sh == 0) break;          // the chosen bin is taken whole, or no bits are left
         sh = max(sh - 8, 0);
     }
     return SelectBound{prefix, shift};

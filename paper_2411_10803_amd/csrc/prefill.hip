@@ -931,12 +931,13 @@ __global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
 {
     __shared__ float s_redf[16];
     __shared__ int s_red[16];
-    __shared__ int s_hist[256];
+    __shared__ int s_hist[kSelectHistInts];
     if ((int)blockIdx.x >= p.B) {                    // block-uniform: the blocks that copy the text rows
         copy_text_rows<IPT>(p, tr, vis_valid, txt_len, is_key, budget, s_red);
         return;
     }
     const int b = blockIdx.x, tid = threadIdx.x;
+    if (tid < 256) s_hist[tid] = 0;                  // for block_select_topk, after later barriers
     const int Mv = p.Mv;
     const int rows_cap = p.Rcap + p.N;
     float v[IPT], iv[IPT];
@@ -988,7 +989,7 @@ __global__ __launch_bounds__(1024) void prefill_select_fast_kernel(
             const float s2 = iv[t] / alpha;
             rk[t] = (ok[t] && !key[t]) ? rank_key(fmaxf(s1, s2), tid + t * 1024) : 0ull;
         }
-        const SelectBound sb = block_radix_select_reg<IPT>(rk, extra, s_hist);
+        const SelectBound sb = block_select_topk<IPT>(rk, extra, s_hist);
 #pragma unroll
         for (int t = 0; t < IPT; ++t) keep[t] = key[t] || (rk[t] != 0 && extra > 0 && (rk[t] >> sb.shift) >= sb.bound);
     } else {
