@@ -9,7 +9,12 @@
  *
  * Conventions common to all calls
  *   - Every data pointer is DEVICE memory owned by the caller (inputs, outputs and the workspace).
- *     The library allocates nothing, frees nothing and keeps no state between calls.
+ *     The entry points of this header allocate nothing, free nothing and keep no state between
+ *     calls, with these exceptions, all stated here: the thread-local text behind
+ *     mustdrop_last_error(); the static device buffer of mustdrop_encode_merge_noalloc and the
+ *     address of it that the library looks up once per device (see there); and, while a caller
+ *     has switched on the benchmarking aid declared in mustdrop_bench.h (a separate header, not
+ *     needed to use the method), one pair of HIP events per kernel launch.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream).  No
  *     call synchronises with the host; variable-length results are reported through device-side
  *     count arrays and the outputs are padded to a static capacity.
@@ -32,7 +37,10 @@
 extern "C" {
 #endif
 
-typedef enum { MD_F32 = 0, MD_BF16 = 1 } md_dtype;
+/* Element types and modes cross the boundary as plain ints (a caller may hand over any value: one
+ * that names nothing is an error code, never undefined behaviour). */
+typedef int md_dtype;
+enum { MD_F32 = 0, MD_BF16 = 1 };
 
 typedef enum {
     MD_OK = 0,
@@ -45,7 +53,8 @@ typedef enum {
     MD_EHIP = 7         /* the HIP runtime reported an error at launch                  */
 } md_status;
 
-typedef enum { MD_FILTER_BUDGET = 0, MD_FILTER_THRESHOLD = 1 } md_filter_mode;
+typedef int md_filter_mode;
+enum { MD_FILTER_BUDGET = 0, MD_FILTER_THRESHOLD = 1 };
 
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* mustdrop_last_error(void);
@@ -320,18 +329,6 @@ int mustdrop_decode_keep_strided(
     int32_t* evicted_ids, int32_t* evicted_count,
     const md_kv_layout* cache_layout, int64_t layer_stride,
     void* workspace, size_t workspace_bytes, void* stream);
-
-/* ------------------------------------------------------------------------------------------
- * Benchmarking aid (not part of the method): per-kernel timing with HIP events.
- * Between mustdrop_profile_start() and mustdrop_profile_stop() every kernel the library launches
- * carries an event pair that receives the begin and end timestamps of that dispatch on its stream
- * (what a kernel trace reports; marker events around a launch would add their own few microseconds).
- * _stop waits for the events, destroys them and reports, per distinct kernel name, the summed
- * milliseconds and the number of launches: names is a host array of cap*64 chars, total_ms / calls
- * host arrays of cap entries, *n_out the number of names filled.  Host pointers.  Not thread-safe;
- * do not use while another thread is inside the library. */
-int mustdrop_profile_start(void);
-int mustdrop_profile_stop(char* names, float* total_ms, int* calls, int cap, int* n_out);
 
 #ifdef __cplusplus
 }

@@ -1,5 +1,6 @@
 // Error reporting and version of the C ABI.
 #include "md_host.hpp"
+#include "../../include/mustdrop_bench.h"
 
 #include <string.h>
 
