@@ -68,6 +68,13 @@ __device__ __forceinline__ int window_of_token(const EncodeDims& p, int tok) {
 template <bool BF> struct Vec;
 template <> struct Vec<false> {
     static constexpr int N = 4;
+    // a vector as loaded, and the dot product of two of them added to acc (elements in ascending order)
+    using Raw = f32x4;
+    __device__ static __forceinline__ Raw load_raw(const void* row, int c) { return *reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c); }
+    __device__ static __forceinline__ Raw zero() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ static __forceinline__ float dot(const Raw& a, const Raw& b, float acc) {
+        acc = fmaf(a.x, b.x, acc); acc = fmaf(a.y, b.y, acc); acc = fmaf(a.z, b.z, acc); return fmaf(a.w, b.w, acc);
+    }
     __device__ static __forceinline__ void load(const void* row, int c, float (&o)[4]) {
         const f32x4 v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c);
         o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
@@ -84,6 +91,19 @@ template <> struct Vec<false> {
 };
 template <> struct Vec<true> {
     static constexpr int N = 8;
+    // bf16 pairs stay packed: v_dot2c_f32_bf16 multiplies two pairs and adds both products to an fp32
+    // accumulator (the products of bf16 values are exact in fp32), one instruction per two elements and
+    // no widening
+    using Raw = u32x4;
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    __device__ static __forceinline__ Raw load_raw(const void* row, int c) { return *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c); }
+    __device__ static __forceinline__ Raw zero() { return u32x4{0u, 0u, 0u, 0u}; }
+    __device__ static __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+    }
+    __device__ static __forceinline__ float dot(const Raw& a, const Raw& b, float acc) {
+        acc = dot2(a.x, b.x, acc); acc = dot2(a.y, b.y, acc); acc = dot2(a.z, b.z, acc); return dot2(a.w, b.w, acc);
+    }
     __device__ static __forceinline__ void widen(const u32x4 v, float (&o)[8]) {
         o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
         o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
@@ -179,16 +199,13 @@ __device__ __forceinline__ void cls_logits_rows(
         for (int r = 0; r < R; ++r) part_r[r] = 0.f;
         {
             const int ic = min(idx, nvec - 1);       // lanes beyond the row repeat its last vector and drop it
-            float qv[VEC], kv[R][VEC];
-            Vec<BF>::load(qrow, ic * VEC, qv);
+            typename Vec<BF>::Raw kv[R];
+            const typename Vec<BF>::Raw qv = Vec<BF>::load_raw(qrow, ic * VEC);
 #pragma unroll
-            for (int r = 0; r < R; ++r) Vec<BF>::load(krow[r], ic * VEC, kv[r]);
+            for (int r = 0; r < R; ++r) kv[r] = Vec<BF>::load_raw(krow[r], ic * VEC);
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (!act[r] || idx >= nvec) continue;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) part_r[r] = fmaf(qv[e], kv[r][e], part_r[r]);
-            }
+            for (int r = 0; r < R; ++r)
+                if (act[r] && idx < nvec) part_r[r] = Vec<BF>::dot(qv, kv[r], part_r[r]);
         }
         if (vph < kWave) {
             float lg[R];
@@ -254,24 +271,20 @@ __device__ __forceinline__ void window_sim_item(
     // small windows take two slices of the feature dimension per round (2*WSM loads in flight)
     constexpr int NS = WSM <= 4 ? 2 : 1;
     for (int c0 = lane * VEC; c0 < p.D; c0 += NS * kWave * VEC) {
-        float v[NS][WSM][VEC];
+        typename Vec<BF>::Raw v[NS][WSM];
         bool in[NS];
 #pragma unroll
         for (int q = 0; q < NS; ++q) {
             const int c = c0 + q * kWave * VEC;
             in[q] = c < p.D;
 #pragma unroll
-            for (int m = 0; m < WSM; ++m) Vec<BF>::load(rows[m], in[q] ? c : c0, v[q][m]);
+            for (int m = 0; m < WSM; ++m) v[q][m] = Vec<BF>::load_raw(rows[m], in[q] ? c : c0);
         }
 #pragma unroll
         for (int q = 0; q < NS; ++q)
 #pragma unroll
-            for (int m = 0; m < WSM; ++m) {
-                if (!ok[m] || !in[q]) {
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) v[q][m][e] = 0.f;
-                }
-            }
+            for (int m = 0; m < WSM; ++m)
+                if (!ok[m] || !in[q]) v[q][m] = Vec<BF>::zero();
 #pragma unroll
         for (int q = 0; q < NS; ++q) {
             int idx = 0;
@@ -279,10 +292,8 @@ __device__ __forceinline__ void window_sim_item(
             for (int m = 0; m < WSM; ++m)
 #pragma unroll
                 for (int n = m; n < WSM; ++n) {
-                    float s = G[idx];
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) s = fmaf(v[q][m][e], v[q][n][e], s);
-                    G[idx++] = s;
+                    G[idx] = Vec<BF>::dot(v[q][m], v[q][n], G[idx]);
+                    ++idx;
                 }
         }
     }
