@@ -141,7 +141,12 @@ class Pipeline:
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same counters show for a plain
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
 # The runs and the raw figures are in profiles/hbm_traffic_cfg3_llavanext_b8.txt.
-MEASURED_HBM_TRAFFIC_BYTES = {}
+MEASURED_HBM_TRAFFIC_BYTES = {
+    "prefill_colscore": 214528086, "prefill_rowstats": 182713650, "prefill_compact": 126029989,
+    "encode_scores": 97278868, "encode_emit": 84420301, "prefill_select": 51074379, "prefill_colfix": 42408103,
+    "decode_logits": 30648408, "decode_move": 28228608, "encode_decide": 2424928, "decode_select": 904474,
+    "prefill_cstat": 699392,
+}
 
 
 def stage_bytes(cfg, pipe, counts):
@@ -260,6 +265,8 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
         nb = kb.get(name, 0)
         kernels[name] = {"avg_us": round(us, 2), "calls": k_calls[name], "algorithmic_MB": round(nb / 1e6, 3),
                          "GBps": round(nb / (us * 1e-6) / 1e9, 1) if us > 0 else 0.0, "frac_of_hbm_peak": frac(nb, us)}
+        if cfg.number == HEADLINE and name in MEASURED_HBM_TRAFFIC_BYTES:
+            kernels[name]["measured_traffic_MB"] = round(MEASURED_HBM_TRAFFIC_BYTES[name] / 1e6, 1)
         if name in flops:
             kernels[name]["mfma_frac"] = round(flops[name] / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
     score_names = ("prefill_rowstats", "prefill_cstat", "prefill_colscore", "prefill_colfix")
