@@ -24,6 +24,24 @@ def test_encode_more_than_8192_tokens_per_sample(T, Hg, Wg):
     assert s["merged_rows_checked"] + s["copied_rows_checked"] > 1000
 
 
+@pytest.mark.parametrize("T,Hg,Wg,Hc", [(2, 64, 64, 4), (1, 75, 80, 8), (1, 75, 80, 2)])
+def test_encode_between_4608_and_8192_tokens_per_sample(T, Hg, Wg, Hc):
+    # the register-resident decision kernel at eight tokens per thread, where its dynamic LDS exceeds 64 KiB
+    # (8192 and 6000 tokens); with a head count that is not a multiple of 4 the general kernel takes over
+    from paper_2411_10803_amd import harness
+    cfg = wl.tiny(wl.CONFIGS[4], B=2, T=T, Hg=Hg, Wg=Wg, D=64, Hc=Hc, dc=64 // Hc, kt=1 if T == 1 else 2, kh=2, kw=2, key_budget=70)
+    assert 4608 < cfg.M <= 8192
+    e = wl.encode_inputs(cfg)
+    rng = np.random.default_rng(5)
+    valid = (rng.random((cfg.B, cfg.M)) > 0.1).astype(np.uint8)
+    for v in (None, valid):
+        args = (cfg.T, cfg.Hg, cfg.Wg, cfg.kt, cfg.kh, cfg.kw, 0.9, cfg.key_budget)
+        g = harness.encode_on_gpu(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, v, *args)
+        o = oracle.encode_merge(e["x"], cfg.x_dtype, e["q_cls"], e["k_cls"], cfg.x_dtype, None, v, *args)
+        s = check_encode(g, o, e["x"], cfg.x_dtype, v, *args)
+        assert s["merged_rows_checked"] + s["copied_rows_checked"] > 1000
+
+
 def test_prefill_more_than_8192_vision_tokens():
     from paper_2411_10803_amd import harness
     cfg = wl.tiny(wl.CONFIGS[2], B=1, T=1, Hg=92, Wg=92, N=20, H=2, d=64, C=64)
