@@ -252,10 +252,9 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     constexpr int S = TW == 1 ? 4 : 3;                // LDS slots
     constexpr int SLOT_ROWS = 32 * TW, SLOT_BYTES = SLOT_ROWS * T::ROWB;
     constexpr int NLW = SLOT_ROWS / T::RPL / 4;       // load instructions per wave and step
-    constexpr int QBYTES = 4 * 32 * T::ROWB;          // the four waves' query tiles during the prologue
-    constexpr bool EARLY0 = S * SLOT_BYTES >= QBYTES + SLOT_BYTES;   // the last slot is free meanwhile
-    static_assert(S * SLOT_BYTES >= QBYTES, "the query tiles are staged in the K slots");
+    constexpr int QBYTES = NBW * 32 * T::ROWB;        // the block's query tiles during the prologue (one per wave column)
     __shared__ __attribute__((aligned(1024))) char s_k[S * SLOT_BYTES];
+    __shared__ __attribute__((aligned(1024))) char s_q[QBYTES];
     __shared__ float s_m[4][32], s_z[4][32];
     __shared__ int s_last[4];
     const int lane = lane_id(), wv = wave_id();
@@ -272,81 +271,101 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
 
     // The sweep runs over "effective" key positions e: the Me vision rows that matter (see
     // effective_rows), then the N text rows; e >= Me is row e + jump of K.  Me is a multiple of 32 (or
-    // Mv itself), so a 32-key tile never straddles the jump.  The chunks cut [0, Me + N) evenly.
-    int Me = p.Mv, jump = 0, c0 = 0, c1 = 0, nit = 0;
+    // Mv itself), so a 32-key tile never straddles the jump.  The nch blocks of a (sample, head) take the
+    // SLOT_ROWS-key steps in turn (block ch: steps ch, ch + nch, ...): their shares are even whatever Me is,
+    // and a block knows where its first steps lie before Me has been found.
+    int Me = p.Mv, jump = 0, c1 = 0, nit = 0;
     auto plan = [&]() {
         jump = p.Mv - Me;
-        const int units = (Me + p.N + 127) / 128, upc = (units + p.nch - 1) / p.nch;
-        c0 = ch * upc * 128;
-        c1 = min(c0 + upc * 128, Me + p.N);
-        nit = c1 > c0 ? (c1 - c0 + SLOT_ROWS - 1) / SLOT_ROWS : 0;         // steps of this block
+        c1 = Me + p.N;
+        const int steps = (c1 + SLOT_ROWS - 1) / SLOT_ROWS;
+        nit = steps > ch ? (steps - ch + p.nch - 1) / p.nch : 0;          // steps of this block
     };
-    // step g's tiles go to slot (g + S - 1) % S: step 0 into the last slot, which the query staging leaves free
+    auto step_row0 = [&](int g) { return (ch + g * p.nch) * SLOT_ROWS; };  // effective position of step g's first key
+    // step g's tiles go to slot g % S
     auto issue_step = [&](int g) {
-        char* slot = s_k + ((g + S - 1) % S) * SLOT_BYTES;
-        const int row0 = c0 + g * SLOT_ROWS;
+        char* slot = s_k + (g % S) * SLOT_BYTES;
+        const int row0 = step_row0(g);
 #pragma unroll
         for (int t = 0; t < NLW; ++t) {
             const int sr = (t * 4 + wv) * T::RPL;
             T::issue(rk, krow, row0 + (row0 + sr >= Me ? jump : 0), sr, slot, lane, true);
         }
     };
-    // Validity of this lane's key (lane % 32) in the tiles of the steps g0 .. g0+63, one bit per step.
-    // Fetched in batches of 64 steps: a load inside the steady loop would have the compiler wait for
-    // everything in flight, the K tiles included, once per step.
-    auto key_valid_bits = [&](int g0) -> uint64_t {
-        if (!vb) return ~0ull;
-        uint64_t bits = 0;
-        for (int u0 = 0; u0 < 64 && g0 + u0 < nit; u0 += 16) {
-            uint32_t raw[16];
+    // Validity of the 32 keys of this wave's tile in the steps g0 .. g0+63: lane l fetches the 32 mask bytes of
+    // step g0 + l and turns them into one word (bit r = key r of the tile is a valid vision token; bytes beyond
+    // the sample's Mv slots count as invalid), so a step gets its mask with one lane read and the whole batch
+    // costs one round trip.  (A load inside the steady loop would have the compiler wait for everything in
+    // flight, the K tiles included, once per step.)
+    auto key_valid_masks = [&](int g0) -> uint32_t {
+        if (!vb) return 0xFFFFFFFFu;
+        const long e0 = (long)step_row0(g0 + lane) + tw * 32;         // first key of the tile; a multiple of 32
+        uint32_t mask = 0;
+        if ((reinterpret_cast<uintptr_t>(vb) & 3) == 0) {             // block-uniform: the mask row is word-aligned
+            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(vb), 0, (p.Mv + 3) & ~3, 0x00020000);
+            uint32_t w[8];
+            const int off = (int)min(e0, (long)((p.Mv + 3) & ~3));    // beyond the row: out of the buffer's range, reads 0
 #pragma unroll
-            for (int u = 0; u < 16; ++u)             // unconditional loads from clamped addresses, 16 in flight
-                raw[u] = vb[min(c0 + ((g0 + u0 + u) * TW + tw) * 32 + (lane & 31), p.Mv - 1)];
+            for (int q = 0; q < 8; ++q) w[q] = __builtin_amdgcn_raw_buffer_load_b32(rv, off + 4 * q, 0, 0);
 #pragma unroll
-            for (int u = 0; u < 16; ++u) bits |= (uint64_t)(raw[u] != 0) << (u0 + u);
+            for (int q = 0; q < 8; ++q)
+                mask |= (((w[q] & 0xFFu) ? 1u : 0u) | ((w[q] & 0xFF00u) ? 2u : 0u) | ((w[q] & 0xFF0000u) ? 4u : 0u) |
+                         ((w[q] & 0xFF000000u) ? 8u : 0u)) << (4 * q);
+        } else {
+            for (int r = 0; r < 32; ++r) mask |= (vb[min(e0 + r, (long)p.Mv - 1)] != 0 ? 1u : 0u) << r;
         }
-        return bits;
+        const long left = (long)p.Mv - e0;                            // slots of the row from this tile on
+        if (left < 32) mask &= left <= 0 ? 0u : (1u << left) - 1u;
+        return mask;
     };
 
-    if (!vb) {
-        plan();
-        if (EARLY0 && nit > 0) issue_step(0);
+    // Prologue, one round trip: the query tiles (each wave column's tile, its rows split among the column's
+    // waves), the scan of the validity mask, and the first S-1 steps of K all go out together.  With a mask the
+    // rows that matter (Me) are not known yet: the steps are requested as if they lay below Me, which holds
+    // unless the sample has fewer than (S-1) * nch * SLOT_ROWS rows that matter; then they are requested again.
+    plan();
+#pragma unroll
+    for (int g = 0; g < S - 1; ++g)
+        if (g < nit) issue_step(g);
+    {
+        const __amdgpu_buffer_rsrc_t rq = row_buffer(qb, tl, p.q.token, p.d);
+#pragma unroll
+        for (int t = tw; t < 32 / T::RPL; t += TW)    // this wave's share of its column's 32 query rows
+            T::issue(rq, (uint32_t)(p.q.token * 2), i0, t * T::RPL, s_q + nbw * 32 * T::ROWB, lane, true);
     }
-    char* qtile = s_k + wv * 32 * T::ROWB;
-    issue_query_rows<KS>(qb, p.q.token, p.d, i0, tl, qtile, lane);
-    if (vb) {                                         // the mask scan shares the wait with the query rows
+    if (vb) {
         const int last = wave_max_int(last_set_partial(vb, p.Mv, threadIdx.x, 256));
         if (lane == 0) s_last[wv] = last;
     }
+    uint32_t vismasks = key_valid_masks(0);           // (its loads belong to the same round trip)
+    MD_VM_WAIT(0);
+    block_sync_lds();                                 // query tiles complete, mask scanned, first steps landed
     bf16x8 qf[KS];
-    read_query_frags<KS>(i0, tl, qtile, lane, qf);
-    if (ch == 0 && tw == 0 && nbg < p.Npad / 32) {
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[ks];
-    }
-    block_sync_lds();                                 // every wave has its query fragments: the slots are free
+    read_query_frags<KS>(i0, tl, s_q + nbw * 32 * T::ROWB, lane, qf);
     if (vb) {
+        const int nit_guess = nit;
         Me = effective_rows(max(max(s_last[0], s_last[1]), max(s_last[2], s_last[3])), p.Mv);
         plan();
         if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) mv_eff[b] = Me;   // for the second sweep
+        const int ahead = min(S - 1, max(nit, nit_guess));
+        if (ahead > 0 && step_row0(ahead - 1) + SLOT_ROWS > Me) {            // a requested step reaches beyond Me: again, with the jump
+#pragma unroll
+            for (int g = 0; g < S - 1; ++g)
+                if (g < nit) issue_step(g);
+        }
     } else if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) {
         mv_eff[b] = p.Mv;
     }
-    if ((!EARLY0 || vb) && nit > 0) issue_step(0);
-#pragma unroll
-    for (int g = 1; g < S - 1; ++g)
-        if (g < nit) issue_step(g);
-    uint64_t visbits = key_valid_bits(0);
 
     float m = -INFINITY, z = 0.f;
     const int i = i0 + (lane & 31);
     // what the arithmetic of a finished tile needs besides its accumulator
     struct Pending { bool all; uint32_t vis; };
     auto visibility = [&](int g) -> Pending {
-        const int j0 = c0 + (g * TW + tw) * 32;       // effective position of the tile's first key
-        const bool v_ok = ((visbits >> (g & 63)) & 1ull) != 0 && j0 + (lane & 31) < Me;
-        const uint32_t vmask = (uint32_t)__ballot(v_ok);     // the tile's 32 keys (vision keys only)
+        const int j0 = step_row0(g) + tw * 32;        // effective position of the tile's first key
+        // the tile's 32 keys (vision keys only): valid, and below the rows that matter
+        uint32_t vmask = (uint32_t)__builtin_amdgcn_readlane((int)vismasks, g & 63);
+        if (j0 + 32 > Me) vmask &= j0 >= Me ? 0u : (1u << (Me - j0)) - 1u;
         Pending pd;
         pd.all = j0 + 32 <= Me && vmask == 0xFFFFFFFFu;
         pd.vis = 0xFFFFu;
@@ -367,7 +386,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         if (g + S - 2 < nit) { MD_VM_WAIT((S - 2) * NLW); } else { MD_VM_WAIT(0); }   // this wave's part of step g has landed
         block_sync_lds();                             // ... and everyone else's; step g-1's slot is free
         if (g + S - 1 < nit) issue_step(g + S - 1);
-        T::frags(T::frag_base(s_k + ((g + S - 1) % S) * SLOT_BYTES + tw * 32 * T::ROWB, lane), kf);
+        T::frags(T::frag_base(s_k + (g % S) * SLOT_BYTES + tw * 32 * T::ROWB, lane), kf);
     };
     // The MFMA chain of step g is issued together with the arithmetic on the tile of step g-1.
     auto step = [&](int g, f32x16& acc_new, const f32x16& acc_old, Pending& pend) {
@@ -382,7 +401,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
             online_update_masked(acc_old, pend.vis, scale_log2e, m, z);
         }
         pend = visibility(g);
-        if ((g & 63) == 63 && g + 1 < nit) visbits = key_valid_bits(g + 1);   // (drains the loads in flight: once per 64 steps)
+        if ((g & 63) == 63 && g + 1 < nit) vismasks = key_valid_masks(g + 1);   // (drains the loads in flight: once per 64 steps)
     };
     f32x16 accA, accB;
     Pending pend{true, 0xFFFFu};
@@ -404,6 +423,12 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         if (pend.all) online_update_all(accA, scale_log2e, m, z); else online_update_masked(accA, pend.vis, scale_log2e, m, z);
     }
     MD_VM_WAIT(0);
+    // the fragment-major copy of the text queries for the second sweep (here, where no load waits behind the stores)
+    if (ch == 0 && tw == 0 && nbg < p.Npad / 32) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qfrag[((((long)b * p.H + h) * (p.Npad / 32) + nbg) * KS + ks) * kWave + lane] = qf[ks];
+    }
     // merge the two lane halves (same text row, the other 16 keys), then the tile lanes
     {
         const float mo = __shfl_xor(m, 32, kWave), zo = __shfl_xor(z, 32, kWave);
