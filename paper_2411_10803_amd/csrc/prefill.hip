@@ -241,22 +241,25 @@ __device__ __forceinline__ void interleave_mfma_valu() {
     }
 }
 
-template <int NBW, int KS>
-__global__ __launch_bounds__(256) void prefill_rowstats_kernel(
+template <int NBW, int TW, int KS>
+__global__ __launch_bounds__(64 * NBW * TW) void prefill_rowstats_kernel(
     const uint16_t* __restrict__ q_txt, const uint16_t* __restrict__ k,
     const uint8_t* __restrict__ vis_valid, const int32_t* __restrict__ txt_len, PrefillDims p, float scale_log2e,
     float2* __restrict__ partial, float* __restrict__ cstat, bf16x8* __restrict__ qfrag, int32_t* __restrict__ mv_eff)
 {
     using T = LdsRows<KS>;
-    constexpr int TW = 4 / NBW;                       // key tiles per step, one per tile lane
+    // NBW wave columns (one 32-row text block each) x TW tile lanes (one 32-key tile of a step each): four waves,
+    // or eight (NBW = 4, TW = 2) where one block then covers what two chunk blocks would and their statistics meet
+    // in LDS instead of in a separate kernel
+    constexpr int NW = NBW * TW;
     constexpr int S = TW == 1 ? 4 : 3;                // LDS slots
     constexpr int SLOT_ROWS = 32 * TW, SLOT_BYTES = SLOT_ROWS * T::ROWB;
-    constexpr int NLW = SLOT_ROWS / T::RPL / 4;       // load instructions per wave and step
+    constexpr int NLW = SLOT_ROWS / T::RPL / NW;      // load instructions per wave and step
     constexpr int QBYTES = NBW * 32 * T::ROWB;        // the block's query tiles during the prologue (one per wave column)
     __shared__ __attribute__((aligned(1024))) char s_k[S * SLOT_BYTES];
     __shared__ __attribute__((aligned(1024))) char s_q[QBYTES];
-    __shared__ float s_m[4][32], s_z[4][32];
-    __shared__ int s_last[4];
+    __shared__ float s_m[NW][32], s_z[NW][32];
+    __shared__ int s_last[NW];
     const int lane = lane_id(), wv = wave_id();
     const int nbw = wv % NBW, tw = wv / NBW;
     const int ch = blockIdx.x % p.nch, tg = blockIdx.x / p.nch, h = blockIdx.y, b = blockIdx.z;
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
         const int row0 = step_row0(g);
 #pragma unroll
         for (int t = 0; t < NLW; ++t) {
-            const int sr = (t * 4 + wv) * T::RPL;
+            const int sr = (t * NW + wv) * T::RPL;
             T::issue(rk, krow, row0 + (row0 + sr >= Me ? jump : 0), sr, slot, lane, true);
         }
     };
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
             T::issue(rq, (uint32_t)(p.q.token * 2), i0, t * T::RPL, s_q + nbw * 32 * T::ROWB, lane, true);
     }
     if (vb) {
-        const int last = wave_max_int(last_set_partial(vb, p.Mv, threadIdx.x, 256));
+        const int last = wave_max_int(last_set_partial(vb, p.Mv, threadIdx.x, 64 * NW));
         if (lane == 0) s_last[wv] = last;
     }
     uint32_t vismasks = key_valid_masks(0);           // (its loads belong to the same round trip)
@@ -344,7 +347,10 @@ __global__ __launch_bounds__(256) void prefill_rowstats_kernel(
     read_query_frags<KS>(i0, tl, s_q + nbw * 32 * T::ROWB, lane, qf);
     if (vb) {
         const int nit_guess = nit;
-        Me = effective_rows(max(max(s_last[0], s_last[1]), max(s_last[2], s_last[3])), p.Mv);
+        int last = s_last[0];
+#pragma unroll
+        for (int w2 = 1; w2 < NW; ++w2) last = max(last, s_last[w2]);
+        Me = effective_rows(last, p.Mv);
         plan();
         if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) mv_eff[b] = Me;   // for the second sweep
         const int ahead = min(S - 1, max(nit, nit_guess));
@@ -1131,7 +1137,7 @@ struct PrefillWorkspace {
 
 
 // Launch shapes of the two sweeps; pure host arithmetic shared by the workspace size and the launch.
-struct ScorePlan { int nbt, nbw, ng, nch, chunk; ColPlan col; int occ; };
+struct ScorePlan { int nbt, nbw, ng, nch, chunk, rs_waves; ColPlan col; int occ; };
 constexpr int kNumCU = 256;                          // MI355X
 
 ScorePlan plan_scores(int B, int Mv, int N, int H) {
@@ -1143,6 +1149,10 @@ ScorePlan plan_scores(int B, int Mv, int N, int H) {
     // four units per chunk
     const int units = (Mv + N + 127) / 128;
     int nch = (MD_RS_BLOCKS + B * H * s.ng - 1) / (B * H * s.ng);
+    // four text blocks and two chunks per (sample, head): one block of eight waves takes both halves instead
+    // (same number of waves on the chip, the halves' statistics meet in LDS, no merge kernel)
+    s.rs_waves = 4;
+    if (s.nbw == 4 && nch == 2) { s.rs_waves = 8; nch = 1; }
     if (nch > units / 4) nch = units / 4;
     if (nch < 1) nch = 1;
     if (nch > kMaxChunks) nch = kMaxChunks;
@@ -1190,12 +1200,13 @@ int launch_scores(const PrefillDims& p, const ScorePlan& s, const PrefillWorkspa
     const uint16_t* kp = static_cast<const uint16_t*>(k);
     if (!row_lse) {
         dim3 g1(p.nch * s.ng, p.H, p.B);
-#define MD_ROWSTATS(NBW_)                                                                                      \
-        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW_, KS>), g1, 256, 0,                    \
+#define MD_ROWSTATS(NBW_, TW_)                                                                                 \
+        MD_LAUNCH("prefill_rowstats", st, (prefill_rowstats_kernel<NBW_, TW_, KS>), g1, 64 * NBW_ * TW_, 0,   \
             qp, kp, vis_valid, txt_len, p, scale_log2e, w.partial, w.cstat, w.qfrag, w.mv_eff)
-        if (s.nbw == 1) MD_ROWSTATS(1);
-        else if (s.nbw == 2) MD_ROWSTATS(2);
-        else MD_ROWSTATS(4);
+        if (s.nbw == 1) MD_ROWSTATS(1, 4);
+        else if (s.nbw == 2) MD_ROWSTATS(2, 2);
+        else if (s.rs_waves == 8) MD_ROWSTATS(4, 2);
+        else MD_ROWSTATS(4, 1);
 #undef MD_ROWSTATS
         if (p.nch > 1) {
             const long n = (long)p.B * p.H * p.Npad;
