@@ -1160,7 +1160,9 @@ ScorePlan plan_scores(int B, int Mv, int N, int H) {
     s.chunk = upc * 128;
     s.nch = (units + upc - 1) / upc;
     // sweep 2: a persistent grid; units of (128 keys, one head), at least four per block
-    s.occ = 2;                                        // blocks per CU the kernel's register budget allows
+    // blocks per CU: two where a block holds four text blocks (the long form needs the second block to cover its
+    // waits); one for the shorter forms, measured faster there (fewer, longer runs: fewer pieces, fewer prologues)
+    s.occ = s.nbw == 4 ? 2 : 1;
     ColPlan& c = s.col;
     c.nkg = (Mv + kColKeys - 1) / kColKeys;
     c.U = (long)B * c.nkg * H;
