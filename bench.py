@@ -142,10 +142,9 @@ class Pipeline:
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
 # The runs and the raw figures are in profiles/hbm_traffic_cfg3_llavanext_b8.txt.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "prefill_colscore": 214528086, "prefill_rowstats": 182713650, "prefill_compact": 126029989,
-    "encode_scores": 97278868, "encode_emit": 84420301, "prefill_select": 51074379, "prefill_colfix": 42408103,
-    "decode_logits": 30648408, "decode_move": 28228608, "encode_decide": 2424928, "decode_select": 904474,
-    "prefill_cstat": 699392,
+    "prefill_colscore": 214266734, "prefill_rowstats": 173928637, "prefill_compact": 126029995,
+    "encode_scores": 97278177, "encode_emit": 84424331, "prefill_select": 51074392, "prefill_colfix": 42384633,
+    "decode_logits": 30648477, "decode_move": 28228608, "encode_decide": 2424928, "decode_select": 904465,
 }
 
 
