@@ -8,8 +8,8 @@
 //   prefill_rowstats_kernel  per (sample, head, key chunk): S = K Q^T on the MFMA units, online
 //                            (max, sum-exp) per text row -> row statistics (prefill_cstat_kernel
 //                            merges the chunks); with row_lse only prefill_qpack_kernel runs
-//   prefill_colscore_kernel  persistent blocks over units of (128 vision keys, one head): recompute
-//                            S, p = exp(s - m)/Z, accumulate the head mean a[i][j] of a 128-key tile
+//   prefill_colscore_kernel  persistent blocks over units of (64 or 128 vision keys, one head): recompute
+//                            S, p = exp(s - m)/Z, accumulate the head mean a[i][j] of such a key tile
 //                            in registers; a block's share of a tile is written as one piece
 //   prefill_colfix_kernel    sums a tile's pieces in a fixed order, column sum / max -> V_j, I_j
 // The N x Mv probability matrix of a head is never written to memory.
@@ -27,7 +27,6 @@ namespace md {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kColKeys = 128;                        // vision keys per unit of the column-score sweep
 constexpr int kMaxChunks = 8;                        // key chunks per (sample, head) in the row-statistics sweep, at most
 
 struct PrefillDims {
@@ -531,12 +530,15 @@ __global__ __launch_bounds__(256) void prefill_qpack_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Sweep 2: head-mean probabilities.  The work is cut into units (128 vision keys of a sample, one head);
+// Sweep 2: head-mean probabilities.  The work is cut into units (kb vision keys of a sample, one head; kb = 64,
+// or 128 with a single text block: smaller key groups mean smaller pieces and less to hand over, at the price of
+// the query fragments being fetched from L2 more often per K byte; 64 measured best where a block holds two or
+// four text blocks, 32 worse);
 // a persistent grid of P blocks (one or two per CU) takes equal, contiguous runs of units
 // [p*U/P, (p+1)*U/P), ordered (sample, key group, head), whatever the shape: no block count has to
-// match the chip.  A block of 4 waves holds a [128 keys x 32*NBW text rows] tile of a[i][j] in
+// match the chip.  A block of 4 waves holds a [kb keys x 32*NBW text rows] tile of a[i][j] in
 // registers (wave w: text block w % NBW, the KT key tiles of tile lane w / NBW) and adds one head's
-// probabilities per unit.  Per unit the 128 K rows go global -> registers -> LDS (two slots; the rows
+// probabilities per unit.  Per unit the kb K rows go global -> registers -> LDS (two slots; the rows
 // of unit u+2 are requested while unit u is worked on), the wave's text-query fragments come from
 // qfrag (coalesced).  The row statistics are folded into one constant per (head, text row):
 // p = exp2(s*scale*log2e + c), c = -m - log2(Z*H) (cstat: from sweep 1, or from the caller's
@@ -545,7 +547,7 @@ __global__ __launch_bounds__(256) void prefill_qpack_kernel(
 // "piece" (fp32, key-major); prefill_colfix_kernel adds a key group's pieces in a fixed order and
 // reduces over the text rows (Eq. 8 / Eq. 10).  Which block holds which piece is a function of the
 // shapes alone, so the result does not depend on timing.
-struct ColPlan { int P; long U; int nkg; int Gmax; };
+struct ColPlan { int P; long U; int nkg; int Gmax; int kb; };   // kb: vision keys per unit (a power of two)
 
 __host__ __device__ __forceinline__ int unit_block(long u, int P, long U) { return (int)(((u + 1) * P - 1) / U); }
 
@@ -554,11 +556,11 @@ __host__ __device__ __forceinline__ int unit_block(long u, int P, long U) { retu
 // Fewer units than the host planned for means fewer blocks at work only where a key group would
 // otherwise be cut into more pieces than the workspace holds (Gmax).
 struct ColRun { long U; int P; int tile0; int nk; };
-__device__ __forceinline__ int key_groups(int rows) { return (rows + kColKeys - 1) / kColKeys; }
+__device__ __forceinline__ int key_groups(int rows, int kb) { return (rows + kb - 1) / kb; }
 __device__ __forceinline__ ColRun effective_run(const int32_t* __restrict__ mv_eff, int B, int H, ColPlan cp, int bq) {
     int tiles = 0, tile0 = 0, nk = 0;
     for (int b = 0; b < B; ++b) {
-        const int n = key_groups(mv_eff[b]);
+        const int n = key_groups(mv_eff[b], cp.kb);
         if (b == bq) { tile0 = tiles; nk = n; }
         tiles += n;
     }
@@ -580,7 +582,7 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
     const int32_t* __restrict__ mv_eff, PrefillDims p, ColPlan cp, float scale_log2e, int tgrp, float* __restrict__ apart)
 {
     constexpr int TW = 4 / NBW;
-    constexpr int KB = 32 * TW * KT;                  // keys per unit (128)
+    constexpr int KB = 32 * TW * KT;                  // keys per unit (= cp.kb)
     constexpr int CH = 2 * KS;                        // 16-byte chunks per row
     constexpr int PITCH = CH * 16 + 16;               // padded row pitch: conflict-free 128-bit accesses
     constexpr int SLOT_BYTES = KB * PITCH;
@@ -616,7 +618,7 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
         int first = 0;
         x.b = 0; x.kg = 0; x.nk = 1;
         for (int b = 0; b < p.B; ++b) {
-            const int n = key_groups(mv_eff[b]);
+            const int n = key_groups(mv_eff[b], KB);
             if (x.t >= first && x.t < first + n) { x.b = b; x.kg = x.t - first; x.nk = n; }
             first += n;
         }
@@ -628,7 +630,7 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
             ++x.t;
             if (++x.kg == x.nk) {
                 x.kg = 0;
-                do { ++x.b; x.nk = x.b < p.B ? key_groups(mv_eff[x.b]) : 1; } while (x.nk == 0);
+                do { ++x.b; x.nk = x.b < p.B ? key_groups(mv_eff[x.b], KB) : 1; } while (x.nk == 0);
             }
         }
     };
@@ -761,8 +763,8 @@ __global__ __launch_bounds__(256) void prefill_colfix_kernel(
     if (j0 >= p.Mv) return;
     const ColRun run = effective_run(mv_eff, p.B, p.H, cp, b);
     // keys behind the rows that matter: no pieces were written, their scores are zero
-    const bool skipped = j0 / kColKeys >= run.nk;
-    const long tile = run.tile0 + j0 / kColKeys;
+    const bool skipped = j0 / cp.kb >= run.nk;
+    const long tile = run.tile0 + j0 / cp.kb;
     const int npieces = skipped ? 0 : unit_block(tile * p.H + p.H - 1, run.P, run.U) - unit_block(tile * p.H, run.P, run.U) + 1;
     float s[kFixKeys], mx[kFixKeys];
 #pragma unroll
@@ -1159,13 +1161,15 @@ ScorePlan plan_scores(int B, int Mv, int N, int H) {
     const int upc = (units + nch - 1) / nch;
     s.chunk = upc * 128;
     s.nch = (units + upc - 1) / upc;
-    // sweep 2: a persistent grid; units of (128 keys, one head), at least four per block
-    // blocks per CU: two where a block holds four text blocks (the long form needs the second block to cover its
-    // waits); one for the shorter forms, measured faster there (fewer, longer runs: fewer pieces, fewer prologues)
-    s.occ = s.nbw == 4 ? 2 : 1;
+    // sweep 2: a persistent grid; units of (kb keys, one head), at least four per block
     ColPlan& c = s.col;
-    c.nkg = (Mv + kColKeys - 1) / kColKeys;
+    c.kb = s.nbw == 1 ? 128 : 64;
+    c.nkg = (Mv + c.kb - 1) / c.kb;
     c.U = (long)B * c.nkg * H;
+    // blocks per CU: two where a block holds four text blocks (the second block covers the first one's waits),
+    // and with two text blocks when the runs stay long enough (20 units per CU); otherwise one (fewer, longer
+    // runs: fewer pieces, fewer prologues; measured faster there)
+    s.occ = s.nbw == 4 || (s.nbw == 2 && c.U >= 20L * kNumCU) ? 2 : 1;
     long P = (c.U + 3) / 4;
     if (P > kNumCU * s.occ) P = kNumCU * s.occ;
     if (P < 1) P = 1;
@@ -1223,9 +1227,10 @@ int launch_scores(const PrefillDims& p, const ScorePlan& s, const PrefillWorkspa
 #define MD_COLSCORE(NBW_, KT_)                                                                                 \
         MD_LAUNCH("prefill_colscore", st, (prefill_colscore_kernel<NBW_, KT_, KS>), s.col.P, 256, 0,           \
             w.qfrag, kp, w.cstat, w.mv_eff, p, s.col, scale_log2e, tg, w.apart)
+        // 32 * (4 / NBW) * KT keys per unit = s.col.kb
         if (s.nbw == 1) MD_COLSCORE(1, 1);
-        else if (s.nbw == 2) MD_COLSCORE(2, 2);
-        else MD_COLSCORE(4, 4);
+        else if (s.nbw == 2) MD_COLSCORE(2, 1);
+        else MD_COLSCORE(4, 2);
 #undef MD_COLSCORE
     }
     const int fx = (p.Mv + 4 * kFixKeys - 1) / (4 * kFixKeys);          // four waves of kFixKeys keys per block
