@@ -142,9 +142,9 @@ class Pipeline:
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
 # The runs and the raw figures are in profiles/hbm_traffic_cfg3_llavanext_b8.txt.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "prefill_colscore": 214266734, "prefill_rowstats": 173928637, "prefill_compact": 126029995,
-    "encode_scores": 97278177, "encode_emit": 84424331, "prefill_select": 51074392, "prefill_colfix": 42384633,
-    "decode_logits": 30648477, "decode_move": 28228608, "encode_decide": 2424928, "decode_select": 904465,
+    "prefill_colscore": 203617737, "prefill_rowstats": 173924529, "prefill_compact": 126029997,
+    "encode_scores": 97272864, "encode_emit": 84416481, "prefill_select": 51074353, "decode_logits": 30653008,
+    "decode_move": 28228608, "prefill_colfix": 26057767, "encode_decide": 2424928, "decode_select": 904454,
 }
 
 
