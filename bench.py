@@ -7,7 +7,9 @@ One "step" = one pass of the whole path over one batch of a synthetic workload:
 
 chained on the device (out_valid / out_is_key feed the prefill stage; its compacted K/V, out_len,
 out_protect and out_ids are the decode stage's cache state).  Inputs are seeded synthetic tensors
-resident in HBM before the timed region.  Prints ONE JSON line.
+resident in HBM before the timed region.  Successive steps take turns on several sets of buffers (about
+1 GB in all), as a job working through a stream of batches would: no step finds its inputs in the 256 MB
+Infinity Cache (`same_buffers` gives the figures of the step repeated on one set).  Prints ONE JSON line.
 
 The headline (`value`, `roofline`, `cpu_baseline`) is the largest prefill workload, the high-resolution
 LLaVA-NeXT shape (batch 8 x 2880 vision tokens, 128 text tokens).  The same line carries one block per
@@ -21,6 +23,7 @@ the HBM roofline on the stage's algorithmic bytes, and the MFMA rate of the scor
 from __future__ import annotations
 
 import argparse
+import copy
 import json
 import os
 import sys
@@ -122,6 +125,23 @@ class Pipeline:
         self.prefill()
         self.decode()
 
+    _DEVICE_TENSORS = ("x", "q_cls", "k_cls", "q_txt", "k", "v", "hidden", "q_dec", "acc")
+
+    def clone(self):
+        """A further set of the device buffers that carry data (inputs, outputs, decode state) with the same
+        contents; the workspaces are shared, as a job that allocates them once would have it."""
+        q = copy.copy(self)
+        for name in self._DEVICE_TENSORS:
+            setattr(q, name, getattr(self, name).clone())
+        q.enc_out = {k: (v.clone() if v is not None else None) for k, v in self.enc_out.items()}
+        q.pre_out = {k: (v.clone() if v is not None else None) for k, v in self.pre_out.items()}
+        return q
+
+    def device_bytes(self):
+        ts = [getattr(self, n) for n in self._DEVICE_TENSORS]
+        ts += [v for v in self.enc_out.values() if v is not None] + [v for v in self.pre_out.values() if v is not None]
+        return sum(t.numel() * t.element_size() for t in ts)
+
     def make_row_lse(self):
         """What the layer's attention kernel would hand over (Sec. 3.4): per head and text row, the natural-log
         sum of exp(scale * q.k) over the valid vision keys and the text keys 0..i.  Plain torch: an INPUT of the
@@ -135,6 +155,25 @@ class Pipeline:
             mask = torch.cat([valid[b][None, :].expand(c.N, c.M), causal], dim=1)
             out[b] = torch.logsumexp(lg.masked_fill(~mask[None], float("-inf")), dim=-1)
         self.row_lse = out
+
+
+class Rotation:
+    """Several sets of a workload's data buffers taken in turn, about 1 GB in all (four times the 256 MB Infinity
+    Cache): a call finds none of its inputs, and nothing an earlier call on the same set wrote, in a cache.
+    That is what a job that works through a stream of batches sees; repeating the step on ONE set of
+    buffers lets part of the inputs survive in the cache from step to step (reported as `same_buffers`)."""
+
+    def __init__(self, pipe, total_bytes=1 << 30):
+        n = int(min(16, max(2, -(-total_bytes // max(pipe.device_bytes(), 1)))))
+        self.pipes = [pipe] + [pipe.clone() for _ in range(n - 1)]
+        self.n, self.i = n, 0
+
+    def each(self, f):
+        def g():
+            p = self.pipes[self.i % self.n]
+            self.i += 1
+            f(p)
+        return g
 
 
 # HBM bytes per launch of the headline workload's kernels, from two rocprofv3 --pmc runs of this script
@@ -223,17 +262,25 @@ def frac(nbytes, us):
 
 
 def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceiling=False):
-    """One prefill workload: the chained step, its stages, its kernels, the with-LSE variant, cold inputs."""
+    """One prefill workload: the chained step, its stages, its kernels and the with-LSE variant, each call on the
+    next of several sets of buffers (see Rotation), and the step on one set of buffers for comparison."""
     pipe = Pipeline(cfg, torch, md, harness)
-    for _ in range(warmup):
-        pipe.step()
-    step_ms = timed(torch, pipe.step, steps)
-    enc_ms = timed(torch, pipe.encode, steps)
-    pre_ms = timed(torch, pipe.prefill, steps)
-    pipe.prefill()
-    dec_ms = timed(torch, lambda: (pipe.prefill(), pipe.decode()), steps) - pre_ms
-    k_us, k_calls = profile_steps(binding, pipe.step, steps)
+    rot = Rotation(pipe)
+    step = rot.each(lambda p: p.step())
+    for _ in range(max(warmup, rot.n)):
+        step()
+    step_ms = timed(torch, step, steps)
+    enc_ms = timed(torch, rot.each(lambda p: p.encode()), steps)
+    pre_ms = timed(torch, rot.each(lambda p: p.prefill()), steps)
+    dec_ms = timed(torch, rot.each(lambda p: (p.prefill(), p.decode())), steps) - pre_ms
+    k_us, k_calls = profile_steps(binding, step, steps)
     torch.cuda.synchronize()
+    # the same on one set of buffers, for comparison
+    for _ in range(3):
+        pipe.step()
+    same = {"us_per_step": round(timed(torch, pipe.step, steps) * 1e3, 2),
+            "encode_us": round(timed(torch, pipe.encode, steps) * 1e3, 2),
+            "prefill_us": round(timed(torch, pipe.prefill, steps) * 1e3, 2)}
 
     out_count = pipe.enc_out["out_count"].cpu().numpy()
     kept = np.minimum(pipe.pre_out["kept_count"].cpu().numpy(), pipe.R)
@@ -251,11 +298,16 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
 
     # the same prefill call with the attention kernel's row normalisers handed over (one sweep over K)
     pipe.make_row_lse()
+    for q in rot.pipes:
+        q.row_lse = pipe.row_lse
     pipe.prefill(with_lse=True)
     torch.cuda.synchronize()
-    same = bool((pipe.pre_out["kept_index"] == kept_index).all())
-    lse_ms = timed(torch, lambda: pipe.prefill(with_lse=True), steps)
-    lse_us, _ = profile_steps(binding, lambda: pipe.prefill(with_lse=True), steps)
+    same_sel = bool((pipe.pre_out["kept_index"] == kept_index).all())
+    with_lse = rot.each(lambda p: p.prefill(with_lse=True))
+    for _ in range(rot.n):
+        with_lse()
+    lse_ms = timed(torch, with_lse, steps)
+    lse_us, _ = profile_steps(binding, with_lse, steps)
     torch.cuda.synchronize()
     pipe.prefill()
 
@@ -309,8 +361,10 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
         "prefill_with_lse": {"us": round(lse_ms * 1e3, 2), "score_us": round(lse_score_us, 2),
                              "score_frac_of_hbm_peak": frac(sb["prefill_score"], lse_score_us),
                              "kernels_us": {n: round(u, 2) for n, u in lse_us.items()},
-                             "same_selection_as_without": same},
+                             "same_selection_as_without": same_sel},
+        "buffer_sets": rot.n, "buffer_set_MB": round(pipe.device_bytes() / 1e6, 1), "same_buffers": same,
     }
+    del rot
     return pipe, block, step_ms
 
 
@@ -462,36 +516,6 @@ def static_handoff(torch, md, binding, cfg, layers=32, kept_vision=64, reps=10, 
             "move_GBps": round(move_bytes / (us.get("decode_move", 1e9) * 1e-6) / 1e9, 1)}
 
 
-def cold_vs_warm(torch, pipe, iters=48):
-    """Stage times with the inputs rotating over several distinct copies (more than the 256 MB Infinity Cache
-    in total: every call finds its inputs in HBM) against the same call repeated on one set."""
-    out = {}
-    state = {"i": 0}
-    for stage, names, fn in (("encode", ("x", "q_cls", "k_cls"), pipe.encode), ("prefill", ("q_txt", "k", "v", "hidden"), pipe.prefill)):
-        orig = {n: getattr(pipe, n) for n in names}
-        mb = sum(t.numel() * t.element_size() for t in orig.values()) / 1e6
-        sets = int(min(16, max(2, np.ceil(600.0 / mb))))
-        copies = [orig] + [{n: t.clone() for n, t in orig.items()} for _ in range(sets - 1)]
-
-        def rotating():
-            for n, t in copies[state["i"] % sets].items():
-                setattr(pipe, n, t)
-            state["i"] += 1
-            fn()
-
-        for _ in range(sets):
-            rotating()
-        cold = timed(torch, rotating, iters)
-        for n, t in orig.items():
-            setattr(pipe, n, t)
-        fn()
-        warm = timed(torch, fn, iters)
-        out[stage] = {"warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2), "input_MB_per_set": round(mb, 1),
-                      "sets": sets}
-        del copies
-    return out
-
-
 def variable_length(torch, md, cfg, pipe):
     """The printed threshold forms end to end (Eq. 7 with mu = mean + lambda*std; Eq. 9-10 with gamma and
     alpha scaled jointly by bisection until the mean kept count is near Table 3's prefill average of 64):
@@ -630,7 +654,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the chained-prefill, hand-off, cold-input and threshold extras")
+    ap.add_argument("--no-extras", action="store_true", help="skip the chained-prefill, hand-off and threshold extras")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) to scale rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -671,8 +695,6 @@ def main():
                    "step": "encode_merge -> prefill_filter -> decode_evict"},
         "stages": head["stages"], "counts": head["counts"], "roofline": head["roofline"], "kernels": head["kernels"],
     }
-    if not args.no_extras:
-        head["cold_vs_warm"] = cold_vs_warm(torch, pipe)
     if not args.no_parity:
         result["parity"] = parity_check(cfg, pipe, harness)
     if not args.no_cpu_baseline:
@@ -691,14 +713,12 @@ def main():
             continue
         c = wl.CONFIGS[n]
         p2, blk, _ = measure_workload(torch, md, binding, harness, c, steps_other, args.warmup)
-        if not args.no_extras:
-            blk["cold_vs_warm"] = cold_vs_warm(torch, p2)
-            if n == 2:                                   # the extras that are defined on the batch-16 LLaVA-1.5 shape
-                blk["progressive_prefill"] = progressive_prefill(torch, md, harness, c, p2)
-                blk["variable_length"] = variable_length(torch, md, c, p2)
-                blk["static_handoff"] = static_handoff(torch, md, binding, c)
-                blk["static_handoff_video"] = static_handoff(torch, md, binding, c, B=8, M=2048, kept_vision=1024,
-                                                             reps=5, name="video_8x256_keep_half")
+        if not args.no_extras and n == 2:                # the extras that are defined on the batch-16 LLaVA-1.5 shape
+            blk["progressive_prefill"] = progressive_prefill(torch, md, harness, c, p2)
+            blk["variable_length"] = variable_length(torch, md, c, p2)
+            blk["static_handoff"] = static_handoff(torch, md, binding, c)
+            blk["static_handoff_video"] = static_handoff(torch, md, binding, c, B=8, M=2048, kept_vision=1024,
+                                                         reps=5, name="video_8x256_keep_half")
         blocks[c.name] = blk
         del p2
         torch.cuda.empty_cache()

@@ -613,12 +613,13 @@ __global__ __launch_bounds__(256) void decode_move_kernel(
             const bool two = c2 < rv;
             auto ld = [](const u32x4* q) { return STREAM_ONCE ? __builtin_nontemporal_load(q) : *q; };
             auto st = [](u32x4* q, const u32x4& v) { if (STREAM_ONCE) __builtin_nontemporal_store(v, q); else *q = v; };
-            const u32x4 k0 = ld(k_cache + src + c), v0 = ld(v_cache + src + c);
+            // the V rows are not read on this path at all (only moved): always streamed
+            const u32x4 k0 = ld(k_cache + src + c), v0 = __builtin_nontemporal_load(v_cache + src + c);
             u32x4 k1 = k0, v1 = v0;
-            if (two) { k1 = ld(k_cache + src + c2); v1 = ld(v_cache + src + c2); }
+            if (two) { k1 = ld(k_cache + src + c2); v1 = __builtin_nontemporal_load(v_cache + src + c2); }
             st(k_cache + dst + c, k0);
-            st(v_cache + dst + c, v0);
-            if (two) { st(k_cache + dst + c2, k1); st(v_cache + dst + c2, v1); }
+            __builtin_nontemporal_store(v0, v_cache + dst + c);
+            if (two) { st(k_cache + dst + c2, k1); __builtin_nontemporal_store(v1, v_cache + dst + c2); }
         }
     }
 }

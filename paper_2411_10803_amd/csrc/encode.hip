@@ -71,6 +71,7 @@ template <> struct Vec<false> {
     // a vector as loaded, and the dot product of two of them added to acc (elements in ascending order)
     using Raw = f32x4;
     __device__ static __forceinline__ Raw load_raw(const void* row, int c) { return *reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c); }
+    __device__ static __forceinline__ Raw load_raw_once(const void* row, int c) { return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(static_cast<const float*>(row) + c)); }
     __device__ static __forceinline__ Raw zero() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
     __device__ static __forceinline__ float dot(const Raw& a, const Raw& b, float acc) {
         acc = fmaf(a.x, b.x, acc); acc = fmaf(a.y, b.y, acc); acc = fmaf(a.z, b.z, acc); return fmaf(a.w, b.w, acc);
@@ -97,6 +98,7 @@ template <> struct Vec<true> {
     using Raw = u32x4;
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     __device__ static __forceinline__ Raw load_raw(const void* row, int c) { return *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c); }
+    __device__ static __forceinline__ Raw load_raw_once(const void* row, int c) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(row) + c)); }
     __device__ static __forceinline__ Raw zero() { return u32x4{0u, 0u, 0u, 0u}; }
     __device__ static __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
         return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
@@ -202,7 +204,9 @@ __device__ __forceinline__ void cls_logits_rows(
             typename Vec<BF>::Raw kv[R];
             const typename Vec<BF>::Raw qv = Vec<BF>::load_raw(qrow, ic * VEC);
 #pragma unroll
-            for (int r = 0; r < R; ++r) kv[r] = Vec<BF>::load_raw(krow[r], ic * VEC);
+            // the key rows are read exactly once: streaming loads, so that they do not push x (read again by
+            // the emit kernel) out of the Infinity Cache
+            for (int r = 0; r < R; ++r) kv[r] = Vec<BF>::load_raw_once(krow[r], ic * VEC);
 #pragma unroll
             for (int r = 0; r < R; ++r)
                 if (act[r] && idx < nvec) part_r[r] = Vec<BF>::dot(qv, kv[r], part_r[r]);

@@ -642,7 +642,9 @@ __global__ __launch_bounds__(256, 2) void prefill_colscore_kernel(
 #pragma unroll
         for (int t = 0; t < NLW; ++t) {
             const int row = live ? min(x.kg * KB + (t * 4 + wv) * RPL + lane / CH, p.Mv - 1) : 0;
-            st[t] = *reinterpret_cast<const u32x4*>(kb + (long)row * tok_stride);
+            // the last read of these rows (sweep 1 read them with plain loads, so part of them is still in the
+            // Infinity Cache): streaming loads, which leave the cache to data that is used again
+            st[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (long)row * tok_stride));
         }
     };
     auto store_k = [&](int slot, const u32x4 (&st)[NLW]) {
@@ -782,8 +784,8 @@ __global__ __launch_bounds__(256) void prefill_colfix_kernel(
 #pragma unroll
             for (int q = 0; q < kFixKeys; ++q) {
                 const float* ap = apart + g * gstride + ((long)b * p.Mv + min(j0 + q, p.Mv - 1)) * p.Npad;
-                x0[q] = ap[ca];
-                x1[q] = ap[cb];
+                x0[q] = __builtin_nontemporal_load(ap + ca);       // a piece is read once
+                x1[q] = __builtin_nontemporal_load(ap + cb);
             }
 #pragma unroll
             for (int q = 0; q < kFixKeys; ++q) { a0[q] += x0[q]; a1[q] += x1[q]; }
@@ -947,9 +949,10 @@ __device__ __forceinline__ void copy_text_rows(
     for (int c = c0; c < kv; c += 256) {
         const u32x4 a = __builtin_nontemporal_load(tr.k + src * kv + c), a2 = __builtin_nontemporal_load(tr.v + src * kv + c);
         tr.k_out[dst * kv + c] = a;
-        tr.v_out[dst * kv + c] = a2;
+        __builtin_nontemporal_store(a2, tr.v_out + dst * kv + c);          // streaming stores: see prefill_compact_kernel
     }
-    for (int c = c0; c < hv; c += 256) tr.hidden_out[dst * hv + c] = __builtin_nontemporal_load(tr.hidden + src * hv + c);
+    for (int c = c0; c < hv; c += 256)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(tr.hidden + src * hv + c), tr.hidden_out + dst * hv + c);
 }
 
 template <int IPT>
@@ -1075,8 +1078,13 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
     u32x4* vd = v_out + ((long)b * rows_cap + o) * kv;
     // every source row is read once (streaming loads; the copies are read again by the next stage),
     // four vectors in flight
+    // hidden and V rows are written with streaming stores: nothing on this path reads them again, and left as
+    // dirty lines in the Infinity Cache they would be written back in the middle of whatever kernel streams
+    // through it next (measured: the sweep that follows 150 MB of plain stores takes 10 us longer); the K
+    // rows, which a scoring pass reads next, keep plain stores
+    auto put = [](u32x4* q, const u32x4& v, bool nt) { if (nt) __builtin_nontemporal_store(v, q); else *q = v; };
     auto copy2 = [&](const u32x4* __restrict__ s0, u32x4* __restrict__ d0, const u32x4* __restrict__ s1,
-                     u32x4* __restrict__ d1, int n) {
+                     u32x4* __restrict__ d1, int n, bool nt0, bool nt1) {
         const int step = 2 * blockDim.x;
         for (int c = threadIdx.x; c < n; c += step) {
             const int c2 = c + blockDim.x;
@@ -1084,14 +1092,14 @@ __global__ __launch_bounds__(256) void prefill_compact_kernel(
             const u32x4 a0 = __builtin_nontemporal_load(s0 + c), a1 = __builtin_nontemporal_load(s1 + c);
             u32x4 b0 = a0, b1 = a1;
             if (two) { b0 = __builtin_nontemporal_load(s0 + c2); b1 = __builtin_nontemporal_load(s1 + c2); }
-            d0[c] = a0;
-            d1[c] = a1;
-            if (two) { d0[c2] = b0; d1[c2] = b1; }
+            put(d0 + c, a0, nt0);
+            put(d1 + c, a1, nt1);
+            if (two) { put(d0 + c2, b0, nt0); put(d1 + c2, b1, nt1); }
         }
     };
-    copy2(ks, kd, vs, vd, kv);
+    copy2(ks, kd, vs, vd, kv, false, true);
     const int half = (hv + 1) / 2;                   // the hidden row as two halves
-    copy2(hs, hd, hs + half, hd + half, hv - half);
+    copy2(hs, hd, hs + half, hd + half, hv - half, true, true);
     if (hv & 1) {                                    // odd vector count: the first half has one more
         const int c = half - 1;
         if (threadIdx.x == 0) hd[c] = hs[c];
