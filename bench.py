@@ -176,14 +176,14 @@ class Rotation:
         return g
 
 
-# HBM bytes per launch of the headline workload's kernels, from two rocprofv3 --pmc runs of this script
+# HBM bytes per launch of the headline workload's kernels, from two rocprofv3 --pmc runs of this script (--step-only)
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same counters show for a plain
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
 # The runs and the raw figures are in profiles/hbm_traffic_cfg3_llavanext_b8.txt.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "prefill_colscore": 203617737, "prefill_rowstats": 173924529, "prefill_compact": 126029997,
-    "encode_scores": 97272864, "encode_emit": 84416481, "prefill_select": 51074353, "decode_logits": 30653008,
-    "decode_move": 28228608, "prefill_colfix": 26057767, "encode_decide": 2424928, "decode_select": 904454,
+    "prefill_colscore": 190553347, "prefill_rowstats": 173924668, "prefill_compact": 126029922,
+    "encode_scores": 96989373, "encode_emit": 84425702, "prefill_select": 51073328, "decode_logits": 30648471,
+    "decode_move": 28228608, "prefill_colfix": 26057733, "encode_decide": 2424928, "decode_select": 904431,
 }
 
 
@@ -261,7 +261,7 @@ def frac(nbytes, us):
     return round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None
 
 
-def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceiling=False):
+def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceiling=False, step_only=False):
     """One prefill workload: the chained step, its stages, its kernels and the with-LSE variant, each call on the
     next of several sets of buffers (see Rotation), and the step on one set of buffers for comparison."""
     pipe = Pipeline(cfg, torch, md, harness)
@@ -270,17 +270,25 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
     for _ in range(max(warmup, rot.n)):
         step()
     step_ms = timed(torch, step, steps)
-    enc_ms = timed(torch, rot.each(lambda p: p.encode()), steps)
-    pre_ms = timed(torch, rot.each(lambda p: p.prefill()), steps)
-    dec_ms = timed(torch, rot.each(lambda p: (p.prefill(), p.decode())), steps) - pre_ms
+    if not step_only:
+        enc_ms = timed(torch, rot.each(lambda p: p.encode()), steps)
+        pre_ms = timed(torch, rot.each(lambda p: p.prefill()), steps)
+        dec_ms = timed(torch, rot.each(lambda p: (p.prefill(), p.decode())), steps) - pre_ms
     k_us, k_calls = profile_steps(binding, step, steps)
     torch.cuda.synchronize()
-    # the same on one set of buffers, for comparison
-    for _ in range(3):
-        pipe.step()
-    same = {"us_per_step": round(timed(torch, pipe.step, steps) * 1e3, 2),
-            "encode_us": round(timed(torch, pipe.encode, steps) * 1e3, 2),
-            "prefill_us": round(timed(torch, pipe.prefill, steps) * 1e3, 2)}
+    same = None
+    if step_only:
+        # nothing but the chained step runs (a profiler then sees only its launches); a stage's time is the
+        # sum of its kernels' durations
+        stage_of = lambda pre: sum(us for n, us in k_us.items() if n.startswith(pre)) * 1e-3
+        enc_ms, pre_ms, dec_ms = stage_of("encode"), stage_of("prefill"), stage_of("decode")
+    else:
+        # the same on one set of buffers, for comparison
+        for _ in range(3):
+            pipe.step()
+        same = {"us_per_step": round(timed(torch, pipe.step, steps) * 1e3, 2),
+                "encode_us": round(timed(torch, pipe.encode, steps) * 1e3, 2),
+                "prefill_us": round(timed(torch, pipe.prefill, steps) * 1e3, 2)}
 
     out_count = pipe.enc_out["out_count"].cpu().numpy()
     kept = np.minimum(pipe.pre_out["kept_count"].cpu().numpy(), pipe.R)
@@ -297,19 +305,21 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
     kb, sb, flops = stage_bytes(cfg, pipe, counts)
 
     # the same prefill call with the attention kernel's row normalisers handed over (one sweep over K)
-    pipe.make_row_lse()
-    for q in rot.pipes:
-        q.row_lse = pipe.row_lse
-    pipe.prefill(with_lse=True)
-    torch.cuda.synchronize()
-    same_sel = bool((pipe.pre_out["kept_index"] == kept_index).all())
-    with_lse = rot.each(lambda p: p.prefill(with_lse=True))
-    for _ in range(rot.n):
-        with_lse()
-    lse_ms = timed(torch, with_lse, steps)
-    lse_us, _ = profile_steps(binding, with_lse, steps)
-    torch.cuda.synchronize()
-    pipe.prefill()
+    lse_ms, lse_us, same_sel = 0.0, {}, None
+    if not step_only:
+        pipe.make_row_lse()
+        for q in rot.pipes:
+            q.row_lse = pipe.row_lse
+        pipe.prefill(with_lse=True)
+        torch.cuda.synchronize()
+        same_sel = bool((pipe.pre_out["kept_index"] == kept_index).all())
+        with_lse = rot.each(lambda p: p.prefill(with_lse=True))
+        for _ in range(rot.n):
+            with_lse()
+        lse_ms = timed(torch, with_lse, steps)
+        lse_us, _ = profile_steps(binding, with_lse, steps)
+        torch.cuda.synchronize()
+        pipe.prefill()
 
     kernels = {}
     for name, us in k_us.items():
@@ -358,12 +368,16 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
         "us_per_step": round(step_ms * 1e3, 2), "vision_tokens_per_s": tps(step_ms),
         "step_algorithmic_MB": round(step_bytes / 1e6, 2), "step_frac_of_hbm_peak": frac(step_bytes, step_ms * 1e3),
         "stages": stages, "counts": counts, "kernels": kernels, "roofline": roofline,
-        "prefill_with_lse": {"us": round(lse_ms * 1e3, 2), "score_us": round(lse_score_us, 2),
-                             "score_frac_of_hbm_peak": frac(sb["prefill_score"], lse_score_us),
-                             "kernels_us": {n: round(u, 2) for n, u in lse_us.items()},
-                             "same_selection_as_without": same_sel},
-        "buffer_sets": rot.n, "buffer_set_MB": round(pipe.device_bytes() / 1e6, 1), "same_buffers": same,
+        "buffer_sets": rot.n, "buffer_set_MB": round(pipe.device_bytes() / 1e6, 1),
     }
+    if step_only:
+        block["stage_times"] = "sums of the stage's kernel durations (--step-only)"
+    else:
+        block["same_buffers"] = same
+        block["prefill_with_lse"] = {"us": round(lse_ms * 1e3, 2), "score_us": round(lse_score_us, 2),
+                                     "score_frac_of_hbm_peak": frac(sb["prefill_score"], lse_score_us),
+                                     "kernels_us": {n: round(u, 2) for n, u in lse_us.items()},
+                                     "same_selection_as_without": same_sel}
     del rot
     return pipe, block, step_ms
 
@@ -655,6 +669,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the chained-prefill, hand-off and threshold extras")
+    ap.add_argument("--step-only", action="store_true",
+                    help="run nothing but the chained step of the headline workload (for profiler runs: every launch "
+                         "the profiler sees belongs to the timed configuration)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) to scale rocprofv3 --pmc byte counters")
     args = ap.parse_args()
@@ -670,6 +687,9 @@ def main():
     from paper_2411_10803_amd import binding, harness
     md.library()
     want = sorted({int(x) for x in args.workloads.split(",") if x} | {HEADLINE})
+    if args.step_only:
+        want = [HEADLINE]
+        args.no_extras = args.no_parity = args.no_cpu_baseline = True
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -681,7 +701,8 @@ def main():
 
     # the headline first: its K timed steps after W warm-up steps are the figures of the contract
     cfg = wl.CONFIGS[HEADLINE]
-    pipe, head, ms_per_step = measure_workload(torch, md, binding, harness, cfg, args.steps, args.warmup, with_ceiling=True)
+    pipe, head, ms_per_step = measure_workload(torch, md, binding, harness, cfg, args.steps, args.warmup,
+                                               with_ceiling=not args.step_only, step_only=args.step_only)
     blocks = {cfg.name: head}
     result = {
         "metric": "vision tokens processed/sec per pipeline stage; achieved % of HBM/MFMA roofline",
