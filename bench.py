@@ -176,6 +176,42 @@ class Rotation:
         return g
 
 
+def two_batches_in_flight(torch, pipe, steps):
+    """Throughput with two batches in flight: successive steps go to two HIP streams in turn, as a job that works
+    through a stream of independent batches can issue them.  While one batch is in a kernel that occupies a few
+    CUs (the per-sample decision kernels) or in a launch gap, the other one's kernels have the chip.  Every
+    stream has its own workspaces and its own two sets of data buffers (taken in turn, as in Rotation)."""
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    lanes = []
+    for _ in streams:
+        sets = [pipe.clone(), pipe.clone()]
+        ws = (pipe.enc_ws.clone(), pipe.pre_ws.clone(), pipe.dec_ws.clone())
+        for q in sets:
+            q.enc_ws, q.pre_ws, q.dec_ws = ws
+        lanes.append(sets)
+    state = {"i": 0}
+
+    def step():
+        i = state["i"]
+        state["i"] += 1
+        with torch.cuda.stream(streams[i % 2]):
+            lanes[i % 2][(i // 2) % 2].step()
+
+    main = torch.cuda.current_stream()
+    for st in streams:
+        st.wait_stream(main)
+    for _ in range(8):
+        step()
+    ms = timed(torch, step, steps)                  # timed() synchronises the whole device on both sides
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    enqueue_us = (time.perf_counter() - t0) * 1e6 / steps
+    torch.cuda.synchronize()
+    return {"streams": 2, "us_per_step": round(ms * 1e3, 2), "vision_tokens_per_s": pipe.cfg.B * pipe.cfg.M / (ms * 1e-3),
+            "host_enqueue_us_per_step": round(enqueue_us, 1)}
+
+
 # HBM bytes per launch of the headline workload's kernels, from two rocprofv3 --pmc runs of this script (--step-only)
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same counters show for a plain
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
@@ -374,6 +410,8 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
         block["stage_times"] = "sums of the stage's kernel durations (--step-only)"
     else:
         block["same_buffers"] = same
+        if cfg.B > 1:
+            block["two_batches_in_flight"] = two_batches_in_flight(torch, pipe, steps)
         block["prefill_with_lse"] = {"us": round(lse_ms * 1e3, 2), "score_us": round(lse_score_us, 2),
                                      "score_frac_of_hbm_peak": frac(sb["prefill_score"], lse_score_us),
                                      "kernels_us": {n: round(u, 2) for n, u in lse_us.items()},

@@ -25,7 +25,9 @@
  *   - Return value: MD_OK or an error code.  Argument errors are detected on the host before any
  *     kernel is launched; mustdrop_last_error() returns a thread-local description.
  *   - `workspace` must hold at least mustdrop_<stage>_workspace_bytes(...) bytes, 256-byte aligned.
- *     Calls that share a workspace must be ordered on one stream.
+ *     Calls that share a workspace must be ordered on one stream.  Calls that share neither a
+ *     workspace nor an output or state buffer may overlap in time (several streams): a caller with
+ *     independent batches can keep two of them in flight.
  */
 #ifndef MUSTDROP_H
 #define MUSTDROP_H
