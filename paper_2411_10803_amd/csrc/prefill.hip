@@ -251,7 +251,9 @@ __global__ __launch_bounds__(64 * NBW * TW) void prefill_rowstats_kernel(
     // or eight (NBW = 4, TW = 2) where one block then covers what two chunk blocks would and their statistics meet
     // in LDS instead of in a separate kernel
     constexpr int NW = NBW * TW;
-    constexpr int S = TW == 1 ? 4 : 3;                // LDS slots
+    // LDS slots.  The eight-wave form runs with two (one step in flight while one is worked on): with more
+    // requests outstanding per CU the sweep gets slower, not faster, when K comes from HBM (46.3 against 47.9 us)
+    constexpr int S = TW == 1 ? 4 : (NW == 8 ? 2 : 3);
     constexpr int SLOT_ROWS = 32 * TW, SLOT_BYTES = SLOT_ROWS * T::ROWB;
     constexpr int NLW = SLOT_ROWS / T::RPL / NW;      // load instructions per wave and step
     constexpr int QBYTES = NBW * 32 * T::ROWB;        // the block's query tiles during the prologue (one per wave column)
