@@ -182,7 +182,7 @@ def batches_in_flight(torch, pipe, steps, n):
     CUs (the per-sample decision kernels) or in a launch gap, the others' kernels have the chip.  Every stream
     has its own workspaces and its own two sets of data buffers (taken in turn, as in Rotation).  Chains of equal
     length that start together stay in step with each other and gain nothing, so stream j starts once stream
-    j-1 has finished its first encode call."""
+    j-1 has finished its first prefill call."""
     streams = [torch.cuda.Stream() for _ in range(n)]
     lanes = []
     for _ in streams:
@@ -198,10 +198,10 @@ def batches_in_flight(torch, pipe, steps, n):
             with torch.cuda.stream(streams[j]):
                 if i < n - 1:                         # the first step of every stream but the last: stagger the next one
                     q.encode()
+                    q.prefill()
                     ev = torch.cuda.Event()
                     ev.record()
                     streams[j + 1].wait_event(ev)
-                    q.prefill()
                     q.decode()
                 else:
                     q.step()
