@@ -868,7 +868,9 @@ int decode_evict_impl(
         MD_LAUNCH("decode_select", st, (decode_select_kernel), B, 1024, lds,
             p, w.logits, decay, budget, acc, ids, protect, len, w.keep, w.holes, w.movers, w.n_move, evicted_ids, evicted_count);
     }
-    dim3 g3(32, B);
+    // blocks per sample: enough that a small batch still covers the chip and a block has one or two rows to move
+    const int move_x = B >= 32 ? 32 : (B >= 16 ? 64 : 128);
+    dim3 g3(move_x, B);
     if (dense && cache_bytes > (size_t)128 << 20)
         MD_LAUNCH("decode_move", st, (decode_move_kernel<true>), g3, 256, 0,
             p, w.holes, w.movers, w.n_move, static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache), 0l);
