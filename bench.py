@@ -799,6 +799,9 @@ def main():
                    "step": "encode_merge -> prefill_filter -> decode_evict"},
         "stages": head["stages"], "counts": head["counts"], "roofline": head["roofline"], "kernels": head["kernels"],
     }
+    for extra in ("same_buffers", "batches_in_flight"):   # beside `value`: the step on one set of buffers, and the
+        if extra in head:                                 # throughput with several batches in flight on several streams
+            result[extra] = head[extra]
     if not args.no_parity:
         result["parity"] = parity_check(cfg, pipe, harness)
     if not args.no_cpu_baseline:
