@@ -859,7 +859,10 @@ int decode_evict_impl(
     }
         if (ipt <= 1) { MD_SELECT_FAST_H(1) }
         else if (ipt <= 2) { MD_SELECT_FAST_H(2) }
+        else if (ipt <= 3) { MD_SELECT_FAST_H(3) }
         else if (ipt <= 4) { MD_SELECT_FAST_H(4) }
+        else if (ipt <= 5) { MD_SELECT_FAST_H(5) }
+        else if (ipt <= 6) { MD_SELECT_FAST_H(6) }
         else { MD_SELECT_FAST_H(8) }
 #undef MD_SELECT_FAST_H
 #undef MD_SELECT_FAST

@@ -1038,7 +1038,10 @@ int encode_merge_impl(
     do { if (ws <= 4) MD_DECIDE_FAST(IPT_, 4); else if (ws <= 8) MD_DECIDE_FAST(IPT_, 8); else MD_DECIDE_FAST(IPT_, 16); } while (0)
     if (fast_ok && M <= 1024) MD_DECIDE_FAST_WS(1);
     else if (fast_ok && M <= 2048) MD_DECIDE_FAST_WS(2);
+    else if (fast_ok && M <= 3072) MD_DECIDE_FAST_WS(3);     // e.g. five tiles of 24 x 24 tokens
     else if (fast_ok && M <= 4096) MD_DECIDE_FAST_WS(4);
+    else if (fast_ok && M <= 5120) MD_DECIDE_FAST_WS(5);     // e.g. eight frames of 24 x 24 tokens
+    else if (fast_ok && M <= 6144) MD_DECIDE_FAST_WS(6);
     else if (fast_ok) MD_DECIDE_FAST_WS(8);
     else
         MD_LAUNCH("encode_decide", st, (encode_decide_kernel), B, 1024, 0,

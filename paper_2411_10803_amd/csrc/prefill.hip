@@ -1344,7 +1344,10 @@ int prefill_filter_impl(
         src_row, kept_index, kept_count, out_len, out_protect, score_global, score_indiv, tr)
     if (Mv <= 1024) MD_PSELECT_FAST(1);
     else if (Mv <= 2048) MD_PSELECT_FAST(2);
+    else if (Mv <= 3072) MD_PSELECT_FAST(3);
     else if (Mv <= 4096) MD_PSELECT_FAST(4);
+    else if (Mv <= 5120) MD_PSELECT_FAST(5);
+    else if (Mv <= 6144) MD_PSELECT_FAST(6);
     else if (Mv <= 8192) MD_PSELECT_FAST(8);
     else
         MD_LAUNCH("prefill_select", st, (prefill_select_kernel), B, 1024, 0,
