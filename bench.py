@@ -228,9 +228,9 @@ def batches_in_flight(torch, pipe, steps, n):
 # 256 MiB device copy (FETCH_SIZE reads half the bytes moved: factor 2.0; WRITE_SIZE: factor 1.0).
 # The runs and the raw figures are in profiles/hbm_traffic_cfg3_llavanext_b8.txt.
 MEASURED_HBM_TRAFFIC_BYTES = {
-    "prefill_colscore": 190573405, "prefill_rowstats": 173920572, "prefill_compact": 126029899,
-    "encode_scores": 96990543, "encode_emit": 84431547, "prefill_select": 51074344, "decode_logits": 30648412,
-    "decode_move": 28228608, "prefill_colfix": 26057728, "encode_decide": 2424928, "decode_select": 904434,
+    "prefill_colscore": 190564186, "prefill_rowstats": 173929793, "prefill_compact": 126029887,
+    "encode_scores": 96988952, "encode_emit": 84443517, "prefill_select": 51057960, "decode_logits": 30648432,
+    "decode_move": 28310568, "prefill_colfix": 26057728, "encode_decide": 2399328, "decode_select": 901728,
 }
 
 
