@@ -78,3 +78,26 @@ def test_decode_general_kernels(H, d, L0):
     o["evicted_ids"], o["evicted_count"] = r["evicted_ids"], r["evicted_count"]
     check_decode(g, o, s0, cfg.decode_budget)
     assert np.all(g["len"] == cfg.decode_budget)
+
+
+@pytest.mark.parametrize("Hg,Wg", [(50, 54), (70, 80)])          # 2700 and 5600 vision tokens: 3 and 6 tokens per thread
+def test_prefill_selection_forms_between_the_powers_of_two(Hg, Wg):
+    from paper_2411_10803_amd import harness
+    cfg = wl.tiny(wl.CONFIGS[2], B=2, T=1, Hg=Hg, Wg=Wg, N=20, H=2, d=64, C=64)
+    Mv = cfg.M
+    t = wl.prefill_inputs(cfg)
+    is_key = wl.random_key_mask(cfg, 40)
+    rng = np.random.default_rng(11)
+    vis = (rng.random((cfg.B, Mv)) > 0.15).astype(np.uint8)
+    scale, gamma, alpha = 1 / 8.0, 1.0 / Mv, 2.0 / cfg.L
+    R = 400
+    g = harness.prefill_on_gpu(t, Mv, vis, None, is_key, scale, FILTER_BUDGET, R, gamma, alpha, R)
+    o = oracle.prefill_filter(t["q_txt"], t["k"], t["v"], t["hidden"], vis, None, is_key, Mv, scale,
+                              FILTER_BUDGET, R, gamma, alpha, R)
+    check_prefill(g, o, t, Mv, vis, is_key, FILTER_BUDGET, R, gamma, alpha, R)
+    assert np.all(g["kept_count"] == R)
+
+
+@pytest.mark.parametrize("L0", [2500, 5600])                     # streaming kernels with 3 and 6 entries per thread
+def test_decode_selection_forms_between_the_powers_of_two(L0):
+    test_decode_general_kernels(4, 128, L0)
