@@ -308,7 +308,7 @@ def frac(nbytes, us):
     return round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us > 0 else None
 
 
-def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceiling=False, step_only=False):
+def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceiling=False, step_only=False, in_flight=True):
     """One prefill workload: the chained step, its stages, its kernels and the with-LSE variant, each call on the
     next of several sets of buffers (see Rotation), and the step on one set of buffers for comparison."""
     pipe = Pipeline(cfg, torch, md, harness)
@@ -421,7 +421,7 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
         block["stage_times"] = "sums of the stage's kernel durations (--step-only)"
     else:
         block["same_buffers"] = same
-        if cfg.B > 1:
+        if cfg.B > 1 and in_flight:
             block["batches_in_flight"] = [batches_in_flight(torch, pipe, 2 * steps, n) for n in (2, 4)]
             torch.cuda.empty_cache()
         block["prefill_with_lse"] = {"us": round(lse_ms * 1e3, 2), "score_us": round(lse_score_us, 2),
@@ -432,7 +432,39 @@ def measure_workload(torch, md, binding, harness, cfg, steps, warmup, with_ceili
     return pipe, block, step_ms
 
 
-def decode_loop_cfg5(torch, md, binding, harness, steps):
+def two_decode_loops(torch, md, cfg, steps, state, qs, kn, vn, scale):
+    """Two independent decode loops in flight (two streams, each with its own caches, state and workspace): one
+    loop's selection, move and append kernels run beside the other's read of its K cache.  The second stream
+    starts half a step late (a device copy ahead of its first step), or the two would stay in step."""
+    lanes = [state, tuple(x.clone() for x in state)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    pad = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
+    pad2 = torch.empty_like(pad)
+
+    def run(count):
+        s = steps - 1
+        for i in range(count):
+            k_, v_, a_, i_, p_, l_, w_ = lanes[i % 2]
+            with torch.cuda.stream(streams[i % 2]):
+                if i == 1:
+                    pad2.copy_(pad)
+                md.mustdrop_decode_append(kn[s], vn[s], k_, v_, a_, i_, p_, l_, cfg.L0 + steps, 1)
+                md.mustdrop_decode_evict(qs[s], k_, v_, a_, i_, p_, l_, scale, 1.0, cfg.decode_budget, workspace=w_)
+
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    run(8)
+    runs = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        run(128)
+        torch.cuda.synchronize()
+        runs.append((time.perf_counter() - t1) * 1e6 / 128)
+    return {"streams": 2, "us_per_step": round(sorted(runs)[1], 2), "us_per_step_runs": [round(r, 2) for r in runs]}
+
+
+def decode_loop_cfg5(torch, md, binding, harness, steps, in_flight=True):
     """Decode-stage workload proper: batch 64, 4096-entry cache, 256 steps, budget 1024."""
     cfg = wl.CONFIGS[5]
     steps = min(steps, cfg.steps)
@@ -478,37 +510,10 @@ def decode_loop_cfg5(torch, md, binding, harness, steps):
         md.mustdrop_decode_append(kn[s], vn[s], kc, vc, acc, ids, protect, length, cfg.L0 + steps, 1)
         md.mustdrop_decode_evict(qs[s], kc, vc, acc, ids, protect, length, scale, 1.0, cfg.decode_budget, workspace=ws)
     steady_ms = timed(torch, steady, 64)
-    # two independent decode loops in flight (two streams, each with its own caches, state and workspace): one
-    # loop's selection, move and append kernels run beside the other's read of its K cache.  The second stream
-    # starts half a step late (a device copy ahead of its first step), or the two would stay in step.
-    lanes = [(kc, vc, acc, ids, protect, length, ws),
-             tuple(x.clone() for x in (kc, vc, acc, ids, protect, length, ws))]
-    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    pad = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
-    pad2 = torch.empty_like(pad)
-
-    def run(count):
-        s = steps - 1
-        for i in range(count):
-            k_, v_, a_, i_, p_, l_, w_ = lanes[i % 2]
-            with torch.cuda.stream(streams[i % 2]):
-                if i == 1:
-                    pad2.copy_(pad)
-                md.mustdrop_decode_append(kn[s], vn[s], k_, v_, a_, i_, p_, l_, cfg.L0 + steps, 1)
-                md.mustdrop_decode_evict(qs[s], k_, v_, a_, i_, p_, l_, scale, 1.0, cfg.decode_budget, workspace=w_)
-
-    for st in streams:
-        st.wait_stream(torch.cuda.current_stream())
-    run(8)
-    runs = []
-    for _ in range(3):
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        run(128)
-        torch.cuda.synchronize()
-        runs.append((time.perf_counter() - t1) * 1e6 / 128)
-    two_us = sorted(runs)[1]
-    del lanes, pad, pad2
+    two = None
+    if in_flight:
+        two = two_decode_loops(torch, md, cfg, steps, (kc, vc, acc, ids, protect, length, ws), qs, kn, vn, scale)
+        two["frac_of_hbm_peak"] = frac(B * (cfg.decode_budget + 1) * H * d * 2 + 2 * B * 2 * H * d * 2, two["us_per_step"])
     entries = B * cfg.L0 + (steps - 1) * B * (cfg.decode_budget + 1)
     steady_bytes = B * (cfg.decode_budget + 1) * H * d * 2 + 2 * B * 2 * H * d * 2
     k_us = {n: round(r["ms"] * 1e3 / max(r["calls"], 1), 2) for n, r in prof.items()}
@@ -525,8 +530,7 @@ def decode_loop_cfg5(torch, md, binding, harness, steps):
         "first_step_frac_of_hbm_peak": round(B * cfg.L0 * H * d * 2 / (first_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "steady_us_per_step": round(steady_ms * 1e3, 2), "steady_algorithmic_MB": round(steady_bytes / 1e6, 2),
         "steady_frac_of_hbm_peak": frac(steady_bytes, steady_ms * 1e3), "kernels_us": k_us, "roofline": roof,
-        "two_loops_in_flight": {"streams": 2, "us_per_step": round(two_us, 2), "us_per_step_runs": [round(r, 2) for r in runs],
-                                "frac_of_hbm_peak": frac(steady_bytes, two_us)},
+        "two_loops_in_flight": two,
     }
 
 
@@ -752,6 +756,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the chained-prefill, hand-off and threshold extras")
+    ap.add_argument("--no-in-flight", action="store_true",
+                    help="skip the measurements with several batches (or decode loops) in flight on several streams (for "
+                         "profiler runs: overlapping kernels lengthen each other's durations in a trace)")
     ap.add_argument("--step-only", action="store_true",
                     help="run nothing but the chained step of the headline workload (for profiler runs: every launch "
                          "the profiler sees belongs to the timed configuration)")
@@ -785,7 +792,8 @@ def main():
     # the headline first: its K timed steps after W warm-up steps are the figures of the contract
     cfg = wl.CONFIGS[HEADLINE]
     pipe, head, ms_per_step = measure_workload(torch, md, binding, harness, cfg, args.steps, args.warmup,
-                                               with_ceiling=not args.step_only, step_only=args.step_only)
+                                               with_ceiling=not args.step_only, step_only=args.step_only,
+                                               in_flight=not args.no_in_flight)
     blocks = {cfg.name: head}
     result = {
         "metric": "vision tokens processed/sec per pipeline stage; achieved % of HBM/MFMA roofline",
@@ -815,11 +823,12 @@ def main():
         if n == HEADLINE:
             continue
         if n == 5:
-            blocks[wl.CONFIGS[5].name] = decode_loop_cfg5(torch, md, binding, harness, args.decode_steps)
+            blocks[wl.CONFIGS[5].name] = decode_loop_cfg5(torch, md, binding, harness, args.decode_steps,
+                                                            in_flight=not args.no_in_flight)
             torch.cuda.empty_cache()
             continue
         c = wl.CONFIGS[n]
-        p2, blk, _ = measure_workload(torch, md, binding, harness, c, steps_other, args.warmup)
+        p2, blk, _ = measure_workload(torch, md, binding, harness, c, steps_other, args.warmup, in_flight=not args.no_in_flight)
         if not args.no_extras and n == 2:                # the extras that are defined on the batch-16 LLaVA-1.5 shape
             blk["progressive_prefill"] = progressive_prefill(torch, md, harness, c, p2)
             blk["variable_length"] = variable_length(torch, md, c, p2)
